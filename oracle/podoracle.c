@@ -1,0 +1,417 @@
+/*
+ * podoracle.c -- plain, slow CPU statement of what the pod rollout computes.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Nothing in the product path may call, link or
+ * import this file; it exists so that tests, the smoke check and the bench's
+ * CPU-baseline leg have an independent result to compare the HIP kernels with.
+ * It shares no code, header, table or helper with the HIP sources.
+ *
+ * What it follows.  The paper states the computation only in words: a worker
+ * produces batches of transitions from an actor acting in a batched
+ * environment of independent sub-environments (Sec. 4.2 "Worker"), the data are
+ * tensors in contiguous GPU memory (Sec. 4.3 "Cloud-oriented optimizations"),
+ * and the stock-trading task has state {balance, shares, close prices,
+ * technical indicators}, actions {buy, sell, hold} and reward "change of
+ * account value" (Table 1, Sec. 5.3; initial capital 1e6 and a proportional
+ * transaction cost in the caption of Fig. 6).  All experiments use PPO
+ * (Sec. 5.2), which implies a Gaussian policy and generalised advantage
+ * estimation.  Every concrete rule below (trade order, truncation, execution
+ * and valuation price, reset, GAE termination handling) is a reading of those
+ * passages; the readings are listed in the design notes of the repository.
+ *
+ * Arithmetic.  Decisions that produce integers (share counts, cursors) are
+ * taken in IEEE binary32 with one rounding per operation in a fixed order, so
+ * another implementation can reproduce them bit for bit.  Everything that is a
+ * real-valued result (network outputs, asset value, reward, log-probability,
+ * GAE, leaderboard moments) is evaluated in binary64.
+ *
+ * Pins (tests/test_oracle_*.py): zero-action and forced-liquidation closed
+ * forms, self-financing identity, cash/holdings non-negativity, order-of-trade
+ * cases, exact-rational brute force on a 1-env 2-stock 3-step grid; numpy
+ * matmul + tanh for the MLP; library bf16 rounding and hand-built ties for
+ * the bf16 emulation; closed forms and the O(T^2) direct sum for GAE; numpy
+ * mean/var/stable argsort for the leaderboard.  The whole free-running rollout
+ * has no printed trajectory in the paper to compare with: parity unpinned for
+ * the composition, pinned stage by stage.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* Constants of the trading task (Table 1 / Fig. 6 caption) and of the
+ * observation scaling.  Plain data, filled by the caller. */
+typedef struct orc_cfg {
+  int32_t n_stocks;     /* D */
+  int32_t n_ind;        /* K indicators per stock */
+  int32_t horizon;      /* H: an episode ends when the cursor reaches H */
+  float cash0;          /* initial capital */
+  float hmax;           /* largest trade per stock and step, in shares */
+  float cost;           /* proportional transaction cost c */
+  float sigma;          /* fixed standard deviation of the Gaussian policy */
+  float reward_scale;   /* rho */
+  float obs_scale[4];   /* cash, price, holdings, indicator */
+} orc_cfg;
+
+/* flag bits reported per (t, env, stock) */
+#define ORC_FLAG_TRUNC 1u /* a*hmax within a few ulp of an integer */
+#define ORC_FLAG_FLOOR 2u /* cash/u within a few ulp of an integer */
+#define ORC_FLAG_GUARD 4u /* the q -= 1 guard of the buy rule fired */
+
+static int state_dim(const orc_cfg *c) { return 1 + 2 * c->n_stocks + c->n_stocks * c->n_ind; }
+
+/* ------------------------------------------------------------------ bf16 -- */
+
+/* Round a binary32 value to the nearest bfloat16 (8 significand bits), ties
+ * to even, returned as binary32.  NaN stays NaN. */
+float orc_bf16_round(float x) {
+  uint32_t u;
+  memcpy(&u, &x, 4);
+  if ((u & 0x7f800000u) == 0x7f800000u && (u & 0x007fffffu)) {
+    u |= 0x00400000u; /* quiet NaN, keep sign */
+    u &= 0xffff0000u;
+  } else {
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7fffu + lsb;
+    u &= 0xffff0000u;
+  }
+  memcpy(&x, &u, 4);
+  return x;
+}
+
+void orc_bf16_round_array(const float *in, float *out, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) out[i] = orc_bf16_round(in[i]);
+}
+
+/* ------------------------------------------------------------------- MLP -- */
+
+/* One affine layer for one row: out[j] = b[j] + sum_i in[i] * W[i][j], inputs
+ * taken in ascending order of i, accumulated in binary64. */
+static void affine(int n_in, int n_out, const double *in, const float *W, const float *b, double *out) {
+  for (int j = 0; j < n_out; ++j) out[j] = 0.0;
+  for (int i = 0; i < n_in; ++i) {
+    const double xi = in[i];
+    const float *w = W + (int64_t)i * n_out;
+    for (int j = 0; j < n_out; ++j) out[j] += xi * (double)w[j];
+  }
+  for (int j = 0; j < n_out; ++j) out[j] += (double)b[j];
+}
+
+/* Three-layer perceptron on `rows` input rows (actor: tanh on the output too;
+ * critic: linear scalar output).  X is [rows, ldx] with the first S entries of
+ * each row used; W1 [S,Hd], W2 [Hd,Hd], W3 [Hd,O] row-major, biases [out].
+ * bf16 != 0: inputs and hidden activations are rounded to bfloat16 before each
+ * layer; the weights passed in must then already be bfloat16-valued (see
+ * orc_bf16_round_array) -- products of two bfloat16 values are exact in
+ * binary64, so the result is the true value of the rounded-operand network.
+ * out is [rows, O] in binary64. */
+void orc_mlp(int64_t rows, int S, int Hd, int O, const float *X, int64_t ldx, const float *W1, const float *b1,
+             const float *W2, const float *b2, const float *W3, const float *b3, int out_tanh, int bf16, double *out) {
+  int widest = S > Hd ? S : Hd;
+  double *a = (double *)malloc(sizeof(double) * (size_t)widest);
+  double *z = (double *)malloc(sizeof(double) * (size_t)(Hd > O ? Hd : O));
+  for (int64_t r = 0; r < rows; ++r) {
+    const float *x = X + r * ldx;
+    for (int i = 0; i < S; ++i) a[i] = bf16 ? (double)orc_bf16_round(x[i]) : (double)x[i];
+    affine(S, Hd, a, W1, b1, z);
+    for (int j = 0; j < Hd; ++j) {
+      double h = tanh(z[j]);
+      a[j] = bf16 ? (double)orc_bf16_round((float)h) : h;
+    }
+    affine(Hd, Hd, a, W2, b2, z);
+    for (int j = 0; j < Hd; ++j) {
+      double h = tanh(z[j]);
+      a[j] = bf16 ? (double)orc_bf16_round((float)h) : h;
+    }
+    affine(Hd, O, a, W3, b3, z);
+    for (int j = 0; j < O; ++j) out[r * O + j] = out_tanh ? tanh(z[j]) : z[j];
+  }
+  free(a);
+  free(z);
+}
+
+/* ----------------------------------------------------------- environment -- */
+
+/* Observation of one env (Table 1 state space): [cash, prices, holdings,
+ * indicators (stock-major)], each block scaled by its power-of-two factor. */
+void orc_observe(const orc_cfg *c, float cash, const int32_t *h, const float *p, const float *ind, float *obs) {
+  const int D = c->n_stocks, K = c->n_ind;
+  obs[0] = cash * c->obs_scale[0];
+  for (int d = 0; d < D; ++d) obs[1 + d] = p[d] * c->obs_scale[1];
+  for (int d = 0; d < D; ++d) obs[1 + D + d] = (float)h[d] * c->obs_scale[2];
+  for (int i = 0; i < D * K; ++i) obs[1 + 2 * D + i] = ind[i] * c->obs_scale[3];
+}
+
+/* Gaussian policy sample with externally drawn standard-normal noise:
+ * a_raw = mu + sigma * eps (two binary32 roundings), and the log-density of
+ * a_raw under N(mu, sigma^2 I), which depends on eps only. */
+void orc_sample(int D, float sigma, const float *mu, const float *eps, float *a_raw, double *logp) {
+  const double half_log_2pi = 0.91893853320467274178;
+  double lp = 0.0;
+  for (int d = 0; d < D; ++d) {
+    volatile float se = sigma * eps[d];
+    volatile float a = mu[d] + se;
+    a_raw[d] = a;
+    lp += -0.5 * (double)eps[d] * (double)eps[d] - log((double)sigma) - half_log_2pi;
+  }
+  *logp = lp;
+}
+
+/* x lies within a few binary32 ulp of an integer without being one. */
+static int near_integer(double x) {
+  double ax = fabs(x);
+  double tol = 8.0 * ldexp(1.0, -24) * (ax > 1.0 ? ax : 1.0);
+  double gap = fabs(x - nearbyint(x));
+  return gap != 0.0 && gap <= tol;
+}
+
+/* Trade execution of one env at prices p (buy / sell / hold of Table 1):
+ * wanted shares k_d = trunc(clamp(a_d) * hmax); first every sale in ascending
+ * stock order (limited by the holding), then every purchase in ascending stock
+ * order (limited by the cash left, cost included).  binary32 throughout, one
+ * rounding per operation.  shares[d] receives the signed executed quantity,
+ * flags[d] (optional) the ORC_FLAG_* bits. */
+void orc_trade(const orc_cfg *c, float *cash_io, int32_t *h, const float *a_raw, const float *p, int32_t *shares,
+               uint8_t *flags) {
+  const int D = c->n_stocks;
+  volatile float cash = *cash_io;
+  volatile float one_minus_c = 1.0f - c->cost;
+  volatile float one_plus_c = 1.0f + c->cost;
+  int32_t *k = (int32_t *)malloc(sizeof(int32_t) * (size_t)D);
+  for (int d = 0; d < D; ++d) {
+    float a = a_raw[d];
+    a = a < -1.0f ? -1.0f : a;
+    a = a > 1.0f ? 1.0f : a;
+    volatile float x = a * c->hmax;
+    k[d] = (int32_t)truncf(x);
+    shares[d] = 0;
+    if (flags) flags[d] = near_integer((double)a * (double)c->hmax) ? ORC_FLAG_TRUNC : 0;
+  }
+  for (int d = 0; d < D; ++d) {
+    if (k[d] >= 0) continue;
+    int32_t q = -k[d] < h[d] ? -k[d] : h[d];
+    h[d] -= q;
+    volatile float gross = p[d] * (float)q;
+    volatile float net = gross * one_minus_c;
+    cash = cash + net;
+    shares[d] = -q;
+  }
+  for (int d = 0; d < D; ++d) {
+    if (k[d] <= 0) continue;
+    volatile float u = p[d] * one_plus_c;
+    volatile float ratio = cash / u;
+    int32_t m = (int32_t)floorf(ratio);
+    if (m < 0) m = 0;
+    int32_t q = k[d] < m ? k[d] : m;
+    volatile float outlay = (float)q * u;
+    if (flags && near_integer((double)cash / (double)u) && m <= k[d] + 1) flags[d] |= ORC_FLAG_FLOOR;
+    if (outlay > cash) {
+      q -= 1;
+      outlay = (float)q * u;
+      if (flags) flags[d] |= ORC_FLAG_GUARD;
+    }
+    h[d] += q;
+    cash = cash - outlay;
+    shares[d] = q;
+  }
+  free(k);
+  *cash_io = cash;
+}
+
+/* Account value in binary64: cash + sum_d h_d * p_d. */
+double orc_asset(int D, float cash, const int32_t *h, const float *p) {
+  double v = (double)cash;
+  for (int d = 0; d < D; ++d) v += (double)h[d] * (double)p[d];
+  return v;
+}
+
+/* Per-env persistent state.  Arrays of length N (h: [N, D]). */
+typedef struct orc_state {
+  float *cash;
+  int32_t *h;
+  int32_t *tau;
+  double *asset;
+  double *ep_ret, *ep_sum, *ep_sqsum;
+  int32_t *ep_cnt;
+} orc_state;
+
+void orc_reset_state(const orc_cfg *c, int64_t N, orc_state *s) {
+  for (int64_t n = 0; n < N; ++n) {
+    s->cash[n] = c->cash0;
+    s->tau[n] = 0;
+    s->asset[n] = (double)c->cash0;
+    s->ep_ret[n] = s->ep_sum[n] = s->ep_sqsum[n] = 0.0;
+    s->ep_cnt[n] = 0;
+    for (int d = 0; d < c->n_stocks; ++d) s->h[n * c->n_stocks + d] = 0;
+  }
+}
+
+/* One transition of env n given its raw action: trade at the prices of the
+ * current cursor, advance the cursor, value the portfolio at the new prices,
+ * reward = rho * (change of account value) (Table 1), episode end when the
+ * cursor reaches H, then bookkeeping of the finished episode's return and
+ * reset to the initial capital with no shares.  p_now / p_next are the market
+ * rows at the cursor before / after the advance.  Returns the reward. */
+double orc_env_step(const orc_cfg *c, int64_t n, orc_state *s, const float *a_raw, const float *p_now,
+                    const float *p_next, int32_t *shares, uint8_t *flags, uint8_t *done_out) {
+  const int D = c->n_stocks;
+  int32_t *h = s->h + n * D;
+  orc_trade(c, &s->cash[n], h, a_raw, p_now, shares, flags);
+  s->tau[n] += 1;
+  double asset_new = orc_asset(D, s->cash[n], h, p_next);
+  double r = (asset_new - s->asset[n]) * (double)c->reward_scale;
+  s->asset[n] = asset_new;
+  s->ep_ret[n] += r;
+  uint8_t done = (uint8_t)(s->tau[n] == c->horizon);
+  if (done) {
+    s->ep_sum[n] += s->ep_ret[n];
+    s->ep_sqsum[n] += s->ep_ret[n] * s->ep_ret[n];
+    s->ep_cnt[n] += 1;
+    s->ep_ret[n] = 0.0;
+    s->cash[n] = c->cash0;
+    for (int d = 0; d < D; ++d) h[d] = 0;
+    s->tau[n] = 0;
+    s->asset[n] = (double)c->cash0;
+  }
+  *done_out = done;
+  return r;
+}
+
+/* The worker's rollout (Sec. 4.2): N independent sub-environments, T steps.
+ *
+ *   market:  price [H+1, M, D], ind [H+1, M, D*K]; env n reads path market_of[n]
+ *   nets:    per-agent weights, agent_of[n] selects the agent of env n;
+ *            layouts as in orc_mlp with a leading agent axis; critic pointers
+ *            may be NULL (then value is not written)
+ *   noise:   [T, N, D] standard normal
+ *   mu_forced: NULL, or [T, N, D] policy means to use instead of the actor
+ *   outputs (any may be NULL): obs [T+1,N,S] f32, mu [T,N,D] f64, act_raw
+ *            [T,N,D] f32, logp [T,N] f64, reward [T,N] f64, done [T,N] u8,
+ *            value [T+1,N] f64, shares [T,N,D] i32, flags [T,N,D] u8
+ * State is read and updated in place, so consecutive calls continue episodes. */
+int orc_rollout(const orc_cfg *c, int64_t N, int M, int Hd, int bf16, int T, const int32_t *agent_of,
+                const int32_t *market_of, const float *price, const float *ind, const float *const *actor,
+                const float *const *critic, const float *noise, const float *mu_forced, orc_state *s, float *obs_out,
+                double *mu_out, float *act_out, double *logp_out, double *reward_out, uint8_t *done_out,
+                double *value_out, int32_t *shares_out, uint8_t *flags_out) {
+  const int D = c->n_stocks, K = c->n_ind, S = state_dim(c);
+  const int64_t w1 = (int64_t)S * Hd, w2 = (int64_t)Hd * Hd, w3a = (int64_t)Hd * D, w3c = Hd;
+  float *obs = (float *)malloc(sizeof(float) * (size_t)S);
+  float *mu32 = (float *)malloc(sizeof(float) * (size_t)D);
+  float *a_raw = (float *)malloc(sizeof(float) * (size_t)D);
+  double *mu = (double *)malloc(sizeof(double) * (size_t)D);
+  int32_t *shares = (int32_t *)malloc(sizeof(int32_t) * (size_t)D);
+  uint8_t *flags = (uint8_t *)malloc((size_t)D);
+  if (!obs || !mu32 || !a_raw || !mu || !shares || !flags) return -1;
+  for (int64_t n = 0; n < N; ++n) {
+    const int g = agent_of[n];
+    const int64_t m = market_of[n];
+    for (int t = 0; t <= T; ++t) {
+      const int32_t tau = s->tau[n];
+      const float *p_now = price + ((int64_t)tau * M + m) * D;
+      const float *i_now = ind + ((int64_t)tau * M + m) * D * K;
+      orc_observe(c, s->cash[n], s->h + n * D, p_now, i_now, obs);
+      if (obs_out) memcpy(obs_out + ((int64_t)t * N + n) * S, obs, sizeof(float) * (size_t)S);
+      if (critic && value_out) {
+        double v;
+        orc_mlp(1, S, Hd, 1, obs, S, critic[0] + g * w1, critic[1] + (int64_t)g * Hd, critic[2] + g * w2,
+                critic[3] + (int64_t)g * Hd, critic[4] + g * w3c, critic[5] + g, 0, bf16, &v);
+        value_out[(int64_t)t * N + n] = v;
+      }
+      if (t == T) break;
+      const int64_t tn = (int64_t)t * N + n;
+      if (mu_forced) {
+        for (int d = 0; d < D; ++d) mu[d] = (double)mu_forced[tn * D + d];
+      } else {
+        orc_mlp(1, S, Hd, D, obs, S, actor[0] + g * w1, actor[1] + (int64_t)g * Hd, actor[2] + g * w2,
+                actor[3] + (int64_t)g * Hd, actor[4] + g * w3a, actor[5] + (int64_t)g * D, 1, bf16, mu);
+      }
+      for (int d = 0; d < D; ++d) mu32[d] = (float)mu[d];
+      double lp;
+      orc_sample(D, c->sigma, mu32, noise + tn * D, a_raw, &lp);
+      const float *p_next = price + ((int64_t)(tau + 1) * M + m) * D;
+      uint8_t done;
+      double r = orc_env_step(c, n, s, a_raw, p_now, p_next, shares, flags, &done);
+      if (mu_out) memcpy(mu_out + tn * D, mu, sizeof(double) * (size_t)D);
+      if (act_out) memcpy(act_out + tn * D, a_raw, sizeof(float) * (size_t)D);
+      if (logp_out) logp_out[tn] = lp;
+      if (reward_out) reward_out[tn] = r;
+      if (done_out) done_out[tn] = done;
+      if (shares_out) memcpy(shares_out + tn * D, shares, sizeof(int32_t) * (size_t)D);
+      if (flags_out) memcpy(flags_out + tn * D, flags, (size_t)D);
+    }
+  }
+  free(obs);
+  free(mu32);
+  free(a_raw);
+  free(mu);
+  free(shares);
+  free(flags);
+  return 0;
+}
+
+/* ------------------------------------------------------------------- GAE -- */
+
+/* Generalised advantage estimation per env, backwards in time (implied by the
+ * use of PPO, Sec. 5.2): with nd_t = 1 - done_t,
+ *   delta_t = r_t + gamma nd_t V_{t+1} - V_t,
+ *   A_t = delta_t + gamma lambda nd_t A_{t+1},  A_T = 0,   R_t = A_t + V_t.
+ * An episode end is a termination: nothing is bootstrapped through it.
+ * reward [T,N], value [T+1,N], done [T,N]; adv, ret [T,N]. */
+void orc_gae(int T, int64_t N, const double *reward, const double *value, const uint8_t *done, double gamma,
+             double lambda, double *adv, double *ret) {
+  for (int64_t n = 0; n < N; ++n) {
+    double a_next = 0.0;
+    for (int t = T - 1; t >= 0; --t) {
+      const int64_t i = (int64_t)t * N + n;
+      const double nd = 1.0 - (double)(done[i] != 0);
+      const double delta = reward[i] + gamma * nd * value[i + N] - value[i];
+      const double a = delta + gamma * lambda * nd * a_next;
+      adv[i] = a;
+      ret[i] = a + value[i];
+      a_next = a;
+    }
+  }
+}
+
+/* ----------------------------------------------------------- leaderboard -- */
+
+/* Score of each agent = mean (and population variance) of the returns of the
+ * episodes its envs completed (Sec. 4.1 leaderboard; Sec. 4.2 evaluator: mean
+ * and variance of the episodic reward).  Agents with no finished episode score
+ * -inf with variance 0.  rank[i] = id of the agent in place i, best first,
+ * equal means ordered by lower agent id.  Env n belongs to agent_of[n]. */
+void orc_leaderboard(int P, int64_t N, const int32_t *agent_of, const double *ep_sum, const double *ep_sqsum,
+                     const int32_t *ep_cnt, double *mean, double *var, int32_t *rank) {
+  double *s1 = (double *)calloc((size_t)P, sizeof(double));
+  double *s2 = (double *)calloc((size_t)P, sizeof(double));
+  int64_t *cnt = (int64_t *)calloc((size_t)P, sizeof(int64_t));
+  for (int64_t n = 0; n < N; ++n) {
+    s1[agent_of[n]] += ep_sum[n];
+    s2[agent_of[n]] += ep_sqsum[n];
+    cnt[agent_of[n]] += ep_cnt[n];
+  }
+  for (int g = 0; g < P; ++g) {
+    if (cnt[g] > 0) {
+      mean[g] = s1[g] / (double)cnt[g];
+      var[g] = s2[g] / (double)cnt[g] - mean[g] * mean[g];
+    } else {
+      mean[g] = -INFINITY;
+      var[g] = 0.0;
+    }
+    rank[g] = g;
+  }
+  /* stable insertion sort, descending mean */
+  for (int i = 1; i < P; ++i) {
+    int32_t id = rank[i];
+    int j = i - 1;
+    while (j >= 0 && mean[rank[j]] < mean[id]) {
+      rank[j + 1] = rank[j];
+      --j;
+    }
+    rank[j + 1] = id;
+  }
+  free(s1);
+  free(s2);
+  free(cnt);
+}

@@ -1,0 +1,341 @@
+"""Pins of the CPU checker's trading environment (CPU only).
+
+The paper prints no worked trajectory for the stock-trading task (Table 1 gives
+state / action / reward in words; Fig. 6 caption gives capital and cost), so
+the checker is pinned by closed forms, invariants, order-of-trade cases and an
+exact-rational brute force written independently in this file.
+"""
+import itertools
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2112_05923_amd import inputs
+
+
+def cfg2(D=2, K=1, H=8, **kw):
+    return oracle.make_cfg(D, K, H, **kw)
+
+
+# ---------------------------------------------------------------- closed forms
+
+
+def test_zero_action_holds_everything():
+    cfg = cfg2(D=3)
+    h0 = np.array([5, 0, 17], dtype=np.int32)
+    p = np.array([10.5, 20.25, 99.0], dtype=np.float32)
+    cash, h, shares, _ = oracle.trade(cfg, 1234.5, h0, np.zeros(3, np.float32), p)
+    assert cash == np.float32(1234.5) and (h == h0).all() and (shares == 0).all()
+    # |a| * hmax < 1 truncates to zero shares as well (toward zero on both sides)
+    cash, h, shares, _ = oracle.trade(cfg, 1234.5, h0, np.array([0.0099, -0.0099, 0.0], np.float32), p)
+    assert cash == np.float32(1234.5) and (h == h0).all() and (shares == 0).all()
+
+
+def test_zero_action_reward_is_price_change_of_holdings():
+    D, H = 3, 4
+    cfg = cfg2(D=D, K=1, H=H, reward_scale=0.25)
+    st = oracle.State(cfg, 1)
+    st.cash[0] = 100.0
+    st.h[0] = [2, 3, 4]
+    p0 = np.array([10.0, 20.0, 30.0], np.float32)
+    p1 = np.array([11.0, 19.0, 30.5], np.float32)
+    st.asset[0] = oracle.asset(100.0, st.h[0], p0)
+    r, done, shares, _ = oracle.env_step(cfg, st, 0, np.zeros(D, np.float32), p0, p1)
+    assert r == 0.25 * (2 * 1.0 + 3 * -1.0 + 4 * 0.5)
+    assert done == 0 and st.tau[0] == 1 and (shares == 0).all()
+
+
+def test_truncation_toward_zero_both_signs():
+    cfg = cfg2(D=2, hmax=100.0, cost=0.0)
+    p = np.array([1.0, 1.0], np.float32)
+    _, h, shares, _ = oracle.trade(cfg, 1e6, [50, 50], np.array([0.129, -0.129], np.float32), p)
+    assert shares.tolist() == [12, -12] and h.tolist() == [62, 38]
+    # clamp: |a| > 1 trades exactly hmax
+    _, h, shares, _ = oracle.trade(cfg, 1e6, [500, 500], np.array([3.7, -9.0], np.float32), p)
+    assert shares.tolist() == [100, -100]
+
+
+def test_full_liquidation_closed_form():
+    c = 2.0 ** -9
+    cfg = cfg2(D=2, cost=c)
+    p = np.array([16.0, 40.0], np.float32)
+    cash, h, shares, _ = oracle.trade(cfg, 10.0, [70, 100], np.array([-1.0, -1.0], np.float32), p)
+    assert h.tolist() == [0, 0] and shares.tolist() == [-70, -100]
+    assert float(cash) == 10.0 + (16.0 * 70 + 40.0 * 100) * (1 - c)  # all terms exact in binary32
+
+
+def test_sale_limited_by_holding():
+    cfg = cfg2(D=1, K=1)
+    cash, h, shares, _ = oracle.trade(cfg, 0.0, [7], np.array([-0.5], np.float32), np.array([2.0], np.float32))
+    assert shares.tolist() == [-7] and h.tolist() == [0]
+
+
+def test_cash_starved_buy_is_floor_of_affordable():
+    c = 2.0 ** -10
+    cfg = cfg2(D=1, K=1, cost=c)
+    p = np.array([33.0], np.float32)
+    for cash0 in [0.0, 32.0, 33.0, 33.04, 500.0, 3303.0, 3304.0]:
+        cash, h, shares, _ = oracle.trade(cfg, cash0, [0], np.array([1.0], np.float32), p)
+        want = min(100, int(Fraction(cash0) // (Fraction(33) * (1 + Fraction(1, 1024)))))
+        assert shares.tolist() == [want], cash0
+        assert float(cash) >= 0.0
+        assert Fraction(float(cash)) == Fraction(float(np.float32(cash0))) - want * Fraction(33) * (1 + Fraction(1, 1024))
+
+
+def test_sells_fund_buys_in_same_step():
+    # cash 0: buying stock 0 is only possible with the proceeds of selling stock 1,
+    # which has the HIGHER index: fails if purchases run before sales, or if the
+    # two passes are merged into one ascending sweep.
+    cfg = cfg2(D=2, cost=0.0)
+    p = np.array([10.0, 10.0], np.float32)
+    cash, h, shares, _ = oracle.trade(cfg, 0.0, [0, 40], np.array([0.3, -0.4], np.float32), p)
+    assert shares.tolist() == [30, -40] and h.tolist() == [30, 0] and float(cash) == 100.0
+
+
+def test_buy_priority_is_ascending_stock_index():
+    cfg = cfg2(D=3, cost=0.0)
+    p = np.array([10.0, 10.0, 10.0], np.float32)
+    # 450 of cash, three wishes of 30 shares (300 each): stock 0 full, stock 1 gets the 15 left, stock 2 none
+    cash, h, shares, _ = oracle.trade(cfg, 450.0, [0, 0, 0], np.array([0.3, 0.3, 0.3], np.float32), p)
+    assert shares.tolist() == [30, 15, 0] and float(cash) == 0.0
+    # a larger wish at a higher index does not jump the queue
+    cash, h, shares, _ = oracle.trade(cfg, 450.0, [0, 0, 0], np.array([0.1, 0.2, 1.0], np.float32), p)
+    assert shares.tolist() == [10, 20, 15]
+
+
+def test_costs_apply_on_both_sides():
+    c = 2.0 ** -8
+    cfg = cfg2(D=2, cost=c)
+    p = np.array([8.0, 4.0], np.float32)
+    cash, h, shares, _ = oracle.trade(cfg, 1000.0, [10, 0], np.array([-0.1, 0.1], np.float32), p)
+    assert shares.tolist() == [-10, 10]
+    assert float(cash) == 1000.0 + 80.0 * (1 - c) - 40.0 * (1 + c)
+
+
+def test_execution_at_current_price_valuation_at_next():
+    cfg = cfg2(D=1, K=1, H=5, cost=0.0, reward_scale=1.0)
+    st = oracle.State(cfg, 1)
+    st.cash[0] = 100.0
+    st.asset[0] = 100.0
+    r, done, shares, _ = oracle.env_step(cfg, st, 0, np.array([0.05], np.float32), np.array([10.0], np.float32),
+                                         np.array([12.0], np.float32))
+    assert shares.tolist() == [5] and st.cash[0] == 50.0  # paid 5 * 10, not 5 * 12
+    assert r == 5 * 12.0 + 50.0 - 100.0
+
+
+# ------------------------------------------------------------------ invariants
+
+
+def _tiny_rollout(horizon=None, n_market=None, cost=None, cash0=None, steps=None, seed_shift=0):
+    w = inputs.WORKLOADS["tiny"]
+    if cost is not None:
+        w = w.replace(cost=cost)
+    if cash0 is not None:
+        w = w.replace(cash0=cash0)
+    H = w.steps if horizon is None else horizon
+    d = inputs.make_all(w, horizon=H, n_market=n_market, steps=steps)
+    cfg = oracle.cfg_from_workload(w, horizon=H)
+    T = w.steps if steps is None else steps
+    out, st = oracle.rollout(cfg, w.hidden, False, T, d["price"], d["ind"], d["noise"], actor=d["actor"],
+                             critic=d["critic"])
+    return w, cfg, d, out, st
+
+
+@pytest.mark.parametrize("cash0", [1.0e6, 3.0e3])
+def test_cash_and_holdings_never_negative_and_asset_identity(cash0):
+    w, cfg, d, out, st = _tiny_rollout(cash0=cash0, horizon=16)
+    D, K = w.n_stocks, w.n_ind
+    obs = out["obs"].astype(np.float64)
+    cash = obs[:, :, 0] / w.obs_scale[0]
+    price = obs[:, :, 1:1 + D] / w.obs_scale[1]
+    hold = obs[:, :, 1 + D:1 + 2 * D] / w.obs_scale[2]
+    assert (cash >= 0).all() and (hold >= 0).all()
+    assert (hold == np.round(hold)).all()
+    T = out["reward"].shape[0]
+    # holdings follow the recorded executed trades, reset on done
+    for t in range(T):
+        expect = hold[t] + out["shares"][t]
+        expect[out["done"][t] == 1] = 0
+        assert (hold[t + 1] == expect).all()
+    # reward == rho * change of (cash + holdings . price), recomputed from the record alone
+    H = cfg.horizon
+    for t in range(T):
+        tau = t % H
+        pn = d["price"][tau + 1].astype(np.float64)             # valuation prices [N, D]
+        pc = d["price"][tau].astype(np.float64)
+        assert np.array_equal(price[t], pc)
+        h_after = hold[t] + out["shares"][t]
+        # cash after trading is not in the record when the env resets; rebuild it from the trades
+        fee_free = (out["shares"][t] * pc)
+        cash_after = cash[t] - np.where(out["shares"][t] > 0, fee_free * (1 + w.cost), fee_free * (1 - w.cost)).sum(1)
+        a0 = cash[t] + (hold[t] * pc).sum(1)
+        a1 = cash_after + (h_after * pn).sum(1)
+        np.testing.assert_allclose(out["reward"][t], (a1 - a0) * w.reward_scale, rtol=0,
+                                   atol=16 * float(np.spacing(np.float32(cash0))) * w.reward_scale)
+        nd = out["done"][t] == 0
+        # binary32 cash: a few ulp at the size of the running balance
+        np.testing.assert_allclose(cash[t + 1][nd], cash_after[nd], rtol=1e-6, atol=16 * float(np.spacing(np.float32(cash0))))
+    if cash0 < 1e4:  # the cash-limited branch was really exercised
+        assert (out["flags"] & oracle.FLAG_FLOOR).any() or (np.abs(out["shares"]) < 100).any()
+        wanted = np.trunc(np.clip(out["act_raw"], -1, 1) * np.float32(w.hmax))
+        assert ((wanted > 0) & (out["shares"] < wanted)).any()
+
+
+def test_self_financing_no_cost_constant_prices_gives_zero_reward():
+    w = inputs.WORKLOADS["tiny"].replace(cost=0.0)
+    H = 16
+    d = inputs.make_all(w, horizon=H)
+    d["price"][:] = d["price"][0][None]          # constant prices
+    cfg = oracle.cfg_from_workload(w, horizon=H)
+    out, _ = oracle.rollout(cfg, w.hidden, False, w.steps, d["price"], d["ind"], d["noise"], actor=d["actor"])
+    assert np.abs(out["shares"]).sum() > 1000
+    # with c = 0 every trade swaps cash for shares of equal value; only binary32 rounding of cash is left
+    assert np.abs(out["reward"]).max() <= 0.25 * w.reward_scale
+
+
+def test_fees_are_the_only_loss_at_execution_prices():
+    c = 2.0 ** -7
+    cfg = cfg2(D=3, cost=c)
+    p = np.array([8.0, 4.0, 2.0], np.float32)
+    h0 = np.array([50, 10, 0], np.int32)
+    cash, h, shares, _ = oracle.trade(cfg, 512.0, h0, np.array([-0.25, 0.5, 1.0], np.float32), p)
+    before = 512.0 + float((h0 * p).sum())
+    after = float(cash) + float((h * p).sum())
+    assert before - after == c * float((np.abs(shares) * p).sum())
+
+
+def test_reset_schedule_and_reset_observation():
+    H = 16
+    w, cfg, d, out, st = _tiny_rollout(horizon=H)
+    T = out["reward"].shape[0]
+    want_done = np.array([(t + 1) % H == 0 for t in range(T)], dtype=np.uint8)
+    assert (out["done"] == want_done[:, None]).all()
+    for t in np.nonzero(want_done)[0]:
+        assert np.array_equal(out["obs"][t + 1], out["obs"][0])
+    assert (st.ep_cnt == T // H).all()
+    # episode sums: sum of rewards per episode
+    r = out["reward"].reshape(T // H, H, -1).sum(1)
+    np.testing.assert_allclose(st.ep_sum, r.sum(0), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(st.ep_sqsum, (r ** 2).sum(0), rtol=1e-12, atol=1e-12)
+
+
+def test_horizon_not_dividing_T_and_state_carries_across_calls():
+    w = inputs.WORKLOADS["tiny"]
+    H = 24
+    d = inputs.make_all(w, horizon=H)
+    cfg = oracle.cfg_from_workload(w, horizon=H)
+    full, st_full = oracle.rollout(cfg, w.hidden, False, 64, d["price"], d["ind"], d["noise"], actor=d["actor"])
+    a, st = oracle.rollout(cfg, w.hidden, False, 40, d["price"], d["ind"], d["noise"][:40], actor=d["actor"])
+    b, st = oracle.rollout(cfg, w.hidden, False, 24, d["price"], d["ind"], d["noise"][40:], actor=d["actor"], state=st)
+    for k in ("act_raw", "reward", "done", "shares"):
+        assert np.array_equal(np.concatenate([a[k], b[k]]), full[k]), k
+    assert np.array_equal(a["obs"][-1], b["obs"][0])
+    assert np.array_equal(st.cash, st_full.cash) and np.array_equal(st.h, st_full.h)
+    assert (full["done"].sum(0) == 2).all() and full["done"][23].all() and full["done"][47].all()
+
+
+def test_env_permutation_equivariance_and_shared_market():
+    w = inputs.WORKLOADS["tiny"]
+    d = inputs.make_all(w)
+    cfg = oracle.cfg_from_workload(w)
+    base, _ = oracle.rollout(cfg, w.hidden, False, w.steps, d["price"], d["ind"], d["noise"], actor=d["actor"])
+    perm = np.random.default_rng(0).permutation(w.n_envs)
+    out, _ = oracle.rollout(cfg, w.hidden, False, w.steps, d["price"][:, perm], d["ind"][:, perm],
+                            d["noise"][:, perm], actor=d["actor"])
+    for k in ("obs", "act_raw", "reward", "shares", "done"):
+        assert np.array_equal(out[k], base[k][:, perm]), k
+    # one shared path (M = 1) equals the same path replicated per env (M = N)
+    p1, i1 = d["price"][:, :1], d["ind"][:, :1]
+    shared, _ = oracle.rollout(cfg, w.hidden, False, w.steps, p1, i1, d["noise"], actor=d["actor"])
+    repl, _ = oracle.rollout(cfg, w.hidden, False, w.steps, np.repeat(p1, w.n_envs, 1), np.repeat(i1, w.n_envs, 1),
+                             d["noise"], actor=d["actor"])
+    for k in ("obs", "act_raw", "reward", "shares"):
+        assert np.array_equal(shared[k], repl[k]), k
+
+
+def test_forced_mean_equals_free_running_when_fed_its_own_means():
+    w, cfg, d, out, _ = _tiny_rollout()
+    forced, _ = oracle.rollout(cfg, w.hidden, False, w.steps, d["price"], d["ind"], d["noise"],
+                               mu_forced=out["mu"].astype(np.float32))
+    for k in ("obs", "act_raw", "reward", "shares", "done"):
+        assert np.array_equal(forced[k], out[k]), k
+
+
+def test_observation_layout():
+    cfg = oracle.make_cfg(2, 3, 4, obs_scale=(0.5, 0.25, 2.0, 4.0))
+    obs = oracle.observe(cfg, 8.0, [3, 5], [16.0, 32.0], [1, 2, 3, 4, 5, 6])
+    assert obs.tolist() == [4.0, 4.0, 8.0, 6.0, 10.0, 4.0, 8.0, 12.0, 16.0, 20.0, 24.0]
+
+
+# ----------------------------------------------------------------- brute force
+
+
+def _ledger(actions, prices, cash0, hmax, c, rho):
+    """Exact-rational bookkeeping of one env, written from the trading rules
+    alone: sales first, then purchases in stock order limited by the cash left."""
+    cash = Fraction(cash0)
+    h = [0, 0]
+    asset = Fraction(cash0)
+    shares_log, rewards = [], []
+    for t, a in enumerate(actions):
+        p = [Fraction(x) for x in prices[t]]
+        want = [int(Fraction(x) * hmax) for x in a]          # grid values make this exact; int() truncates toward 0
+        exe = [0, 0]
+        for d in range(2):
+            if want[d] < 0:
+                q = min(-want[d], h[d])
+                h[d] -= q
+                cash += p[d] * q * (1 - c)
+                exe[d] = -q
+        for d in range(2):
+            if want[d] > 0:
+                q = min(want[d], int(cash // (p[d] * (1 + c))))
+                h[d] += q
+                cash -= p[d] * q * (1 + c)
+                exe[d] = q
+        pn = [Fraction(x) for x in prices[t + 1]]
+        new_asset = cash + h[0] * pn[0] + h[1] * pn[1]
+        rewards.append((new_asset - asset) * rho)
+        asset = new_asset
+        shares_log.append(exe)
+        assert cash >= 0
+    return shares_log, rewards, cash, h
+
+
+def test_brute_force_all_action_grids_against_exact_rational_ledger():
+    """1 env x 2 stocks x 3 steps, every action sequence on {-1,-1/2,0,1/2,1}^2
+    per step (15 625 sequences).  Integer prices and c = 2^-10 keep every
+    binary32 operation of the checker exact, so equality is demanded."""
+    grid = [-1.0, -0.5, 0.0, 0.5, 1.0]
+    per_step = list(itertools.product(grid, grid))
+    seqs = list(itertools.product(per_step, repeat=3))
+    n = len(seqs)
+    assert n == 15625
+    prices = np.array([[33.0, 17.0], [35.0, 16.0], [31.0, 19.0], [34.0, 18.0], [1.0, 1.0]], np.float32)
+    cash0, hmax, c, rho = 4096.0, 100.0, Fraction(1, 1024), Fraction(1, 64)
+    # horizon 4 > T = 3: no reset inside the three steps, so the final cash and holdings are comparable
+    cfg = oracle.make_cfg(2, 1, 4, cash0=cash0, hmax=hmax, cost=float(c), sigma=0.5, reward_scale=float(rho))
+    mu = np.array(seqs, dtype=np.float32).transpose(1, 0, 2).copy()      # [T=3, N, D=2]
+    noise = np.zeros_like(mu)
+    ind = np.zeros((5, 1, 2), np.float32)
+    out, st = oracle.rollout(cfg, 1, False, 3, prices[:, None, :], ind, noise, mu_forced=mu)
+    limited = 0
+    for i, seq in enumerate(seqs):
+        sh, rw, cash, h = _ledger(seq, prices.tolist(), cash0, int(hmax), c, rho)
+        assert out["shares"][:, i].tolist() == sh, (i, seq)
+        assert [Fraction(float(x)) for x in out["reward"][:, i]] == rw, (i, seq)
+        assert Fraction(float(st.cash[i])) == cash and st.h[i].tolist() == h, (i, seq)
+        limited += any(0 < s[d] < int(abs(a[d]) * 100) for s, a in zip(sh, seq) for d in range(2))
+    assert limited > 1000  # the cash-limited branch is hit in a large share of the sequences
+
+
+def test_trade_flags_mark_only_near_boundaries():
+    cfg = cfg2(D=2, cost=0.0)
+    p = np.array([3.0, 3.0], np.float32)
+    _, _, _, flags = oracle.trade(cfg, 100.0, [0, 0], np.array([0.255, 0.5], np.float32), p)
+    assert flags.tolist() == [0, 0]
+    a = np.nextafter(np.float32(0.25), np.float32(0))      # a * 100 just below 25
+    _, _, shares, flags = oracle.trade(cfg, 1e6, [0, 0], np.array([a, 0.0], np.float32), p)
+    assert flags[0] & oracle.FLAG_TRUNC
