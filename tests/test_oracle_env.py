@@ -339,3 +339,38 @@ def test_trade_flags_mark_only_near_boundaries():
     a = np.nextafter(np.float32(0.25), np.float32(0))      # a * 100 just below 25
     _, _, shares, flags = oracle.trade(cfg, 1e6, [0, 0], np.array([a, 0.0], np.float32), p)
     assert flags[0] & oracle.FLAG_TRUNC
+
+
+def test_rounded_quotient_never_overspends():
+    """cash / u is rounded to binary32 before the floor; when the true quotient
+    lies just below an integer m the rounded one can equal m.  Buying m shares
+    is then allowed only if the binary32 outlay fl(m * u) does not exceed the
+    cash; otherwise one share fewer is bought.  Cash never goes negative."""
+    c = 1.0e-3
+    cfg = cfg2(D=1, K=1, cost=c)
+    rng = np.random.default_rng(11)
+    hits = guards = 0
+    for _ in range(6000):
+        p = np.float32(rng.uniform(10, 100))
+        u = np.float32(p * np.float32(np.float32(1.0) + np.float32(c)))
+        m = int(rng.integers(2, 100))
+        cash = np.float32(np.float32(m) * u)
+        for _ in range(4):
+            if Fraction(float(cash)) < m * Fraction(float(u)):
+                break
+            cash = np.nextafter(cash, np.float32(0))
+        if Fraction(float(cash)) >= m * Fraction(float(u)) or np.float32(cash / u) != np.float32(m):
+            continue
+        hits += 1
+        cash2, h, shares, flags = oracle.trade(cfg, float(cash), [0], np.array([1.0], np.float32), np.array([p]))
+        outlay_m = np.float32(np.float32(m) * u)
+        assert float(cash2) >= 0.0
+        assert flags[0] & oracle.FLAG_FLOOR
+        if outlay_m > cash:
+            guards += 1
+            assert shares.tolist() == [m - 1] and flags[0] & oracle.FLAG_GUARD, (p, m, cash)
+            assert cash2 == np.float32(cash - np.float32(np.float32(m - 1) * u))
+        else:
+            assert shares.tolist() == [m] and not flags[0] & oracle.FLAG_GUARD, (p, m, cash)
+            assert cash2 == np.float32(cash - outlay_m)
+    assert hits > 50 and guards > 10, (hits, guards)
