@@ -1,0 +1,198 @@
+/*
+ * podrollout.h -- C ABI of the single-GPU rollout hot path of one pod.
+ *
+ * The paper describes a pod's worker as an actor interacting with a batched
+ * environment of independent sub-environments to produce batches of
+ * transitions (Sec. 4.2 "Worker"), with all data kept as tensors in contiguous
+ * GPU memory (Sec. 4.3 "Cloud-oriented optimizations").  This library is that
+ * worker for the stock-trading task of Table 1 / Sec. 5.3 (state: balance,
+ * shares, close prices, technical indicators; actions: buy / sell / hold;
+ * reward: change of account value; initial capital and proportional
+ * transaction cost as in the caption of Fig. 6), plus the critic forward and
+ * the advantage estimation that the PPO learner of Sec. 5.2 consumes, and the
+ * leaderboard score of Sec. 4.1 (mean / variance of episodic reward).
+ *
+ * General rules
+ *  - Every pointer is a DEVICE pointer unless its comment says "host".
+ *  - The caller owns every device buffer, including the workspace; the library
+ *    borrows them: market and workspace for the life of the handle, all others
+ *    until the work enqueued by the call has finished.  The library allocates
+ *    only the small host-side handle.
+ *  - Every call enqueues its work on the HIP stream given at init (or passed
+ *    in, for compute_gae) and returns without synchronising.
+ *  - Return value: PR_OK (0) or a negative pr_status.  Arguments are validated
+ *    before any device work is enqueued, so a failed call changes nothing.
+ *    No exceptions, no abort().
+ *  - Row-major layouts; "[T, N, D]" means D is the fastest axis.
+ *
+ * Notation: N envs, P agents (env n belongs to agent n / (N/P)), D stocks,
+ * K indicators per stock, S = 1 + 2D + DK state width, Hd hidden width,
+ * H episode horizon (market has H+1 rows), M market paths, T rollout steps.
+ */
+#ifndef PODROLLOUT_H
+#define PODROLLOUT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum pr_status {
+  PR_OK = 0,
+  PR_EINVAL = -1,       /* bad shape, null pointer, scale not a power of two, ... */
+  PR_ENOMEM = -2,       /* workspace too small / host handle allocation failed    */
+  PR_EHIP = -3,         /* a HIP call failed; see rollout_last_hip_error()        */
+  PR_EUNSUPPORTED = -4  /* valid request outside the shapes the kernels cover     */
+} pr_status;
+
+enum { PR_MLP_F32 = 0, PR_MLP_BF16 = 1 };        /* pr_config.mlp_dtype */
+enum { PR_SCHED_STEPWISE = 0, PR_SCHED_FUSED = 1 }; /* pr_config.schedule  */
+enum { PR_NET_ACTOR = 0, PR_NET_CRITIC = 1 };
+
+/* Plain data, copied at init. */
+typedef struct pr_config {
+  int32_t n_envs;       /* N >= 1 */
+  int32_t n_agents;     /* P >= 1, N % P == 0 */
+  int32_t n_stocks;     /* D >= 1 */
+  int32_t n_ind;        /* K >= 0 */
+  int32_t hidden;       /* Hd, multiple of 32 */
+  int32_t horizon;      /* H >= 1 */
+  int32_t n_market;     /* M in {1, N}: env n reads market path n % M */
+  int32_t mlp_dtype;    /* PR_MLP_F32: fp32 operands on fp32 matrix cores;
+                           PR_MLP_BF16: observations, weights and hidden
+                           activations rounded to bf16 (nearest-even),
+                           fp32 accumulate, fp32 bias / tanh / outputs */
+  int32_t schedule;     /* PR_SCHED_STEPWISE: one actor launch and one env launch
+                           per step; PR_SCHED_FUSED: one persistent launch that
+                           keeps each env tile on one compute unit for all T
+                           steps.  Same results bit for bit. */
+  float cash0;          /* initial capital (> 0) */
+  float hmax;           /* largest trade per stock and step, in shares */
+  float cost;           /* proportional transaction cost c, 0 <= c < 1 */
+  float sigma;          /* fixed std of the Gaussian policy (> 0) */
+  float reward_scale;   /* rho: reward = rho * change of account value */
+  float obs_scale[4];   /* cash, price, holdings, indicator; positive powers of two */
+} pr_config;
+
+/* Market paths (Table 1: close prices, technical indicators). */
+typedef struct pr_market {
+  const float *price;   /* [H+1, M, D]   > 0 */
+  const float *ind;     /* [H+1, M, D*K] stock-major; may be NULL when K == 0 */
+} pr_market;
+
+/* One network 3-layer perceptron per agent, fp32, weights [in, out] row-major:
+ * W1 [P, S, Hd], b1 [P, Hd], W2 [P, Hd, Hd], b2 [P, Hd], W3 [P, Hd, O],
+ * b3 [P, O]; O = D for the actor (tanh after every layer, output included),
+ * O = 1 for the critic (tanh on the hidden layers, linear output). */
+typedef struct pr_weights {
+  const float *W1, *b1, *W2, *b2, *W3, *b3;
+} pr_weights;
+
+/* The rollout buffer: what the worker hands to the learner.  "opt" pointers
+ * may be NULL and are then not written. */
+typedef struct pr_buffers {
+  float *obs;        /* [T+1, N, S] observation before each step, and the last one:
+                        [cash*s0, price_d*s1, holdings_d*s2, ind_{d,k}*s3]         */
+  float *act_raw;    /* [T, N, D]   sampled action mu + sigma*eps, before clamping */
+  float *reward;     /* [T, N]                                                     */
+  uint8_t *done;     /* [T, N]      1 where the step ended an episode              */
+  float *value;      /* opt [T+1, N] critic value of every observation             */
+  float *logp;       /* opt [T, N]  log-density of act_raw under the policy        */
+  float *mu;         /* opt [T, N, D] policy mean                                  */
+  int32_t *shares;   /* opt [T, N, D] executed trades, signed (+ buy, - sell)      */
+} pr_buffers;
+
+/* Per-env state, env-major user layout, for inspection and for planting a
+ * state in tests.  Any pointer may be NULL (skipped). */
+typedef struct pr_state {
+  float *cash;       /* [N]    */
+  int32_t *holdings; /* [N, D] */
+  int32_t *cursor;   /* [N]    market row of the current observation, 0 <= tau < H */
+  double *ep_return; /* [N]    return accumulated in the running episode           */
+  double *ep_sum;    /* [N]    sum of the returns of finished episodes             */
+  double *ep_sqsum;  /* [N]    sum of their squares                                */
+  int32_t *ep_count; /* [N]    number of finished episodes                         */
+} pr_state;
+
+typedef struct pr_handle pr_handle;
+
+/* Device bytes rollout_init needs in `workspace` for this config (packed
+ * weights, env state, per-step scratch).  out: host pointer. */
+int rollout_workspace_bytes(const pr_config *cfg, size_t *out);
+
+/* Create a rollout worker (Sec. 4.2).  Packs both networks into the layout the
+ * matrix-core kernels read, puts every env at (cash0, no shares, cursor 0).
+ * cfg, market, actor, critic: host structs holding device pointers.
+ * workspace: device, 256-byte aligned, >= rollout_workspace_bytes.
+ * hip_stream: a hipStream_t (NULL = default stream); all later calls on the
+ * handle enqueue there.  out: host pointer receiving the handle.
+ * PR_EUNSUPPORTED when Hd, D or the schedule is outside what the kernels cover
+ * (Hd % 32 != 0, Hd > 1024, P > 1 with N/P not a multiple of 64, fused
+ * schedule with a shape it does not implement). */
+int rollout_init(const pr_config *cfg, const pr_market *market, const pr_weights *actor, const pr_weights *critic,
+                 void *workspace, size_t workspace_bytes, void *hip_stream, pr_handle **out);
+
+/* Replace both networks (a new policy for the same envs); env state is kept. */
+int rollout_set_weights(pr_handle *h, const pr_weights *actor, const pr_weights *critic);
+
+/* All envs back to cash0, no shares, cursor 0; episode statistics cleared. */
+int rollout_reset(pr_handle *h);
+
+/* T steps of agent-environment interaction for all N envs (Sec. 4.2 worker;
+ * Table 1 stock trading):
+ *   obs_t -> actor -> mu_t;  a = mu_t + sigma * noise_t;  k_d = trunc(clamp(a_d,-1,1) * hmax);
+ *   every sale in ascending stock order (at most the holding, proceeds * (1-c)),
+ *   then every purchase in ascending stock order (at most what the cash left pays for at price * (1+c));
+ *   cursor += 1; reward = rho * (account value at the new prices - account value before);
+ *   done when the cursor reaches H, then the env restarts from cash0 with no shares at cursor 0.
+ * Then, if out->value is given, the critic on all T+1 observations.
+ * noise: [T, N, D] standard-normal draws supplied by the caller.
+ * Env state persists in the handle: obs row 0 of a call is the last
+ * observation of the previous call.  T >= 1. */
+int rollout_step_T(pr_handle *h, int32_t T, const float *noise, const pr_buffers *out);
+
+/* The same T steps with the policy mean supplied by the caller instead of the
+ * actor (mu: [T, N, D]); the critic is not run and out->value, out->mu are
+ * ignored.  This is the environment + sampling stage on its own. */
+int rollout_step_forced(pr_handle *h, int32_t T, const float *mu, const float *noise, const pr_buffers *out);
+
+/* One network on its own: rows of X ([rows, S], row stride ldx floats) through
+ * the actor (Y [rows, D]) or the critic (Y [rows]) of the agent that owns env
+ * (row % N).  This is the kernel rollout_step_T uses for the critic and, in the
+ * stepwise schedule, for the actor. */
+int rollout_mlp_forward(pr_handle *h, int32_t net, int64_t rows, const float *X, int64_t ldx, float *Y);
+
+/* Copy the per-env state out of / into the handle (device buffers). */
+int rollout_get_state(pr_handle *h, const pr_state *out);
+int rollout_set_state(pr_handle *h, const pr_state *in);
+
+/* Generalised advantage estimation (implied by PPO, Sec. 5.2), per env,
+ * backwards over t, with nd_t = 1 - done_t:
+ *   delta_t = r_t + gamma nd_t V_{t+1} - V_t;  A_t = delta_t + gamma lambda nd_t A_{t+1}, A_T = 0;  R_t = A_t + V_t.
+ * Stateless.  reward, done: [T, N]; value: [T+1, N]; adv, ret: [T, N] outputs.
+ * hip_stream: hipStream_t to enqueue on.  T >= 1, N >= 1. */
+int compute_gae(void *hip_stream, int32_t T, int32_t N, const float *reward, const float *value, const uint8_t *done,
+                float gamma, float lambda, float *adv, float *ret);
+
+/* Leaderboard score of every agent (Sec. 4.1; Sec. 4.2 evaluator): mean and
+ * population variance of the returns of the episodes its envs have finished
+ * since the last reset, and the agents ordered best first (equal means: lower
+ * id first; agents without a finished episode score -inf and come last).
+ * score_mean, score_var: [P] f64; rank: [P] agent ids. */
+int rollout_leaderboard(pr_handle *h, double *score_mean, double *score_var, int32_t *rank);
+
+/* Free the host handle.  Device memory stays with the caller. */
+int rollout_destroy(pr_handle *h);
+
+/* Static text for a pr_status (host string, never NULL). */
+const char *rollout_strerror(int code);
+
+/* hipError_t value of the last failed HIP call on this thread (0 if none). */
+int rollout_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PODROLLOUT_H */

@@ -1,0 +1,345 @@
+// C ABI of libpodrollout: argument validation, workspace layout and the
+// sequencing of kernel launches.  No arithmetic of the method lives here.
+#include <math.h>
+#include <new>
+#include <stdlib.h>
+#include <string.h>
+
+#include "pod_internal.h"
+
+using namespace pod;
+
+struct pr_handle {
+  pr_config cfg;
+  hipStream_t stream;
+  EnvDims dims;
+  EnvState st;
+  pr_market market;
+  PackedNet actor, critic;
+  void *w_packed[2][3];   // device, per net and layer
+  float *b_packed[2][3];
+  float *mu_scratch;      // [N, D]
+  int32_t S;
+};
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+int hip_fail(hipError_t e) {
+  g_last_hip = (int)e;
+  return PR_EHIP;
+}
+
+#define POD_HIP(call)                       \
+  do {                                      \
+    hipError_t e__ = (call);                \
+    if (e__ != hipSuccess) return hip_fail(e__); \
+  } while (0)
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+bool is_pow2_float(float x) {
+  if (!(x > 0.0f) || isinf(x)) return false;
+  int e;
+  return frexpf(x, &e) == 0.5f;
+}
+
+struct Layout {
+  size_t w[2][3], b[2][3];
+  size_t cash, tau, h, ep_ret, ep_sum, ep_sqsum, ep_cnt, mu;
+  size_t total;
+};
+
+int state_dim(const pr_config &c) { return 1 + 2 * c.n_stocks + c.n_stocks * c.n_ind; }
+
+int validate_config(const pr_config *c) {
+  if (!c) return PR_EINVAL;
+  if (c->n_envs < 1 || c->n_agents < 1 || c->n_envs % c->n_agents != 0) return PR_EINVAL;
+  if (c->n_stocks < 1 || c->n_ind < 0 || c->hidden < 1 || c->horizon < 1) return PR_EINVAL;
+  if (c->n_market != 1 && c->n_market != c->n_envs) return PR_EINVAL;
+  if (c->mlp_dtype != PR_MLP_F32 && c->mlp_dtype != PR_MLP_BF16) return PR_EINVAL;
+  if (c->schedule != PR_SCHED_STEPWISE && c->schedule != PR_SCHED_FUSED) return PR_EINVAL;
+  if (!(c->cash0 > 0.0f) || !(c->hmax > 0.0f) || !(c->cost >= 0.0f) || !(c->cost < 1.0f)) return PR_EINVAL;
+  if (!(c->sigma > 0.0f) || !isfinite(c->reward_scale) || !isfinite(c->cash0) || !isfinite(c->hmax)) return PR_EINVAL;
+  for (int i = 0; i < 4; ++i)
+    if (!is_pow2_float(c->obs_scale[i])) return PR_EINVAL;
+  // index arithmetic inside the kernels is 32-bit per step and per market row
+  const double nd = (double)c->n_envs * c->n_stocks * (c->n_ind > 1 ? c->n_ind : 1);
+  const double rows = ((double)c->horizon + 1.0) * c->n_market;
+  if (nd >= 2147483647.0 || rows >= 2147483647.0 || (double)c->n_envs * state_dim(*c) >= 2147483647.0)
+    return PR_EINVAL;
+  // shapes the kernels cover
+  const int S = state_dim(*c);
+  if (!mlp_supported(S, c->hidden, c->n_stocks, c->mlp_dtype) || !mlp_supported(S, c->hidden, 1, c->mlp_dtype))
+    return PR_EUNSUPPORTED;
+  if (c->n_agents > 1 && (c->n_envs / c->n_agents) % 64 != 0) return PR_EUNSUPPORTED;
+  if (c->schedule == PR_SCHED_FUSED) return PR_EUNSUPPORTED;
+  return PR_OK;
+}
+
+Layout make_layout(const pr_config &c) {
+  Layout L;
+  const int S = state_dim(c), Hd = c.hidden, D = c.n_stocks, P = c.n_agents, bf = c.mlp_dtype;
+  const size_t N = (size_t)c.n_envs;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  };
+  const int in_dim[3] = {S, Hd, Hd};
+  for (int net = 0; net < 2; ++net) {
+    const int out_dim[3] = {Hd, Hd, net == 0 ? D : 1};
+    for (int l = 0; l < 3; ++l) {
+      L.w[net][l] = take(packed_weight_bytes(in_dim[l], out_dim[l], bf) * P);
+      L.b[net][l] = take((size_t)padded_out(out_dim[l]) * 4 * P);
+    }
+  }
+  L.cash = take(N * 4);
+  L.tau = take(N * 4);
+  L.h = take(N * D * 4);
+  L.ep_ret = take(N * 8);
+  L.ep_sum = take(N * 8);
+  L.ep_sqsum = take(N * 8);
+  L.ep_cnt = take(N * 4);
+  L.mu = take(N * D * 4);
+  L.total = off;
+  return L;
+}
+
+void fill_net(PackedNet &pn, const pr_handle *h, int net) {
+  const pr_config &c = h->cfg;
+  const int S = h->S, Hd = c.hidden, D = c.n_stocks, bf = c.mlp_dtype;
+  const int KB = bf ? 16 : 8;
+  const int in_dim[3] = {S, Hd, Hd};
+  const int out_dim[3] = {Hd, Hd, net == 0 ? D : 1};
+  for (int l = 0; l < 3; ++l) {
+    pn.W[l] = h->w_packed[net][l];
+    pn.b[l] = h->b_packed[net][l];
+    pn.w_stride[l] = (int64_t)packed_weight_bytes(in_dim[l], out_dim[l], bf);
+    pn.b_stride[l] = padded_out(out_dim[l]);
+    pn.in_dim[l] = in_dim[l];
+    pn.out_dim[l] = out_dim[l];
+    pn.nkb[l] = (in_dim[l] + KB - 1) / KB;
+    pn.nct[l] = (out_dim[l] + 31) / 32;
+  }
+  pn.bf16 = bf;
+  pn.out_tanh = net == 0 ? 1 : 0;
+}
+
+bool weights_ok(const pr_weights *w) { return w && w->W1 && w->b1 && w->W2 && w->b2 && w->W3 && w->b3; }
+
+int pack_nets(pr_handle *h, const pr_weights *actor, const pr_weights *critic) {
+  const pr_config &c = h->cfg;
+  const int S = h->S, Hd = c.hidden, D = c.n_stocks, P = c.n_agents, bf = c.mlp_dtype;
+  const pr_weights *ws[2] = {actor, critic};
+  for (int net = 0; net < 2; ++net) {
+    const float *W[3] = {ws[net]->W1, ws[net]->W2, ws[net]->W3};
+    const float *b[3] = {ws[net]->b1, ws[net]->b2, ws[net]->b3};
+    const int in_dim[3] = {S, Hd, Hd};
+    const int out_dim[3] = {Hd, Hd, net == 0 ? D : 1};
+    for (int l = 0; l < 3; ++l)
+      POD_HIP(launch_pack_layer(h->stream, W[l], b[l], P, in_dim[l], out_dim[l], bf, h->w_packed[net][l],
+                                h->b_packed[net][l]));
+  }
+  return PR_OK;
+}
+
+int check_buffers(const pr_buffers *o) {
+  if (!o || !o->obs || !o->act_raw || !o->reward || !o->done) return PR_EINVAL;
+  return PR_OK;
+}
+
+StepIO step_io(const pr_handle *h, const pr_buffers *o, int t, const float *mu, const float *noise) {
+  const size_t N = (size_t)h->cfg.n_envs, D = (size_t)h->cfg.n_stocks, S = (size_t)h->S;
+  StepIO io;
+  io.mu = mu;
+  io.noise = noise + (size_t)t * N * D;
+  io.obs_next = o->obs + (size_t)(t + 1) * N * S;
+  io.act_raw = o->act_raw + (size_t)t * N * D;
+  io.reward = o->reward + (size_t)t * N;
+  io.done = o->done + (size_t)t * N;
+  io.logp = o->logp ? o->logp + (size_t)t * N : nullptr;
+  io.shares = o->shares ? o->shares + (size_t)t * N * D : nullptr;
+  return io;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rollout_workspace_bytes(const pr_config *cfg, size_t *out) {
+  if (!out) return PR_EINVAL;
+  const int rc = validate_config(cfg);
+  if (rc != PR_OK) return rc;
+  *out = make_layout(*cfg).total;
+  return PR_OK;
+}
+
+int rollout_init(const pr_config *cfg, const pr_market *market, const pr_weights *actor, const pr_weights *critic,
+                 void *workspace, size_t workspace_bytes, void *hip_stream, pr_handle **out) {
+  if (!out) return PR_EINVAL;
+  *out = nullptr;
+  const int rc = validate_config(cfg);
+  if (rc != PR_OK) return rc;
+  if (!market || !market->price || (cfg->n_ind > 0 && !market->ind)) return PR_EINVAL;
+  if (!weights_ok(actor) || !weights_ok(critic)) return PR_EINVAL;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return PR_EINVAL;
+  const Layout L = make_layout(*cfg);
+  if (workspace_bytes < L.total) return PR_ENOMEM;
+
+  pr_handle *h = new (std::nothrow) pr_handle;
+  if (!h) return PR_ENOMEM;
+  memset(h, 0, sizeof(*h));
+  h->cfg = *cfg;
+  h->stream = static_cast<hipStream_t>(hip_stream);
+  h->market = *market;
+  h->S = state_dim(*cfg);
+  unsigned char *ws = static_cast<unsigned char *>(workspace);
+  for (int net = 0; net < 2; ++net)
+    for (int l = 0; l < 3; ++l) {
+      h->w_packed[net][l] = ws + L.w[net][l];
+      h->b_packed[net][l] = reinterpret_cast<float *>(ws + L.b[net][l]);
+    }
+  h->st.cash = reinterpret_cast<float *>(ws + L.cash);
+  h->st.tau = reinterpret_cast<int32_t *>(ws + L.tau);
+  h->st.h = reinterpret_cast<int32_t *>(ws + L.h);
+  h->st.ep_ret = reinterpret_cast<double *>(ws + L.ep_ret);
+  h->st.ep_sum = reinterpret_cast<double *>(ws + L.ep_sum);
+  h->st.ep_sqsum = reinterpret_cast<double *>(ws + L.ep_sqsum);
+  h->st.ep_cnt = reinterpret_cast<int32_t *>(ws + L.ep_cnt);
+  h->mu_scratch = reinterpret_cast<float *>(ws + L.mu);
+
+  EnvDims &d = h->dims;
+  d.N = cfg->n_envs;
+  d.D = cfg->n_stocks;
+  d.K = cfg->n_ind;
+  d.S = h->S;
+  d.H = cfg->horizon;
+  d.M = cfg->n_market;
+  d.cash0 = cfg->cash0;
+  d.hmax = cfg->hmax;
+  d.one_minus_c = 1.0f - cfg->cost;
+  d.one_plus_c = 1.0f + cfg->cost;
+  d.sigma = cfg->sigma;
+  d.rho = cfg->reward_scale;
+  d.logp_const = (float)(-(double)cfg->n_stocks * (log((double)cfg->sigma) + 0.91893853320467274178));
+  d.s_cash = cfg->obs_scale[0];
+  d.s_price = cfg->obs_scale[1];
+  d.s_hold = cfg->obs_scale[2];
+  d.s_ind = cfg->obs_scale[3];
+
+  fill_net(h->actor, h, 0);
+  fill_net(h->critic, h, 1);
+  int prc = pack_nets(h, actor, critic);
+  if (prc == PR_OK) {
+    hipError_t e = launch_state_reset(h->stream, h->dims, h->st);
+    if (e != hipSuccess) prc = hip_fail(e);
+  }
+  if (prc != PR_OK) {
+    delete h;
+    return prc;
+  }
+  *out = h;
+  return PR_OK;
+}
+
+int rollout_set_weights(pr_handle *h, const pr_weights *actor, const pr_weights *critic) {
+  if (!h || !weights_ok(actor) || !weights_ok(critic)) return PR_EINVAL;
+  return pack_nets(h, actor, critic);
+}
+
+int rollout_reset(pr_handle *h) {
+  if (!h) return PR_EINVAL;
+  POD_HIP(launch_state_reset(h->stream, h->dims, h->st));
+  return PR_OK;
+}
+
+int rollout_step_T(pr_handle *h, int32_t T, const float *noise, const pr_buffers *out) {
+  if (!h || T < 1 || !noise) return PR_EINVAL;
+  int rc = check_buffers(out);
+  if (rc != PR_OK) return rc;
+  const size_t N = (size_t)h->cfg.n_envs, D = (size_t)h->cfg.n_stocks, S = (size_t)h->S;
+  const int32_t per_agent = h->cfg.n_envs / h->cfg.n_agents;
+  POD_HIP(launch_observe(h->stream, h->dims, h->st, h->market.price, h->market.ind, out->obs));
+  for (int t = 0; t < T; ++t) {
+    float *mu = out->mu ? out->mu + (size_t)t * N * D : h->mu_scratch;
+    POD_HIP(launch_mlp(h->stream, h->actor, (int64_t)N, out->obs + (size_t)t * N * S, (int64_t)S, mu, (int32_t)N,
+                       per_agent));
+    POD_HIP(launch_env_step(h->stream, h->dims, h->st, h->market.price, h->market.ind,
+                            step_io(h, out, t, mu, noise)));
+  }
+  if (out->value)
+    POD_HIP(launch_mlp(h->stream, h->critic, (int64_t)(T + 1) * (int64_t)N, out->obs, (int64_t)S, out->value,
+                       (int32_t)N, per_agent));
+  return PR_OK;
+}
+
+int rollout_step_forced(pr_handle *h, int32_t T, const float *mu, const float *noise, const pr_buffers *out) {
+  if (!h || T < 1 || !noise || !mu) return PR_EINVAL;
+  int rc = check_buffers(out);
+  if (rc != PR_OK) return rc;
+  const size_t N = (size_t)h->cfg.n_envs, D = (size_t)h->cfg.n_stocks;
+  POD_HIP(launch_observe(h->stream, h->dims, h->st, h->market.price, h->market.ind, out->obs));
+  for (int t = 0; t < T; ++t)
+    POD_HIP(launch_env_step(h->stream, h->dims, h->st, h->market.price, h->market.ind,
+                            step_io(h, out, t, mu + (size_t)t * N * D, noise)));
+  return PR_OK;
+}
+
+int rollout_mlp_forward(pr_handle *h, int32_t net, int64_t rows, const float *X, int64_t ldx, float *Y) {
+  if (!h || (net != PR_NET_ACTOR && net != PR_NET_CRITIC) || rows < 1 || !X || !Y || ldx < h->S) return PR_EINVAL;
+  if ((rows + 63) / 64 > 2147483647LL) return PR_EINVAL;
+  POD_HIP(launch_mlp(h->stream, net == PR_NET_ACTOR ? h->actor : h->critic, rows, X, ldx, Y, h->cfg.n_envs,
+                     h->cfg.n_envs / h->cfg.n_agents));
+  return PR_OK;
+}
+
+int rollout_get_state(pr_handle *h, const pr_state *out) {
+  if (!h || !out) return PR_EINVAL;
+  POD_HIP(launch_state_copy(h->stream, h->dims, h->st, *out, true));
+  return PR_OK;
+}
+
+int rollout_set_state(pr_handle *h, const pr_state *in) {
+  if (!h || !in) return PR_EINVAL;
+  POD_HIP(launch_state_copy(h->stream, h->dims, h->st, *in, false));
+  return PR_OK;
+}
+
+int compute_gae(void *hip_stream, int32_t T, int32_t N, const float *reward, const float *value, const uint8_t *done,
+                float gamma, float lambda, float *adv, float *ret) {
+  if (T < 1 || N < 1 || !reward || !value || !done || !adv || !ret) return PR_EINVAL;
+  if (!isfinite(gamma) || !isfinite(lambda)) return PR_EINVAL;
+  if ((double)(T + 1) * (double)N >= 9.0e18) return PR_EINVAL;
+  POD_HIP(launch_gae(static_cast<hipStream_t>(hip_stream), T, N, reward, value, done, gamma, lambda, adv, ret));
+  return PR_OK;
+}
+
+int rollout_leaderboard(pr_handle *h, double *score_mean, double *score_var, int32_t *rank) {
+  if (!h || !score_mean || !score_var || !rank) return PR_EINVAL;
+  POD_HIP(launch_leaderboard(h->stream, h->cfg.n_envs, h->cfg.n_agents, h->st, nullptr, score_mean, score_var, rank));
+  return PR_OK;
+}
+
+int rollout_destroy(pr_handle *h) {
+  if (!h) return PR_EINVAL;
+  delete h;
+  return PR_OK;
+}
+
+const char *rollout_strerror(int code) {
+  switch (code) {
+    case PR_OK: return "ok";
+    case PR_EINVAL: return "invalid argument";
+    case PR_ENOMEM: return "workspace too small or out of host memory";
+    case PR_EHIP: return "HIP call failed";
+    case PR_EUNSUPPORTED: return "shape or schedule not covered by the kernels";
+    default: return "unknown status";
+  }
+}
+
+int rollout_last_hip_error(void) { return g_last_hip; }
+
+}  // extern "C"

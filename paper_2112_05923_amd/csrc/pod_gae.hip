@@ -1,0 +1,100 @@
+// Generalised advantage estimation as a chunked reverse scan (implied by the
+// paper's use of PPO, Sec. 5.2; see compute_gae in podrollout.h).
+//
+// The recurrence A_t = delta_t + c_t A_{t+1} is first-order linear, so a run of
+// steps can be summarised by the pair (a, p) with A_first = a + p * A_after.
+// One workgroup owns 64 consecutive envs (one per lane, so every load of a row
+// is a contiguous 256-byte segment); each of its wavefronts owns a chunk of
+// GAE_L consecutive steps, loads the whole chunk into registers (all loads in
+// flight at once), scans it locally, publishes its (a, p) through LDS, composes
+// the summaries of the later chunks to get its incoming A, and patches its
+// results.  Segments of NW * GAE_L steps are walked from the end of the rollout
+// to the start with the boundary advantage carried in a register.
+#include "pod_internal.h"
+
+namespace pod {
+
+constexpr int GAE_L = 16;    // steps per wavefront chunk (register resident)
+constexpr int GAE_NW = 16;   // wavefronts per workgroup
+
+__global__ __launch_bounds__(GAE_NW * 64) void gae_kernel(int T, int N, const float *__restrict__ reward,
+                                                         const float *__restrict__ value,
+                                                         const uint8_t *__restrict__ done, float gamma, float gl,
+                                                         float *__restrict__ adv, float *__restrict__ ret) {
+  __shared__ float s_a[GAE_NW][64];
+  __shared__ float s_p[GAE_NW][64];
+  const int lane = threadIdx.x & 63;
+  const int w = threadIdx.x >> 6;
+  const int n = blockIdx.x * 64 + lane;
+  const bool live = n < N;
+  const int seg = GAE_NW * GAE_L;
+  float carry = 0.0f;  // advantage at the first step of the segment handled before (later in time)
+
+  for (int hi = T; hi > 0; hi -= seg) {
+    // chunks are numbered from the end of the segment: chunk w covers [c_lo, c_lo + GAE_L)
+    const int c_lo = hi - (w + 1) * GAE_L;
+    float a[GAE_L], p[GAE_L], v[GAE_L];
+    float r[GAE_L];
+    uint8_t dn[GAE_L];
+    float v_after = 0.0f;
+#pragma unroll
+    for (int i = 0; i < GAE_L; ++i) {
+      const int t = c_lo + i;
+      const bool ok = live && t >= 0;
+      const size_t idx = (size_t)(ok ? t : 0) * N + (live ? n : 0);
+      r[i] = ok ? reward[idx] : 0.0f;
+      v[i] = ok ? value[idx] : 0.0f;
+      dn[i] = ok ? done[idx] : (uint8_t)1;
+    }
+    {
+      const int t = c_lo + GAE_L;  // <= T: value has T+1 rows
+      if (live && t >= 0) v_after = value[(size_t)t * N + n];
+    }
+    // local scan, newest step first
+    float a_next = 0.0f, p_next = 1.0f, v_next = v_after;
+#pragma unroll
+    for (int i = GAE_L - 1; i >= 0; --i) {
+      const bool skip = (c_lo + i) < 0;  // before the start of the rollout: identity
+      const float g = dn[i] ? 0.0f : gamma;
+      const float c = dn[i] ? 0.0f : gl;
+      const float delta = fmaf(g, v_next, r[i]) - v[i];
+      const float ai = skip ? a_next : fmaf(c, a_next, delta);
+      const float pi = skip ? p_next : c * p_next;
+      a[i] = ai;
+      p[i] = pi;
+      a_next = ai;
+      p_next = pi;
+      v_next = v[i];
+    }
+    s_a[w][lane] = a_next;
+    s_p[w][lane] = p_next;
+    __syncthreads();
+    // advantage just after this chunk = later chunks of the segment applied to the carry
+    float a_in = carry;
+    for (int c = 0; c < w; ++c) a_in = fmaf(s_p[c][lane], a_in, s_a[c][lane]);
+    float seg_first = a_in;
+    for (int c = w; c < GAE_NW; ++c) seg_first = fmaf(s_p[c][lane], seg_first, s_a[c][lane]);
+    carry = seg_first;
+#pragma unroll
+    for (int i = 0; i < GAE_L; ++i) {
+      const int t = c_lo + i;
+      if (live && t >= 0) {
+        const float A = fmaf(p[i], a_in, a[i]);
+        const size_t idx = (size_t)t * N + n;
+        adv[idx] = A;
+        ret[idx] = A + v[i];
+      }
+    }
+    __syncthreads();  // summaries are rewritten by the next segment
+  }
+}
+
+hipError_t launch_gae(hipStream_t st, int32_t T, int32_t N, const float *reward, const float *value,
+                      const uint8_t *done, float gamma, float lambda, float *adv, float *ret) {
+  const int blocks = (N + 63) / 64;
+  hipLaunchKernelGGL(gae_kernel, dim3(blocks), dim3(GAE_NW * 64), 0, st, (int)T, (int)N, reward, value, done, gamma,
+                     gamma * lambda, adv, ret);
+  return hipGetLastError();
+}
+
+}  // namespace pod

@@ -1,0 +1,83 @@
+// Internal declarations shared by the HIP translation units of libpodrollout.
+// Host-side launchers only; every kernel lives in the .hip file that defines
+// its launcher.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "podrollout.h"
+
+namespace pod {
+
+// ---------------------------------------------------------------- env state
+// Structure-of-arrays env state in the workspace; n is the fastest axis of
+// every array so that a tile of consecutive envs is one contiguous segment.
+struct EnvState {
+  float *cash;       // [N]
+  int32_t *tau;      // [N]
+  int32_t *h;        // [D][N]
+  double *ep_ret;    // [N]
+  double *ep_sum;    // [N]
+  double *ep_sqsum;  // [N]
+  int32_t *ep_cnt;   // [N]
+};
+
+struct EnvDims {
+  int32_t N, D, K, S, H, M;
+  float cash0, hmax, one_minus_c, one_plus_c, sigma, rho;
+  float logp_const;  // -D * (ln sigma + 0.5 ln 2 pi)
+  float s_cash, s_price, s_hold, s_ind;
+};
+
+struct StepIO {
+  const float *mu;     // [N, D] policy mean of this step
+  const float *noise;  // [N, D]
+  float *obs_next;     // [N, S] observation after the step
+  float *act_raw;      // [N, D]
+  float *reward;       // [N]
+  uint8_t *done;       // [N]
+  float *logp;         // [N] or null
+  int32_t *shares;     // [N, D] or null
+};
+
+hipError_t launch_observe(hipStream_t st, const EnvDims &d, const EnvState &s, const float *price, const float *ind,
+                          float *obs);
+hipError_t launch_env_step(hipStream_t st, const EnvDims &d, const EnvState &s, const float *price, const float *ind,
+                           const StepIO &io);
+hipError_t launch_state_reset(hipStream_t st, const EnvDims &d, const EnvState &s);
+hipError_t launch_state_copy(hipStream_t st, const EnvDims &d, const EnvState &s, const pr_state &user, bool to_user);
+hipError_t launch_leaderboard(hipStream_t st, int32_t N, int32_t P, const EnvState &s, double *scratch_mean,
+                              double *score_mean, double *score_var, int32_t *rank);
+size_t env_step_lds_bytes(const EnvDims &d, int *envs_per_block);
+
+// ---------------------------------------------------------------------- GAE
+hipError_t launch_gae(hipStream_t st, int32_t T, int32_t N, const float *reward, const float *value,
+                      const uint8_t *done, float gamma, float lambda, float *adv, float *ret);
+
+// ---------------------------------------------------------------------- MLP
+// Packed network of one agent set.  Weight blocks are stored in the register
+// layout of the matrix-core instruction: block (ct, kb) holds, for the 64 lanes
+// of a wavefront, the 16 bytes lane l feeds as B operand for output columns
+// [32 ct, 32 ct + 32) and inputs [KB kb, KB kb + KB); KB = 16 (bf16) or 8 (fp32).
+struct PackedNet {
+  const void *W[3];       // packed weights per layer, agent-major
+  const float *b[3];      // biases padded to a multiple of 32, agent-major
+  int64_t w_stride[3];    // bytes between agents
+  int32_t b_stride[3];    // floats between agents
+  int32_t in_dim[3], out_dim[3];  // logical sizes
+  int32_t nkb[3], nct[3];         // k-blocks and column tiles per layer
+  int32_t bf16;                   // operand type
+  int32_t out_tanh;               // tanh on the last layer
+};
+
+size_t packed_weight_bytes(int in_dim, int out_dim, int bf16);
+int padded_out(int out_dim);
+hipError_t launch_pack_layer(hipStream_t st, const float *W, const float *b, int P, int in_dim, int out_dim, int bf16,
+                             void *Wp, float *bp);
+// rows of X [rows, ldx] -> Y [rows, out_dim[2]]; row r uses agent ((r % N) / envs_per_agent).
+hipError_t launch_mlp(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx, float *Y,
+                      int32_t N, int32_t envs_per_agent);
+bool mlp_supported(int S, int Hd, int O, int bf16);
+
+}  // namespace pod

@@ -1,0 +1,459 @@
+// Three-layer perceptron forward (actor / critic networks of a pod, Sec. 4.1
+// "training files" and Sec. 4.2 worker) on the matrix cores of gfx950.
+//
+// One workgroup (4 wavefronts) owns a tile of BM = 32 RT rows and carries it
+// through all three layers without leaving the compute unit:
+//   layer 1: A = rows of X, staged from global memory into LDS in k-chunks
+//            (converted to the operand type on the way), B = packed weights;
+//   layer 2: A = hidden tile in LDS;   layer 3: A = hidden tile in LDS.
+// The four wavefronts split the OUTPUT COLUMNS of a layer, so the activation
+// tile is the shared operand (LDS) and every weight block is fetched by
+// exactly one wavefront, straight from global/L2 into the registers it is
+// consumed from: weights are pre-packed in the B-operand register layout, so a
+// block is one 1-KiB fully coalesced load.  Accumulators (fp32) stay in
+// registers for a whole layer; bias + tanh are applied once, on the way to LDS.
+//
+// Operand types: bf16 (v_mfma_f32_32x32x16_bf16, k-block 16) or fp32
+// (v_mfma_f32_32x32x2_f32 x 4, k-block 8).  In both, lane l of a wavefront
+// feeds row/column (l % 32) and the k-half (l / 32) of a k-block: 16 bytes per
+// lane and operand.
+#include "pod_internal.h"
+
+namespace pod {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWaves = 4;
+constexpr int kThreads = kWaves * 64;
+
+template <bool BF16>
+struct Op;
+
+template <>
+struct Op<true> {
+  static constexpr int KB = 16;   // inputs per k-block
+  static constexpr int ESZ = 2;   // bytes per LDS element
+  static __device__ inline void mma(const u32x4 &a, const u32x4 &b, f32x16 &c) {
+    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0,
+                                                0);
+  }
+  static __device__ inline void store(unsigned char *p, float v) { *reinterpret_cast<__bf16 *>(p) = (__bf16)v; }
+};
+
+template <>
+struct Op<false> {
+  static constexpr int KB = 8;
+  static constexpr int ESZ = 4;
+  static __device__ inline void mma(const u32x4 &a, const u32x4 &b, f32x16 &c) {
+    const f32x4 af = __builtin_bit_cast(f32x4, a), bf = __builtin_bit_cast(f32x4, b);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(af[0], bf[0], c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(af[1], bf[1], c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(af[2], bf[2], c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(af[3], bf[3], c, 0, 0, 0);
+  }
+  static __device__ inline void store(unsigned char *p, float v) { *reinterpret_cast<float *>(p) = v; }
+};
+
+// tanh to a few 1e-7 relative: odd Taylor polynomial below 1/4, 1 - 2/(e^{2|x|}+1) above.
+__device__ inline float tanh_accurate(float x) {
+  const float ax = fabsf(x);
+  const float x2 = x * x;
+  float ps = fmaf(x2, 62.0f / 2835.0f, -17.0f / 315.0f);
+  ps = fmaf(x2, ps, 2.0f / 15.0f);
+  ps = fmaf(x2, ps, -1.0f / 3.0f);
+  const float small = fmaf(x2 * x, ps, x);
+  const float e = __builtin_amdgcn_exp2f(ax * 2.8853900817779268f);  // exp(2|x|)
+  const float big = copysignf(1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f), x);
+  return ax < 0.25f ? small : big;
+}
+
+// tanh good to ~1e-7 absolute; used where the result is rounded to bf16 anyway.
+__device__ inline float tanh_fast(float x) {
+  const float e = __builtin_amdgcn_exp2f(x * 2.8853900817779268f);
+  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
+}
+
+struct MlpArgs {
+  const float *X;
+  int64_t ldx;
+  int64_t rows;
+  float *Y;
+  PackedNet net;
+  int32_t N, envs_per_agent;
+  int32_t xpitch;   // bytes per row of one staged X chunk
+  int32_t hpitch;   // bytes per row of the hidden tile
+};
+
+// B-operand block (ct, kb) of a packed layer for this lane.
+__device__ inline u32x4 load_b(const u32x4 *Wp, int nkb, int ct, int kb, int lane) {
+  return Wp[((size_t)ct * nkb + kb) * 64 + lane];
+}
+
+// acc += A(tile in LDS, all k-blocks) * B.  Wavefront-uniform control flow.
+template <bool BF16, int RT, int CT, int PD>
+__device__ inline void layer_from_lds(f32x16 (&acc)[RT][CT], const unsigned char *ldsA, int pitch, int nkb,
+                                      const u32x4 *Wp, int ct0, int nct, int lane) {
+  using O = Op<BF16>;
+  const int arow = lane & 31, g = lane >> 5;
+  int cts[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) cts[c] = min(ct0 + c, nct - 1);
+  u32x4 ring[PD][CT];
+#pragma unroll
+  for (int s = 0; s < PD; ++s)
+    if (s < nkb) {
+#pragma unroll
+      for (int c = 0; c < CT; ++c) ring[s][c] = load_b(Wp, nkb, cts[c], s, lane);
+    }
+  for (int kb0 = 0; kb0 < nkb; kb0 += PD) {
+#pragma unroll
+    for (int s = 0; s < PD; ++s) {
+      const int kb = kb0 + s;
+      if (kb < nkb) {
+        u32x4 a[RT];
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+          a[r] = *reinterpret_cast<const u32x4 *>(ldsA + (size_t)(r * 32 + arow) * pitch + kb * 32 + 16 * g);
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+#pragma unroll
+          for (int c = 0; c < CT; ++c) O::mma(a[r], ring[s][c], acc[r][c]);
+        if (kb + PD < nkb) {
+#pragma unroll
+          for (int c = 0; c < CT; ++c) ring[s][c] = load_b(Wp, nkb, cts[c], kb + PD, lane);
+        }
+      }
+    }
+  }
+}
+
+// acc += A(rows of X in global memory, staged through two LDS chunk buffers) * B.
+// Every wavefront of the workgroup must call this (staging and barriers are
+// collective); `active` says whether this wavefront owns any output column.
+template <bool BF16, int RT, int CT, int PD>
+__device__ inline void layer_from_global(f32x16 (&acc)[RT][CT], unsigned char *ldsX, int xpitch, const float *X,
+                                         int64_t ldx, int64_t row0, int nrows, int S, int nkb, const u32x4 *Wp,
+                                         int ct0, int nct, bool active, int tid) {
+  using O = Op<BF16>;
+  constexpr int BM = 32 * RT;
+  constexpr int KC = PD * O::KB;             // inputs per staged chunk (power of two)
+  constexpr int NPRE = BM * KC / kThreads;   // elements each thread stages per chunk
+  const int lane = tid & 63;
+  const int arow = lane & 31, g = lane >> 5;
+  const int nch = (nkb + PD - 1) / PD;
+  const size_t xbuf = (size_t)BM * xpitch;
+
+  int cts[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) cts[c] = min(ct0 + c, nct - 1);
+  u32x4 ring[PD][CT];
+  if (active) {
+#pragma unroll
+    for (int s = 0; s < PD; ++s)
+      if (s < nkb) {
+#pragma unroll
+        for (int c = 0; c < CT; ++c) ring[s][c] = load_b(Wp, nkb, cts[c], s, lane);
+      }
+  }
+
+  float pre[NPRE];
+  auto gload = [&](int ch) {
+#pragma unroll
+    for (int i = 0; i < NPRE; ++i) {
+      const int idx = tid + kThreads * i;
+      const int row = idx / KC, col = ch * KC + (idx % KC);
+      pre[i] = (row < nrows && col < S) ? X[(row0 + row) * ldx + col] : 0.0f;
+    }
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < NPRE; ++i) {
+      const int idx = tid + kThreads * i;
+      const int row = idx / KC, col = idx % KC;
+      O::store(ldsX + buf * xbuf + (size_t)row * xpitch + col * O::ESZ, pre[i]);
+    }
+  };
+
+  gload(0);
+  sstore(0);
+  __syncthreads();
+  for (int ch = 0; ch < nch; ++ch) {
+    const bool more = ch + 1 < nch;
+    if (more) gload(ch + 1);
+    if (active) {
+      const unsigned char *buf = ldsX + (ch & 1) * xbuf;
+#pragma unroll
+      for (int s = 0; s < PD; ++s) {
+        const int kb = ch * PD + s;
+        if (kb < nkb) {
+          u32x4 a[RT];
+#pragma unroll
+          for (int r = 0; r < RT; ++r)
+            a[r] = *reinterpret_cast<const u32x4 *>(buf + (size_t)(r * 32 + arow) * xpitch + s * 32 + 16 * g);
+#pragma unroll
+          for (int r = 0; r < RT; ++r)
+#pragma unroll
+            for (int c = 0; c < CT; ++c) O::mma(a[r], ring[s][c], acc[r][c]);
+          if (kb + PD < nkb) {
+#pragma unroll
+            for (int c = 0; c < CT; ++c) ring[s][c] = load_b(Wp, nkb, cts[c], kb + PD, lane);
+          }
+        }
+      }
+    }
+    if (more) sstore((ch + 1) & 1);
+    __syncthreads();
+  }
+}
+
+template <int RT, int CT>
+__device__ inline void zero_acc(f32x16 (&acc)[RT][CT]) {
+#pragma unroll
+  for (int r = 0; r < RT; ++r)
+#pragma unroll
+    for (int c = 0; c < CT; ++c)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[r][c][i] = 0.0f;
+}
+
+// hidden = tanh(acc + bias) -> LDS tile in the operand type.
+// Accumulator register i of lane l holds row 8 (i / 4) + 4 (l / 32) + i % 4, column l % 32 of a 32x32 tile.
+template <bool BF16, int RT, int CT>
+__device__ inline void epilogue_to_lds(const f32x16 (&acc)[RT][CT], const float *bias, unsigned char *ldsH, int hpitch,
+                                       int ct0, int nct, int lane) {
+  using O = Op<BF16>;
+  const int g = lane >> 5, cl = lane & 31;
+#pragma unroll
+  for (int c = 0; c < CT; ++c) {
+    if (ct0 + c < nct) {
+      const int col = (ct0 + c) * 32 + cl;
+      const float bv = bias[col];
+#pragma unroll
+      for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int row = r * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+          const float z = acc[r][c][i] + bv;
+          const float hval = BF16 ? tanh_fast(z) : tanh_accurate(z);
+          O::store(ldsH + (size_t)row * hpitch + col * O::ESZ, hval);
+        }
+    }
+  }
+}
+
+template <int RT, int CT>
+__device__ inline void epilogue_to_global(const f32x16 (&acc)[RT][CT], const float *bias, float *Y, int64_t row0,
+                                          int nrows, int O_dim, int out_tanh, int ct0, int nct, int lane) {
+  const int g = lane >> 5, cl = lane & 31;
+#pragma unroll
+  for (int c = 0; c < CT; ++c) {
+    if (ct0 + c < nct) {
+      const int col = (ct0 + c) * 32 + cl;
+      const float bv = bias[col];
+#pragma unroll
+      for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int row = r * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+          const float z = acc[r][c][i] + bv;
+          const float y = out_tanh ? tanh_accurate(z) : z;
+          if (row < nrows && col < O_dim) Y[(row0 + row) * O_dim + col] = y;
+        }
+    }
+  }
+}
+
+template <bool BF16, int RT, int CTH, int CTO>
+__global__ __launch_bounds__(kThreads) void mlp3_kernel(MlpArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  constexpr int BM = 32 * RT;
+  constexpr int PDH = CTH >= 8 ? 2 : 4;
+  constexpr int PDO = CTO >= 8 ? 2 : 4;
+  unsigned char *ldsH = lds;
+  unsigned char *ldsX = lds + (size_t)BM * a.hpitch;
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int64_t row0 = (int64_t)blockIdx.x * BM;
+  const int nrows = (int)min((int64_t)BM, a.rows - row0);
+  const int agent = (int)((row0 % a.N) / a.envs_per_agent);
+  const PackedNet &net = a.net;
+  const u32x4 *W1 = reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(net.W[0]) +
+                                                    (size_t)agent * net.w_stride[0]);
+  const u32x4 *W2 = reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(net.W[1]) +
+                                                    (size_t)agent * net.w_stride[1]);
+  const u32x4 *W3 = reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(net.W[2]) +
+                                                    (size_t)agent * net.w_stride[2]);
+  const float *b1 = net.b[0] + (size_t)agent * net.b_stride[0];
+  const float *b2 = net.b[1] + (size_t)agent * net.b_stride[1];
+  const float *b3 = net.b[2] + (size_t)agent * net.b_stride[2];
+
+  const int cth0 = w * CTH;
+  const bool act_h = cth0 < net.nct[0];
+  {
+    f32x16 acc[RT][CTH];
+    zero_acc<RT, CTH>(acc);
+    layer_from_global<BF16, RT, CTH, PDH>(acc, ldsX, a.xpitch, a.X, a.ldx, row0, nrows, net.in_dim[0], net.nkb[0], W1,
+                                          cth0, net.nct[0], act_h, tid);
+    if (act_h) epilogue_to_lds<BF16, RT, CTH>(acc, b1, ldsH, a.hpitch, cth0, net.nct[0], lane);
+    __syncthreads();
+    zero_acc<RT, CTH>(acc);
+    if (act_h) layer_from_lds<BF16, RT, CTH, PDH>(acc, ldsH, a.hpitch, net.nkb[1], W2, cth0, net.nct[1], lane);
+    __syncthreads();  // every wavefront has read the whole layer-1 tile
+    if (act_h) epilogue_to_lds<BF16, RT, CTH>(acc, b2, ldsH, a.hpitch, cth0, net.nct[1], lane);
+    __syncthreads();
+  }
+  {
+    const int cto0 = w * CTO;
+    if (cto0 < net.nct[2]) {
+      f32x16 acc[RT][CTO];
+      zero_acc<RT, CTO>(acc);
+      layer_from_lds<BF16, RT, CTO, PDO>(acc, ldsH, a.hpitch, net.nkb[2], W3, cto0, net.nct[2], lane);
+      epilogue_to_global<RT, CTO>(acc, b3, a.Y, row0, nrows, net.out_dim[2], net.out_tanh, cto0, net.nct[2], lane);
+    }
+  }
+}
+
+// ------------------------------------------------------------- weight packing
+__global__ void pack_layer_kernel(const float *__restrict__ W, const float *__restrict__ b, int P, int in_dim,
+                                  int out_dim, int bf16, int nkb, int nct, void *__restrict__ Wp,
+                                  float *__restrict__ bp) {
+  const size_t per_agent = (size_t)nct * nkb * 64;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < per_agent * P) {
+    const int agent = (int)(i / per_agent);
+    const size_t j = i - (size_t)agent * per_agent;
+    const int lane = (int)(j & 63);
+    const int kb = (int)((j >> 6) % nkb);
+    const int ct = (int)((j >> 6) / nkb);
+    const int col = ct * 32 + (lane & 31), g = lane >> 5;
+    const float *Wa = W + (size_t)agent * in_dim * out_dim;
+    if (bf16) {
+      __bf16 v[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int k = kb * 16 + 8 * g + e;
+        v[e] = (__bf16)((k < in_dim && col < out_dim) ? Wa[(size_t)k * out_dim + col] : 0.0f);
+      }
+      __bf16 *dst = reinterpret_cast<__bf16 *>(Wp) + i * 8;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dst[e] = v[e];
+    } else {
+      float *dst = reinterpret_cast<float *>(Wp) + i * 4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int k = kb * 8 + 4 * g + e;
+        dst[e] = (k < in_dim && col < out_dim) ? Wa[(size_t)k * out_dim + col] : 0.0f;
+      }
+    }
+  }
+  const size_t nb = (size_t)P * nct * 32;
+  if (i < nb) {
+    const int agent = (int)(i / (nct * 32));
+    const int col = (int)(i % (nct * 32));
+    bp[i] = col < out_dim ? b[(size_t)agent * out_dim + col] : 0.0f;
+  }
+}
+
+int kblock(int bf16) { return bf16 ? 16 : 8; }
+
+struct Shape {
+  int cth, cto;  // column tiles per wavefront, hidden / output layers
+};
+
+bool pick_shape(int Hd, int O, int bf16, Shape *s) {
+  if (Hd < 32 || Hd % 32 != 0 || O < 1) return false;
+  const int nh = Hd / 32, no = (O + 31) / 32;
+  const int need_h = (nh + kWaves - 1) / kWaves, need_o = (no + kWaves - 1) / kWaves;
+  int cth = need_h <= 1 ? 1 : need_h <= 2 ? 2 : need_h <= 4 ? 4 : need_h <= 8 ? 8 : 0;
+  int cto = need_o <= 1 ? 1 : need_o <= 4 ? 4 : 0;
+  if (!cth || !cto) return false;
+  if (!bf16 && cth > 4) return false;       // fp32 hidden tile of 1024 columns exceeds LDS
+  if (cto == 4 && cth < 4) return false;    // wide outputs only with wide hidden layers
+  s->cth = cth;
+  s->cto = cto;
+  return true;
+}
+
+}  // namespace
+
+bool mlp_supported(int S, int Hd, int O, int bf16) {
+  Shape s;
+  return S >= 1 && pick_shape(Hd, O, bf16, &s);
+}
+
+int padded_out(int out_dim) { return (out_dim + 31) / 32 * 32; }
+
+size_t packed_weight_bytes(int in_dim, int out_dim, int bf16) {
+  const int KB = kblock(bf16);
+  const size_t nkb = (in_dim + KB - 1) / KB, nct = (out_dim + 31) / 32;
+  return nkb * nct * 64 * 16;
+}
+
+hipError_t launch_pack_layer(hipStream_t st, const float *W, const float *b, int P, int in_dim, int out_dim, int bf16,
+                             void *Wp, float *bp) {
+  const int KB = kblock(bf16);
+  const int nkb = (in_dim + KB - 1) / KB, nct = (out_dim + 31) / 32;
+  const size_t n = (size_t)P * nct * nkb * 64;
+  const size_t nb = (size_t)P * nct * 32;
+  const size_t total = n > nb ? n : nb;
+  hipLaunchKernelGGL(pack_layer_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, W, b, P, in_dim,
+                     out_dim, bf16, nkb, nct, Wp, bp);
+  return hipGetLastError();
+}
+
+template <bool BF16, int CTH, int CTO>
+static hipError_t launch_one(hipStream_t st, const MlpArgs &a, unsigned blocks, size_t lds) {
+  auto kern = mlp3_kernel<BF16, 2, CTH, CTO>;
+  static bool attr_set = false;  // per instantiation
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(kThreads), lds, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_mlp(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx, float *Y,
+                      int32_t N, int32_t envs_per_agent) {
+  Shape s;
+  if (!pick_shape(net.out_dim[0], net.out_dim[2], net.bf16, &s)) return hipErrorInvalidValue;
+  constexpr int BM = 64;
+  const int esz = net.bf16 ? 2 : 4, KB = kblock(net.bf16);
+  const int pd = s.cth >= 8 ? 2 : 4;
+  MlpArgs a;
+  a.X = X;
+  a.ldx = ldx;
+  a.rows = rows;
+  a.Y = Y;
+  a.net = net;
+  a.N = N;
+  a.envs_per_agent = envs_per_agent;
+  a.xpitch = pd * KB * esz + 16;
+  a.hpitch = net.out_dim[0] * esz + 16;
+  const size_t lds = (size_t)BM * a.hpitch + 2 * (size_t)BM * a.xpitch;
+  if (lds > 160 * 1024) return hipErrorInvalidValue;
+  const unsigned blocks = (unsigned)((rows + BM - 1) / BM);
+#define POD_CASE(B, H, O_) \
+  if ((net.bf16 != 0) == B && s.cth == H && s.cto == O_) return launch_one<B, H, O_>(st, a, blocks, lds);
+  POD_CASE(true, 1, 1)
+  POD_CASE(true, 2, 1)
+  POD_CASE(true, 4, 1)
+  POD_CASE(true, 4, 4)
+  POD_CASE(true, 8, 1)
+  POD_CASE(true, 8, 4)
+  POD_CASE(false, 1, 1)
+  POD_CASE(false, 2, 1)
+  POD_CASE(false, 4, 1)
+  POD_CASE(false, 4, 4)
+#undef POD_CASE
+  return hipErrorInvalidValue;
+}
+
+}  // namespace pod

@@ -1,0 +1,301 @@
+"""GPU-vs-checker parity of every stage of the rollout path, through the C ABI.
+
+Integers (share counts, cursors, done flags, ranks) and everything that is an
+exact function of them (observations, raw actions) must agree bit for bit;
+network outputs within 1e-4 (fp32) / 2e-2 (bf16) relative; rewards and GAE
+within the bounds in tests/parity.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import parity
+from paper_2112_05923_amd import inputs, podrollout as pr
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _dev(d):
+    return {k: torch.from_numpy(np.ascontiguousarray(v)).to(DEV) for k, v in d.items()}
+
+
+def _make(w, horizon=None, n_market=None, steps=None):
+    H = w.steps if horizon is None else horizon
+    d = inputs.make_all(w, horizon=H, n_market=n_market, steps=steps)
+    cfg = pr.make_config(w, horizon=H, n_market=n_market)
+    ro = pr.Rollout(cfg, torch.from_numpy(d["price"]).to(DEV), torch.from_numpy(d["ind"]).to(DEV), _dev(d["actor"]),
+                    _dev(d["critic"]))
+    return d, ro, oracle.cfg_from_workload(w, horizon=H)
+
+
+def _rec(out):
+    return {k: parity.to_np(v) for k, v in out.items()}
+
+
+# ------------------------------------------------------------------------ GAE
+
+@pytest.mark.parametrize("T,N,p_done", [(64, 16, 0.05), (1, 1, 0.0), (300, 1000, 0.02), (257, 65, 0.5), (1024, 333, 0.0)])
+def test_gae_matches_checker(T, N, p_done):
+    rng = np.random.default_rng(T * 1000 + N)
+    r = rng.standard_normal((T, N)).astype(np.float32)
+    v = rng.standard_normal((T + 1, N)).astype(np.float32)
+    done = (rng.random((T, N)) < p_done).astype(np.uint8)
+    adv, ret = pr.compute_gae(torch.from_numpy(r).to(DEV), torch.from_numpy(v).to(DEV), torch.from_numpy(done).to(DEV),
+                              0.99, 0.95)
+    torch.cuda.synchronize()
+    parity.check_gae(r, v, done, 0.99, 0.95, parity.to_np(adv), parity.to_np(ret))
+
+
+def test_gae_gamma_lambda_one_is_reward_to_go_minus_value():
+    rng = np.random.default_rng(5)
+    T, N = 200, 70
+    r = rng.standard_normal((T, N)).astype(np.float32)
+    v = rng.standard_normal((T + 1, N)).astype(np.float32)
+    done = np.zeros((T, N), np.uint8)
+    done[-1] = 1
+    adv, _ = pr.compute_gae(torch.from_numpy(r).to(DEV), torch.from_numpy(v).to(DEV), torch.from_numpy(done).to(DEV),
+                            1.0, 1.0)
+    want = np.cumsum(r[::-1].astype(np.float64), axis=0)[::-1] - v[:-1]
+    np.testing.assert_allclose(parity.to_np(adv), want, rtol=0, atol=2e-4)
+
+
+# ------------------------------------------------------------------- networks
+
+@pytest.mark.parametrize("name,rows,agents", [("tiny", 16, 1), ("tiny", 130, 1), ("dow30", 200, 1), ("large", 150, 1),
+                                              ("dow30", 256, 2)])
+def test_mlp_forward_matches_checker(name, rows, agents):
+    base = inputs.WORKLOADS[name]
+    w = base.replace(n_envs=128 * agents if agents > 1 else 64, n_agents=agents, steps=2)
+    d, ro, _ = _make(w)
+    rng = np.random.default_rng(rows)
+    X = rng.standard_normal((rows, w.state_dim)).astype(np.float32)
+    X[:, 0] *= 0.5
+    Xd = torch.from_numpy(X).to(DEV)
+    mu = parity.to_np(ro.mlp_forward(pr.PR_NET_ACTOR, Xd))
+    val = parity.to_np(ro.mlp_forward(pr.PR_NET_CRITIC, Xd))
+    per_agent = w.n_envs // agents
+    for g in range(agents):
+        sel = ((np.arange(rows) % w.n_envs) // per_agent) == g
+        if sel.any():
+            parity.check_networks(w, d["actor"], d["critic"], X[sel], mu[sel], val[sel], agent=g)
+
+
+def test_mlp_forward_strided_input_and_padding_columns():
+    w = inputs.WORKLOADS["tiny"].replace(n_envs=64, steps=2)
+    d, ro, _ = _make(w)
+    rng = np.random.default_rng(3)
+    S = w.state_dim
+    buf = torch.from_numpy(rng.standard_normal((40, S + 11)).astype(np.float32)).to(DEV)
+    X = buf[:, :S]
+    mu = parity.to_np(ro.mlp_forward(pr.PR_NET_ACTOR, X))
+    parity.check_networks(w, d["actor"], d["critic"], parity.to_np(X), mu, None)
+
+
+# ---------------------------------------------------------------- environment
+
+def _forced_case(w, horizon, n_market=None, T=None, cash0=None, seed=0):
+    if cash0 is not None:
+        w = w.replace(cash0=cash0)
+    T = w.steps if T is None else T
+    d, ro, ocfg = _make(w, horizon=horizon, n_market=n_market, steps=T)
+    rng = np.random.default_rng(seed)
+    mu = rng.uniform(-1.0, 1.0, size=d["noise"].shape).astype(np.float32)
+    out = ro.alloc_buffers(T, value=False, logp=True, mu=False, shares=True)
+    ro.step_forced(T, torch.from_numpy(mu).to(DEV), torch.from_numpy(d["noise"]).to(DEV), out)
+    torch.cuda.synchronize()
+    rec = _rec(out)
+    chk, st = parity.check_env_record(w, ocfg, rec, d["price"], d["ind"], d["noise"], mu)
+    gst = {k: parity.to_np(v) for k, v in ro.get_state().items()}
+    assert np.array_equal(gst["cash"], st.cash) and np.array_equal(gst["holdings"], st.h)
+    assert np.array_equal(gst["cursor"], st.tau) and np.array_equal(gst["ep_count"], st.ep_cnt)
+    np.testing.assert_allclose(gst["ep_sum"], st.ep_sum, rtol=1e-9, atol=1e-9)
+    np.testing.assert_allclose(gst["ep_sqsum"], st.ep_sqsum, rtol=1e-9, atol=1e-9)
+    np.testing.assert_allclose(gst["ep_return"], st.ep_ret, rtol=1e-9, atol=1e-9)
+    return rec, chk
+
+
+def test_env_forced_tiny_full():
+    rec, chk = _forced_case(inputs.WORKLOADS["tiny"], horizon=64)
+    assert np.abs(rec["shares"]).sum() > 0
+
+
+def test_env_forced_resets_inside_rollout_and_cash_starved():
+    rec, chk = _forced_case(inputs.WORKLOADS["tiny"], horizon=24, cash0=3000.0, seed=1)
+    assert rec["done"].sum() == 2 * 16
+    wanted = np.trunc(np.clip(rec["act_raw"], -1, 1) * np.float32(100.0))
+    assert ((wanted > 0) & (rec["shares"] < wanted)).any()
+
+
+def test_env_forced_ragged_tiles_dow30_shape():
+    # 200 envs = 3 full tiles of 64 + a ragged tail of 8; 30 stocks x 8 indicators
+    w = inputs.WORKLOADS["dow30"].replace(n_envs=200, steps=40, hidden=64)
+    _forced_case(w, horizon=16, seed=2)
+
+
+def test_env_forced_shared_market_single_env_and_no_indicators():
+    w = inputs.WORKLOADS["tiny"].replace(n_envs=70)
+    _forced_case(w, horizon=32, n_market=1, seed=3)
+    _forced_case(inputs.WORKLOADS["tiny"].replace(n_envs=1), horizon=64, seed=4)
+    _forced_case(inputs.WORKLOADS["tiny"].replace(n_envs=5, n_stocks=1), horizon=64, seed=5)
+    _forced_case(inputs.WORKLOADS["tiny"].replace(n_envs=33, n_stocks=3, n_ind=0), horizon=64, seed=6)
+
+
+def test_env_wide_universe_shape():
+    # 500 stocks: the small-tile variant of the step kernel
+    w = inputs.WORKLOADS["wide"].replace(n_envs=9, steps=6, hidden=512)
+    _forced_case(w, horizon=4, seed=7)
+
+
+def test_state_roundtrip_and_carry_across_calls():
+    w = inputs.WORKLOADS["tiny"]
+    H = 24
+    d, ro, ocfg = _make(w, horizon=H)
+    noise = torch.from_numpy(d["noise"]).to(DEV)
+    rng = np.random.default_rng(8)
+    mu = rng.uniform(-1, 1, d["noise"].shape).astype(np.float32)
+    mud = torch.from_numpy(mu).to(DEV)
+    a = ro.step_forced(40, mud[:40].contiguous(), noise[:40].contiguous(), ro.alloc_buffers(40, value=False, shares=True))
+    b = ro.step_forced(24, mud[40:].contiguous(), noise[40:].contiguous(), ro.alloc_buffers(24, value=False, shares=True))
+    torch.cuda.synchronize()
+    ra, rb = _rec(a), _rec(b)
+    assert np.array_equal(ra["obs"][-1], rb["obs"][0])
+    joined = {k: np.concatenate([ra[k], rb[k]]) for k in ("act_raw", "reward", "done", "shares", "logp")}
+    joined["obs"] = np.concatenate([ra["obs"], rb["obs"][1:]])
+    parity.check_env_record(w, ocfg, joined, d["price"], d["ind"], d["noise"], mu)
+    # plant a state, read it back
+    st = ro.get_state()
+    st["cash"].fill_(1234.5)
+    st["holdings"].copy_(torch.arange(w.n_envs * w.n_stocks, dtype=torch.int32, device=DEV).view(w.n_envs, -1))
+    st["cursor"].fill_(3)
+    ro.set_state(st)
+    back = ro.get_state()
+    torch.cuda.synchronize()
+    for k in st:
+        assert torch.equal(st[k], back[k]), k
+    ro.reset()
+    z = ro.get_state()
+    assert float(z["cash"].min()) == w.cash0 and int(z["holdings"].abs().sum()) == 0 and int(z["cursor"].sum()) == 0
+
+
+# -------------------------------------------------------------- whole rollout
+
+def _stagewise(w, d, ro, ocfg, T, rec, state0=None):
+    """Teacher-forced stage checks of a recorded free-running rollout."""
+    chk, st = parity.check_env_record(w, ocfg, rec, d["price"], d["ind"], d["noise"][:T], rec["mu"], state0=state0)
+    N, S = w.n_envs, w.state_dim
+    per_agent = N // w.n_agents
+    rng = np.random.default_rng(99)
+    for g in range(w.n_agents):
+        envs = np.arange(g * per_agent, (g + 1) * per_agent)
+        envs = envs[rng.permutation(envs.size)[:8]]
+        ts = rng.permutation(T)[:12]
+        obs = rec["obs"][ts][:, envs].reshape(-1, S)
+        mu = rec["mu"][ts][:, envs].reshape(-1, w.n_stocks)
+        val = rec["value"][ts][:, envs].reshape(-1)
+        parity.check_networks(w, d["actor"], d["critic"], obs, mu, val, agent=g)
+    last = rec["obs"][T].reshape(-1, S)[:4]
+    parity.check_networks(w, d["actor"], d["critic"], last, None, rec["value"][T][:4], agent=0)
+    return chk, st
+
+
+@pytest.mark.parametrize("name,N,T,H", [("tiny", 16, 64, 64), ("tiny", 16, 64, 20), ("dow30", 192, 24, 24),
+                                        ("large", 128, 16, 16)])
+def test_rollout_stagewise(name, N, T, H):
+    w = inputs.WORKLOADS[name].replace(n_envs=N, steps=T)
+    d, ro, ocfg = _make(w, horizon=H)
+    out = ro.alloc_buffers(T, value=True, logp=True, mu=True, shares=True)
+    ro.step_T(T, torch.from_numpy(d["noise"]).to(DEV), out)
+    adv, ret = pr.compute_gae(out["reward"], out["value"], out["done"], w.gamma, w.lam)
+    torch.cuda.synchronize()
+    rec = _rec(out)
+    _stagewise(w, d, ro, ocfg, T, rec)
+    parity.check_gae(rec["reward"], rec["value"], rec["done"], w.gamma, w.lam, parity.to_np(adv), parity.to_np(ret))
+
+
+def test_rollout_free_running_tiny_fp32():
+    """Both sides run the whole loop from the same inputs; integers agree until
+    the first site the checker flags as a rounding boundary."""
+    w = inputs.WORKLOADS["tiny"]
+    d, ro, ocfg = _make(w)
+    T = w.steps
+    out = ro.alloc_buffers(T, value=True, logp=True, mu=True, shares=True)
+    ro.step_T(T, torch.from_numpy(d["noise"]).to(DEV), out)
+    torch.cuda.synchronize()
+    rec = _rec(out)
+    chk, _ = oracle.rollout(ocfg, w.hidden, False, T, d["price"], d["ind"], d["noise"], actor=d["actor"],
+                            critic=d["critic"])
+    alive = np.ones(w.n_envs, bool)
+    compared = 0
+    for t in range(T):
+        same = (rec["shares"][t] == chk["shares"][t]).all(axis=1)
+        flagged = (chk["flags"][t] != 0).any(axis=1)
+        assert (same | flagged | ~alive).all(), f"unflagged share mismatch at t={t}"
+        alive &= same
+        compared += int(alive.sum())
+        a = alive
+        np.testing.assert_allclose(rec["mu"][t][a], chk["mu"][t][a], rtol=2e-4, atol=2e-6)
+        np.testing.assert_allclose(rec["value"][t][a], chk["value"][t][a], rtol=2e-4, atol=2e-6)
+    assert compared > 0.9 * T * w.n_envs
+
+
+def test_rollout_is_deterministic():
+    w = inputs.WORKLOADS["dow30"].replace(n_envs=192, steps=12)
+    d, ro, _ = _make(w, horizon=12)
+    noise = torch.from_numpy(d["noise"]).to(DEV)
+    a = ro.step_T(12, noise, ro.alloc_buffers(12, mu=True, shares=True))
+    ro.reset()
+    b = ro.step_T(12, noise, ro.alloc_buffers(12, mu=True, shares=True))
+    torch.cuda.synchronize()
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+
+
+def test_tournament_population_and_leaderboard():
+    # 4 agents x 64 envs, short episodes so every env finishes several
+    w = inputs.WORKLOADS["tournament"].replace(n_envs=256, n_agents=4, steps=24, hidden=64)
+    H = 8
+    d, ro, ocfg = _make(w, horizon=H)
+    T = 24
+    out = ro.alloc_buffers(T, value=True, logp=True, mu=True, shares=True)
+    ro.step_T(T, torch.from_numpy(d["noise"]).to(DEV), out)
+    mean, var, rank = ro.leaderboard()
+    torch.cuda.synchronize()
+    rec = _rec(out)
+    agent_of = (np.arange(w.n_envs) // (w.n_envs // w.n_agents)).astype(np.int32)
+    chk, st = parity.check_env_record(w, ocfg, rec, d["price"], d["ind"], d["noise"], rec["mu"], agent_of=agent_of)
+    rng = np.random.default_rng(4)
+    for g in range(w.n_agents):
+        envs = g * 64 + rng.permutation(64)[:6]
+        obs = rec["obs"][3][envs]
+        parity.check_networks(w, d["actor"], d["critic"], obs, rec["mu"][3][envs], rec["value"][3][envs], agent=g)
+    m, v, r = oracle.leaderboard(w.n_agents, agent_of, st.ep_sum, st.ep_sqsum, st.ep_cnt)
+    np.testing.assert_allclose(parity.to_np(mean), m, rtol=1e-9)
+    np.testing.assert_allclose(parity.to_np(var), v, rtol=1e-6, atol=1e-12)
+    assert parity.to_np(rank).tolist() == r.tolist()
+    assert (st.ep_cnt == T // H).all()
+
+
+def test_leaderboard_ties_and_unfinished_agents():
+    w = inputs.WORKLOADS["tiny"].replace(n_envs=256, n_agents=4, steps=4)
+    d, ro, _ = _make(w, horizon=50)
+    st = ro.get_state()
+    N = w.n_envs
+    ep_sum = torch.zeros(N, dtype=torch.float64, device=DEV)
+    ep_sq = torch.zeros(N, dtype=torch.float64, device=DEV)
+    cnt = torch.zeros(N, dtype=torch.int32, device=DEV)
+    # agents 1 and 2 tie exactly, agent 0 is worse, agent 3 finished nothing
+    ep_sum[0:64] = -1.0
+    ep_sq[0:64] = 1.0
+    cnt[0:64] = 1
+    ep_sum[64:192] = 2.5
+    ep_sq[64:192] = 6.25
+    cnt[64:192] = 1
+    st.update(ep_sum=ep_sum, ep_sqsum=ep_sq, ep_count=cnt)
+    ro.set_state(st)
+    mean, var, rank = ro.leaderboard()
+    torch.cuda.synchronize()
+    assert parity.to_np(rank).tolist() == [1, 2, 0, 3]
+    assert parity.to_np(mean).tolist() == [-1.0, 2.5, 2.5, -np.inf]
+    assert parity.to_np(var).tolist() == [0.0, 0.0, 0.0, 0.0]

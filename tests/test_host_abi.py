@@ -1,0 +1,96 @@
+"""Host-only checks of the C-ABI library: it loads, exports every function the
+header declares, and rejects bad arguments before touching a device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2112_05923_amd import inputs, podrollout as pr
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "podrollout.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = re.findall(r"^\s*(?:int|const char \*)\s*\**(\w+)\s*\(", src, flags=re.M)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_entry_point():
+    names = _declared()
+    assert {"rollout_init", "rollout_step_T", "compute_gae"} <= set(names)
+    assert sorted(pr.EXPORTS) == names
+    lib = pr.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_sizes_match_header_layout():
+    assert C.sizeof(pr.PrConfig) == 9 * 4 + 5 * 4 + 4 * 4
+    assert C.sizeof(pr.PrBuffers) == 8 * 8 and C.sizeof(pr.PrState) == 7 * 8 and C.sizeof(pr.PrWeights) == 6 * 8
+
+
+def test_strerror():
+    lib = pr.lib()
+    assert lib.rollout_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert lib.rollout_strerror(code)
+
+
+def _ws(cfg):
+    n = C.c_size_t(0)
+    return pr.lib().rollout_workspace_bytes(C.byref(cfg), C.byref(n)), n.value
+
+
+def test_workspace_query_and_config_validation():
+    w = inputs.WORKLOADS["large"]
+    rc, n = _ws(pr.make_config(w))
+    assert rc == pr.PR_OK and n > 16384 * 30 * 8
+    for name in inputs.WORKLOADS:
+        rc, n = _ws(pr.make_config(inputs.WORKLOADS[name]))
+        assert rc == pr.PR_OK, name
+    bad = [dict(n_envs=0), dict(n_agents=3), dict(n_stocks=0), dict(n_ind=-1), dict(horizon=0), dict(n_market=7),
+           dict(mlp_dtype=2), dict(schedule=5), dict(cash0=0.0), dict(hmax=-1.0), dict(cost=1.0), dict(cost=-0.1),
+           dict(sigma=0.0)]
+    for kw in bad:
+        cfg = pr.make_config(w)
+        for k, v in kw.items():
+            setattr(cfg, k, v)
+        rc, _ = _ws(cfg)
+        assert rc == pr.PR_EINVAL, kw
+    cfg = pr.make_config(w)
+    cfg.obs_scale[1] = 0.3          # not a power of two
+    assert _ws(cfg)[0] == pr.PR_EINVAL
+    cfg = pr.make_config(w)
+    cfg.hidden = 100                # not a multiple of 32
+    assert _ws(cfg)[0] == pr.PR_EUNSUPPORTED
+    cfg = pr.make_config(w.replace(n_agents=16384 // 32))   # 32 envs per agent: tiles would straddle agents
+    assert _ws(cfg)[0] == pr.PR_EUNSUPPORTED
+    assert pr.lib().rollout_workspace_bytes(None, None) == pr.PR_EINVAL
+
+
+def test_null_arguments_are_rejected_without_device_work():
+    lib = pr.lib()
+    cfg = pr.make_config(inputs.WORKLOADS["tiny"])
+    h = C.c_void_p()
+    m, wa = pr.PrMarket(), pr.PrWeights()
+    assert lib.rollout_init(C.byref(cfg), C.byref(m), C.byref(wa), C.byref(wa), None, 0, None, C.byref(h)) == pr.PR_EINVAL
+    assert not h.value
+    assert lib.rollout_init(C.byref(cfg), None, None, None, None, 0, None, None) == pr.PR_EINVAL
+    assert lib.rollout_step_T(None, 4, None, None) == pr.PR_EINVAL
+    assert lib.rollout_step_forced(None, 4, None, None, None) == pr.PR_EINVAL
+    assert lib.rollout_mlp_forward(None, 0, 1, None, 1, None) == pr.PR_EINVAL
+    assert lib.rollout_reset(None) == pr.PR_EINVAL
+    assert lib.rollout_destroy(None) == pr.PR_EINVAL
+    assert lib.rollout_leaderboard(None, None, None, None) == pr.PR_EINVAL
+    assert lib.compute_gae(None, 0, 4, None, None, None, 0.99, 0.95, None, None) == pr.PR_EINVAL
+    assert lib.compute_gae(None, 4, 4, None, None, None, 0.99, 0.95, None, None) == pr.PR_EINVAL
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(pr, "_lib", None)
+    monkeypatch.setattr(pr, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libpodrollout.so"))
+    with pytest.raises(FileNotFoundError):
+        pr.lib()
