@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Throughput of the whole rollout hot path on one MI355X.
+
+One "step" = one pass of the path over one batch of synthetic input: T steps of
+{actor forward, Gaussian sampling, trading-env step} for N envs, the critic on
+all T+1 observations, and GAE -- the three C-ABI calls rollout_step_T (without
+values), rollout_mlp_forward (critic on the whole observation buffer, the same
+launch rollout_step_T makes when given a value buffer) and compute_gae, issued
+back to back with HIP events between them so that each stage is timed inside
+the timed region.  Inputs are resident in HBM before the clock starts.
+
+Prints ONE JSON line (metric env-steps/s) with a roofline object for the
+dominant kernel and the CPU checker's rate on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import concurrent.futures as cf
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "mfma_fp32": (157.3, "TFLOP/s")}
+
+
+def kernel_sources_digest() -> str:
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2112_05923_amd", "csrc")
+    for f in sorted(os.listdir(csrc)):
+        h.update(open(os.path.join(csrc, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def recorded_traffic(kernel: str, workload: str):
+    """HBM bytes per launch from the committed counter summary, or None when the
+    kernel sources changed after the counters were taken."""
+    path = os.path.join(ROOT, "profiles", f"pmc_{kernel}_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if ":" in line and not line.startswith("#"):
+            k, v = line.split(":", 1)
+            vals[k.strip()] = v.strip()
+    if vals.get("kernel_sources_digest") != kernel_sources_digest():
+        return None
+    try:
+        return float(vals["hbm_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
+def cpu_baseline(w, n_envs: int, steps: int, threads: int):
+    """The CPU checker as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    from paper_2112_05923_amd import inputs
+
+    ws = w.replace(n_envs=n_envs, steps=steps)
+    d = inputs.make_all(ws)
+    cfg = oracle.cfg_from_workload(ws)
+    chunks = np.array_split(np.arange(n_envs), threads)
+
+    def work(idx):
+        if idx.size == 0:
+            return 0
+        out, _ = oracle.rollout(cfg, ws.hidden, bool(ws.mlp_dtype), steps, d["price"][:, idx], d["ind"][:, idx],
+                                d["noise"][:, idx], actor=d["actor"], critic=d["critic"],
+                                want=("obs", "act_raw", "logp", "reward", "done", "value"))
+        oracle.gae(out["reward"], out["value"], out["done"], ws.gamma, ws.lam)
+        return idx.size
+
+    oracle.lib()
+    t0 = time.perf_counter()
+    with cf.ThreadPoolExecutor(max_workers=threads) as ex:
+        done = sum(ex.map(work, chunks))
+    dt = time.perf_counter() - t0
+    return {"value": done * steps / dt, "unit": "env-steps/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n_envs} envs x {steps} steps of workload '{w.name}' (free-running rollout + critic + GAE), "
+                      f"{dt:.1f} s wall"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="large")
+    ap.add_argument("--schedule", default="stepwise", choices=["stepwise", "fused"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-envs", type=int, default=192)
+    ap.add_argument("--cpu-steps", type=int, default=1024)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (envs shard trivially across GPUs; no multi-GPU "
+                 "path is built or measured). Use --gpus 1.")
+
+    import torch
+    from paper_2112_05923_amd import inputs, podrollout as pr
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    dev = torch.device("cuda:0")
+    w = inputs.WORKLOADS[args.workload]
+    T, N, D, S = w.steps, w.n_envs, w.n_stocks, w.state_dim
+    d = inputs.make_all_device(w, dev)
+    sched = pr.PR_SCHED_FUSED if args.schedule == "fused" else pr.PR_SCHED_STEPWISE
+    ro = pr.Rollout(pr.make_config(w, schedule=sched), d["price"], d["ind"], d["actor"], d["critic"])
+    out = ro.alloc_buffers(T, value=True, logp=True, mu=False, shares=False)
+    roll = dict(out)
+    roll["value"] = None
+    adv = torch.empty((T, N), dtype=torch.float32, device=dev)
+    ret = torch.empty((T, N), dtype=torch.float32, device=dev)
+    obs2d = out["obs"].view((T + 1) * N, S)
+    val2d = out["value"].view((T + 1) * N, 1)
+
+    def one_step(ev=None):
+        ro.reset()
+        if ev:
+            ev[0].record()
+        ro.step_T(T, d["noise"], roll)
+        if ev:
+            ev[1].record()
+        ro.mlp_forward(pr.PR_NET_CRITIC, obs2d, val2d)
+        if ev:
+            ev[2].record()
+        pr.compute_gae(out["reward"], out["value"], out["done"], w.gamma, w.lam, adv, ret)
+        if ev:
+            ev[3].record()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        one_step(events[k])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ms = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in events) / args.steps
+    t_roll, t_critic, t_gae = ms(0, 1), ms(1, 2), ms(2, 3)
+    env_steps = N * T
+    value = env_steps * args.steps / dt
+
+    flops_actor = inputs.mlp_flops_per_env_step(w, critic=False) * env_steps
+    flops_critic = inputs.mlp_flops_per_env_step(w, critic=True) * (T + 1) * N
+    env_bytes = inputs.bytes_per_env_step(w) * env_steps
+    gae_bytes = 17 * env_steps
+    mf = "mfma_bf16" if w.mlp_dtype else "mfma_fp32"
+    stages = {
+        "rollout_T": {"ms": t_roll, "actor_TFLOPs": flops_actor / t_roll / 1e9,
+                      "env_algorithmic_GBps": env_bytes / t_roll / 1e6},
+        "critic": {"ms": t_critic, "TFLOPs": flops_critic / t_critic / 1e9, "frac_mfma": flops_critic / t_critic / 1e9 / PEAK[mf][0]},
+        "gae": {"ms": t_gae, "GBps": gae_bytes / t_gae / 1e6, "frac_hbm": gae_bytes / t_gae / 1e6 / PEAK["hbm"][0]},
+    }
+    # dominant kernel: the single launch that takes the largest share of a step
+    if args.schedule == "fused":
+        dom = {"kernel": "rollout_fused_kernel", "bound": "mfma", "achieved": flops_actor / t_roll / 1e9,
+               "peak": PEAK[mf][0], "unit": "TFLOP/s", "ms_per_launch": t_roll}
+    else:
+        dom = {"kernel": "mlp3_kernel(critic, whole buffer)", "bound": "mfma", "achieved": flops_critic / t_critic / 1e9,
+               "peak": PEAK[mf][0], "unit": "TFLOP/s", "ms_per_launch": t_critic}
+    dom["frac"] = dom["achieved"] / dom["peak"]
+    dom["traffic"] = recorded_traffic("fused" if args.schedule == "fused" else "critic", w.name)
+
+    res = {
+        "metric": "env-steps/sec (transitions/s) on 1 MI355X; achieved HBM GB/s and MFMA %",
+        "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.mlp_dtype else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: N={N} envs, D={D} stocks, K={w.n_ind} indicators, T={T} steps, "
+                               f"MLP {S}-{w.hidden}-{w.hidden}-{{{D},1}}", "schedule": args.schedule,
+                   "env_steps_per_step": env_steps},
+        "roofline": dom,
+        "stages": stages,
+    }
+    if not args.no_cpu_baseline:
+        threads = min(16, os.cpu_count() or 1)
+        res["cpu_baseline"] = cpu_baseline(w, args.cpu_envs, min(args.cpu_steps, T), threads)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

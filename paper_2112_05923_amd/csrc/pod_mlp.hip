@@ -268,7 +268,9 @@ __device__ inline void epilogue_to_global(const f32x16 (&acc)[RT][CT], const flo
   }
 }
 
-template <bool BF16, int RT, int CTH, int CTO>
+// TAG only separates the symbol of the per-step launches (0) from that of the
+// whole-buffer launches (1) so that a profiler reports them as two kernels.
+template <bool BF16, int RT, int CTH, int CTO, int TAG>
 __global__ __launch_bounds__(kThreads) void mlp3_kernel(MlpArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int BM = 32 * RT;
@@ -406,9 +408,9 @@ hipError_t launch_pack_layer(hipStream_t st, const float *W, const float *b, int
   return hipGetLastError();
 }
 
-template <bool BF16, int CTH, int CTO>
-static hipError_t launch_one(hipStream_t st, const MlpArgs &a, unsigned blocks, size_t lds) {
-  auto kern = mlp3_kernel<BF16, 2, CTH, CTO>;
+template <bool BF16, int CTH, int CTO, int TAG>
+static hipError_t launch_tagged(hipStream_t st, const MlpArgs &a, unsigned blocks, size_t lds) {
+  auto kern = mlp3_kernel<BF16, 2, CTH, CTO, TAG>;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -418,6 +420,12 @@ static hipError_t launch_one(hipStream_t st, const MlpArgs &a, unsigned blocks, 
   }
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(kThreads), lds, st, a);
   return hipGetLastError();
+}
+
+template <bool BF16, int CTH, int CTO>
+static hipError_t launch_one(hipStream_t st, const MlpArgs &a, unsigned blocks, size_t lds) {
+  return a.rows > a.N ? launch_tagged<BF16, CTH, CTO, 1>(st, a, blocks, lds)
+                      : launch_tagged<BF16, CTH, CTO, 0>(st, a, blocks, lds);
 }
 
 hipError_t launch_mlp(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx, float *Y,
