@@ -18,6 +18,7 @@
 // feeds row/column (l % 32) and the k-half (l / 32) of a k-block: 16 bytes per
 // lane and operand.
 #include "pod_internal.h"
+#include "pod_tile.h"
 
 namespace pod {
 
@@ -85,6 +86,7 @@ struct MlpArgs {
   float *Y;
   PackedNet net;
   int32_t N, envs_per_agent;
+  int64_t row_offset;  // global index of row 0 of X (agent lookup when a tail is launched on its own)
   int32_t xpitch;   // bytes per row of one staged X chunk
   int32_t hpitch;   // bytes per row of the hidden tile
 };
@@ -282,7 +284,7 @@ __global__ __launch_bounds__(kThreads) void mlp3_kernel(MlpArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int64_t row0 = (int64_t)blockIdx.x * BM;
   const int nrows = (int)min((int64_t)BM, a.rows - row0);
-  const int agent = (int)((row0 % a.N) / a.envs_per_agent);
+  const int agent = (int)(((row0 + a.row_offset) % a.N) / a.envs_per_agent);
   const PackedNet &net = a.net;
   const u32x4 *W1 = reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(net.W[0]) +
                                                     (size_t)agent * net.w_stride[0]);
@@ -317,6 +319,103 @@ __global__ __launch_bounds__(kThreads) void mlp3_kernel(MlpArgs a) {
       layer_from_lds<BF16, RT, CTO, PDO>(acc, ldsH, a.hpitch, net.nkb[2], W3, cto0, net.nct[2], lane);
       epilogue_to_global<RT, CTO>(acc, b3, a.Y, row0, nrows, net.out_dim[2], net.out_tanh, cto0, net.nct[2], lane);
     }
+  }
+}
+
+
+// ------------------------------------------------ persistent whole-tile kernel
+// Used when the rows of X are dense (ldx == S) and a whole 64 x S tile fits in
+// LDS next to the hidden tile.  Each workgroup walks tiles blockIdx.x,
+// blockIdx.x + gridDim.x, ...; the next tile's rows are fetched into registers
+// as flat 16-byte loads (a tile of dense rows is one contiguous segment) while
+// the current tile is in the matrix cores, and dropped into the LDS input tile
+// as soon as layer 1 has finished reading it.
+constexpr int XPRE_MAX = 20;  // 16-byte loads per thread and tile: covers S <= 320
+
+struct TileArgs {
+  const float *X;
+  int64_t rows;
+  float *Y;
+  PackedNet net;
+  int32_t N, envs_per_agent;
+  int32_t S, s_magic;  // s_magic = ceil(2^32 / S): e / S == umulhi(e, s_magic) for e < 2^32 / S
+  int32_t xpitch, hpitch;
+};
+
+template <bool BF16, int CTH, int TAG>
+__global__ __launch_bounds__(tile::kThreads) void mlp_tiles_kernel(TileArgs a) {
+  using namespace tile;
+  using O = tile::Op<BF16>;
+  extern __shared__ __align__(16) unsigned char lds[];
+  unsigned char *ldsH = lds;
+  unsigned char *ldsX = lds + (size_t)BM * a.hpitch;
+  const int tid = threadIdx.x;
+  const int S = a.S;
+  const int64_t ntiles = a.rows / BM;  // a.rows is a multiple of BM
+  const int nx = (BM * S / 4 + kThreads - 1) / kThreads;  // 16-byte loads per thread for a full tile
+
+  for (int i = tid; i < BM * a.xpitch / 4; i += kThreads) reinterpret_cast<uint32_t *>(ldsX)[i] = 0u;
+  __syncthreads();
+
+  // Full tiles only (the launcher sends a ragged tail to the chunked kernel): a tile is BM * S floats,
+  // a multiple of four, so every 16-byte load is either wholly inside the tile or wholly outside.
+  f32x4 pre[XPRE_MAX];
+  const int nelem = BM * S;
+  auto fetch = [&](int64_t t) {
+    const float *src = a.X + t * BM * S;
+#pragma unroll
+    for (int i = 0; i < XPRE_MAX; ++i) {
+      if (i < nx) {
+        const int e0 = 4 * (tid + kThreads * i);
+        if (e0 < nelem) pre[i] = *reinterpret_cast<const f32x4 *>(src + e0);
+      }
+    }
+  };
+  auto stash = [&]() {
+    // the LDS addresses are loop invariant; recompute them per call instead of letting the compiler keep
+    // eighty of them in registers across the matrix-core loops
+    int tid_opaque = tid;
+    asm volatile("" : "+v"(tid_opaque));
+#pragma unroll
+    for (int i = 0; i < XPRE_MAX; ++i) {
+      if (i < nx) {
+        const int e0 = 4 * (tid_opaque + kThreads * i);
+        if (e0 < nelem) {
+          int row = (int)__umulhi((unsigned)e0, (unsigned)a.s_magic);
+          int col = e0 - row * S;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            O::store1(ldsX + (size_t)row * a.xpitch + col * O::ESZ, pre[i][j]);
+            if (++col == S) {
+              col = 0;
+              ++row;
+            }
+          }
+        }
+      }
+    }
+  };
+
+  int64_t t = blockIdx.x;
+  if (t < ntiles) {
+    fetch(t);
+    stash();
+  }
+  for (; t < ntiles; t += gridDim.x) {
+    const int64_t row0 = t * BM;
+    const int64_t tn = t + gridDim.x;
+    const bool more = tn < ntiles;
+    if (more) fetch(tn);
+    __syncthreads();  // input tile complete; previous tile's output layer is done with ldsH
+    const Net net = net_of(a.net, (int)((row0 % a.N) / a.envs_per_agent));
+    const int O_dim = net.out_dim;
+    float *Y = a.Y + row0 * O_dim;
+    mlp_tile<BF16, CTH, false>(
+        net, ldsX, a.xpitch, ldsH, a.hpitch, tid,
+        [&]() {
+          if (more) stash();
+        },
+        [&](int b, int f, float y) { Y[(size_t)b * O_dim + f] = y; });
   }
 }
 
@@ -428,11 +527,90 @@ static hipError_t launch_one(hipStream_t st, const MlpArgs &a, unsigned blocks, 
                       : launch_tagged<BF16, CTH, CTO, 0>(st, a, blocks, lds);
 }
 
+
+template <bool BF16, int CTH, int TAG>
+static hipError_t launch_tiles_tagged(hipStream_t st, const TileArgs &a, unsigned blocks, size_t lds) {
+  auto kern = mlp_tiles_kernel<BF16, CTH, TAG>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(tile::kThreads), lds, st, a);
+  return hipGetLastError();
+}
+
+template <bool BF16, int CTH>
+static hipError_t launch_tiles(hipStream_t st, const TileArgs &a, unsigned blocks, size_t lds) {
+  return a.rows > a.N ? launch_tiles_tagged<BF16, CTH, 1>(st, a, blocks, lds)
+                      : launch_tiles_tagged<BF16, CTH, 0>(st, a, blocks, lds);
+}
+
+int compute_units() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      n = prop.multiProcessorCount;
+    if (n <= 0) n = 256;
+  }
+  return n;
+}
+
+// The whole-tile kernel covers dense rows with S <= 320 and hidden widths up to 512.
+static bool try_launch_tiles(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx, float *Y,
+                             int32_t N, int32_t envs_per_agent, const Shape &s, hipError_t *err) {
+  const int S = net.in_dim[0];
+  if (ldx != S || (reinterpret_cast<uintptr_t>(X) & 15u) || s.cth > 4 || net.nct[2] != 1) return false;
+  if ((tile::BM * S / 4 + tile::kThreads - 1) / tile::kThreads > XPRE_MAX) return false;
+  const int esz = net.bf16 ? 2 : 4, KB = kblock(net.bf16);
+  TileArgs a;
+  a.X = X;
+  a.rows = rows;
+  a.Y = Y;
+  a.net = net;
+  a.N = N;
+  a.envs_per_agent = envs_per_agent;
+  a.S = S;
+  a.s_magic = (int32_t)(uint32_t)((0x100000000ull + (uint64_t)S - 1) / (uint64_t)S);
+  a.xpitch = tile::tile_pitch(net.nkb[0] * KB, esz);
+  a.hpitch = tile::tile_pitch(net.out_dim[0], esz);
+  const size_t lds = (size_t)tile::BM * (a.xpitch + a.hpitch);
+  if (lds > 160 * 1024) return false;
+  const int64_t ntiles = (rows + tile::BM - 1) / tile::BM;
+  const unsigned blocks = (unsigned)(ntiles < compute_units() ? ntiles : compute_units());
+  const bool bf = net.bf16 != 0;
+  if (bf && s.cth == 1) *err = launch_tiles<true, 1>(st, a, blocks, lds);
+  else if (bf && s.cth == 2) *err = launch_tiles<true, 2>(st, a, blocks, lds);
+  else if (bf && s.cth == 4) *err = launch_tiles<true, 4>(st, a, blocks, lds);
+  else if (!bf && s.cth == 1) *err = launch_tiles<false, 1>(st, a, blocks, lds);
+  else if (!bf && s.cth == 2) *err = launch_tiles<false, 2>(st, a, blocks, lds);
+  else if (!bf && s.cth == 4) *err = launch_tiles<false, 4>(st, a, blocks, lds);
+  else return false;
+  return true;
+}
+
 hipError_t launch_mlp(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx, float *Y,
                       int32_t N, int32_t envs_per_agent) {
   Shape s;
   if (!pick_shape(net.out_dim[0], net.out_dim[2], net.bf16, &s)) return hipErrorInvalidValue;
   constexpr int BM = 64;
+  int64_t row_offset = 0;
+  if (rows >= BM) {
+    // full tiles through the persistent whole-tile kernel when it covers the shape; the ragged tail below
+    hipError_t terr = hipSuccess;
+    const int64_t full = rows / BM * BM;
+    if (try_launch_tiles(st, net, full, X, ldx, Y, N, envs_per_agent, s, &terr)) {
+      if (terr != hipSuccess || full == rows) return terr;
+      X += full * ldx;
+      Y += full * net.out_dim[2];
+      row_offset = full;
+      rows -= full;
+    }
+  }
   const int esz = net.bf16 ? 2 : 4, KB = kblock(net.bf16);
   const int pd = s.cth >= 8 ? 2 : 4;
   MlpArgs a;
@@ -443,6 +621,7 @@ hipError_t launch_mlp(hipStream_t st, const PackedNet &net, int64_t rows, const 
   a.net = net;
   a.N = N;
   a.envs_per_agent = envs_per_agent;
+  a.row_offset = row_offset;
   a.xpitch = pd * KB * esz + 16;
   a.hpitch = net.out_dim[0] * esz + 16;
   const size_t lds = (size_t)BM * a.hpitch + 2 * (size_t)BM * a.xpitch;

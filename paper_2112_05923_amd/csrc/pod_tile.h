@@ -1,0 +1,289 @@
+// Matrix-core building blocks for one 64-row batch tile of the 3-layer
+// perceptron (actor / critic networks, Sec. 4.1 and 4.2 of the paper), shared
+// by the batched forward kernel and the persistent rollout kernel.
+//
+// Formulation.  Every layer is computed transposed, C^T = W^T * A^T: the packed
+// weights are the MFMA "A" operand (32 output features x k-block) and the
+// activation tile in LDS is the "B" operand (k-block x 32 batch rows).  In the
+// 32x32 accumulator a lane then owns ONE batch row (l % 32) and, per group
+// j = 0..3, FOUR CONSECUTIVE output features 8 j + 4 (l / 32) + {0..3}.  Four
+// consecutive features are four consecutive k of the next layer, so the
+// epilogue packs them and writes them with a single 8-byte (bf16) or 16-byte
+// (fp32) LDS store into the row-major [batch][feature] tile the next layer
+// reads its B operand from.
+//
+// The four wavefronts of a workgroup split the output features; each streams
+// its own weight blocks from global/L2 through a small register ring that is
+// primed for the next layer before the current layer's epilogue starts.
+#pragma once
+
+#include "pod_internal.h"
+
+namespace pod {
+namespace tile {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kWaves = 4;
+constexpr int kThreads = kWaves * 64;
+constexpr int BM = 64;  // batch rows per tile (two 32-row MFMA tiles)
+
+template <bool BF16>
+struct Op;
+
+template <>
+struct Op<true> {
+  static constexpr int KB = 16;
+  static constexpr int ESZ = 2;
+  // acc += W_block (features x k) * X_block (k x batch)
+  static __device__ inline void mma(const u32x4 &w, const u32x4 &x, f32x16 &c) {
+    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x), c, 0, 0,
+                                                0);
+  }
+  static __device__ inline void store1(unsigned char *p, float v) { *reinterpret_cast<__bf16 *>(p) = (__bf16)v; }
+  static __device__ inline void store4(unsigned char *p, float a, float b, float c, float d) {
+    bf16x4 v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
+    *reinterpret_cast<u32x2 *>(p) = __builtin_bit_cast(u32x2, v);
+  }
+};
+
+template <>
+struct Op<false> {
+  static constexpr int KB = 8;
+  static constexpr int ESZ = 4;
+  static __device__ inline void mma(const u32x4 &w, const u32x4 &x, f32x16 &c) {
+    const f32x4 wf = __builtin_bit_cast(f32x4, w), xf = __builtin_bit_cast(f32x4, x);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[0], xf[0], c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[1], xf[1], c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[2], xf[2], c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[3], xf[3], c, 0, 0, 0);
+  }
+  static __device__ inline void store1(unsigned char *p, float v) { *reinterpret_cast<float *>(p) = v; }
+  static __device__ inline void store4(unsigned char *p, float a, float b, float c, float d) {
+    f32x4 v = {a, b, c, d};
+    *reinterpret_cast<f32x4 *>(p) = v;
+  }
+};
+
+constexpr float kTwoLog2e = 2.8853900817779268f;
+
+// tanh to a few 1e-7 relative: odd Taylor polynomial below 1/4, 1 - 2/(e^{2|x|}+1) above.
+__device__ inline float tanh_accurate(float x) {
+  const float ax = fabsf(x);
+  const float x2 = x * x;
+  float ps = fmaf(x2, 62.0f / 2835.0f, -17.0f / 315.0f);
+  ps = fmaf(x2, ps, 2.0f / 15.0f);
+  ps = fmaf(x2, ps, -1.0f / 3.0f);
+  const float small = fmaf(x2 * x, ps, x);
+  const float e = __builtin_amdgcn_exp2f(ax * kTwoLog2e);
+  const float big = copysignf(1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f), x);
+  return ax < 0.25f ? small : big;
+}
+
+// tanh(z) from t = z * 2 log2(e); ~1e-7 absolute, for results that are rounded to bf16.
+__device__ inline float tanh_from_scaled(float t) {
+  const float e = __builtin_amdgcn_exp2f(t);
+  return fmaf(-2.0f, __builtin_amdgcn_rcpf(e + 1.0f), 1.0f);
+}
+
+// One agent's packed network (pointers already offset to the agent).
+struct Net {
+  const u32x4 *W[3];
+  const float *b[3];
+  int nkb[3], nct[3];
+  int out_dim, out_tanh;
+};
+
+__device__ inline Net net_of(const PackedNet &p, int agent) {
+  Net n;
+#pragma unroll
+  for (int l = 0; l < 3; ++l) {
+    n.W[l] = reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(p.W[l]) +
+                                             (size_t)agent * p.w_stride[l]);
+    n.b[l] = p.b[l] + (size_t)agent * p.b_stride[l];
+    n.nkb[l] = p.nkb[l];
+    n.nct[l] = p.nct[l];
+  }
+  n.out_dim = p.out_dim[2];
+  n.out_tanh = p.out_tanh;
+  return n;
+}
+
+// Weight block (feature tile ct, k-block kb) for this lane.
+__device__ inline u32x4 load_w(const u32x4 *W, int nkb, int ct, int kb, int lane) {
+  return W[((size_t)ct * nkb + kb) * 64 + lane];
+}
+
+// Fill the ring with k-blocks 0..PD-1 of a layer (feature tiles ct0..ct0+CT-1, clamped to the last tile).
+template <int CT, int PD>
+__device__ inline void prime(u32x4 (&ring)[PD][CT], const u32x4 *W, int nkb, int nct, int ct0, int lane) {
+#pragma unroll
+  for (int s = 0; s < PD; ++s)
+    if (s < nkb) {
+#pragma unroll
+      for (int c = 0; c < CT; ++c) ring[s][c] = load_w(W, nkb, min(ct0 + c, nct - 1), s, lane);
+    }
+}
+
+// acc[c][t] += W(feature tile ct0 + c) * X(batch tile bt0 + t) over all k-blocks.  The activation tile is
+// row-major [batch][k] in LDS with `pitch` bytes per row.  The ring must be primed for this layer.
+template <bool BF16, int CT, int NBT, int PD>
+__device__ inline void mma_layer(f32x16 (&acc)[CT][NBT], u32x4 (&ring)[PD][CT], const unsigned char *ldsX, int pitch,
+                                 int nkb, const u32x4 *W, int nct, int ct0, int bt0, int lane) {
+  using O = Op<BF16>;
+  const int brow = lane & 31, g = lane >> 5;
+  const unsigned char *xbase = ldsX + (size_t)(bt0 * 32 + brow) * pitch + 16 * g;
+  for (int kb0 = 0; kb0 < nkb; kb0 += PD) {
+#pragma unroll
+    for (int s = 0; s < PD; ++s) {
+      const int kb = kb0 + s;
+      if (kb < nkb) {
+        u32x4 x[NBT];
+#pragma unroll
+        for (int t = 0; t < NBT; ++t)
+          x[t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)t * 32 * pitch + kb * 32);
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+#pragma unroll
+          for (int t = 0; t < NBT; ++t) O::mma(ring[s][c], x[t], acc[c][t]);
+        if (kb + PD < nkb) {
+#pragma unroll
+          for (int c = 0; c < CT; ++c) ring[s][c] = load_w(W, nkb, min(ct0 + c, nct - 1), kb + PD, lane);
+        }
+      }
+    }
+  }
+}
+
+template <int CT, int NBT>
+__device__ inline void zero_acc(f32x16 (&acc)[CT][NBT]) {
+#pragma unroll
+  for (int c = 0; c < CT; ++c)
+#pragma unroll
+    for (int t = 0; t < NBT; ++t)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[c][t][i] = 0.0f;
+}
+
+// hidden = tanh(acc + bias) -> row-major [batch][feature] LDS tile in the operand type.
+template <bool BF16, int CT, int NBT>
+__device__ inline void epilogue_hidden(const f32x16 (&acc)[CT][NBT], const float *bias, unsigned char *ldsH,
+                                       int hpitch, int nct, int ct0, int bt0, int lane) {
+  using O = Op<BF16>;
+  const int brow = lane & 31, g = lane >> 5;
+#pragma unroll
+  for (int c = 0; c < CT; ++c) {
+    if (ct0 + c < nct) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int f0 = (ct0 + c) * 32 + 8 * j + 4 * g;
+        const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias + f0);
+#pragma unroll
+        for (int t = 0; t < NBT; ++t) {
+          float h[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            if (BF16)
+              h[i] = tanh_from_scaled(fmaf(acc[c][t][4 * j + i], kTwoLog2e, bv[i] * kTwoLog2e));
+            else
+              h[i] = tanh_accurate(acc[c][t][4 * j + i] + bv[i]);
+          }
+          O::store4(ldsH + (size_t)((bt0 + t) * 32 + brow) * hpitch + f0 * O::ESZ, h[0], h[1], h[2], h[3]);
+        }
+        // keep the scheduler from interleaving all groups at once (it would need a register per value)
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+}
+
+// Last layer: y = acc + bias (tanh for the actor) handed to sink(batch_row_in_tile, feature, value).
+template <int CT, int NBT, class Sink>
+__device__ inline void epilogue_out(const f32x16 (&acc)[CT][NBT], const float *bias, int out_dim, int out_tanh,
+                                    int nct, int ct0, int bt0, int lane, Sink sink) {
+  const int brow = lane & 31, g = lane >> 5;
+#pragma unroll
+  for (int c = 0; c < CT; ++c) {
+    if (ct0 + c < nct) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int f0 = (ct0 + c) * 32 + 8 * j + 4 * g;
+        const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias + f0);
+#pragma unroll
+        for (int t = 0; t < NBT; ++t)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float z = acc[c][t][4 * j + i] + bv[i];
+            const float y = out_tanh ? tanh_accurate(z) : z;
+            if (f0 + i < out_dim) sink((bt0 + t) * 32 + brow, f0 + i, y);
+          }
+      }
+    }
+  }
+}
+
+// WIDE_OUT = false: the output layer has at most 32 features (one feature tile).
+// Layers 1-3 for the 64-row tile whose layer-1 input already sits in ldsX (row-major, xpitch bytes per row,
+// padded k columns zero).  ldsH receives the hidden tiles.  `after_l1()` runs once the layer-1 reads of ldsX
+// are complete workgroup-wide (ldsX may be refilled from there on).  Ends without a trailing barrier: the
+// caller must synchronise before ldsH or ldsX are written again.
+template <bool BF16, int CTH, bool WIDE_OUT, class AfterL1, class Sink>
+__device__ inline void mlp_tile(const Net &net, const unsigned char *ldsX, int xpitch, unsigned char *ldsH,
+                                int hpitch, int tid, AfterL1 after_l1, Sink sink) {
+  constexpr int PD = CTH >= 8 ? 2 : 4;
+  const int lane = tid & 63, w = tid >> 6;
+  const int ct0 = w * CTH;
+  const bool act = ct0 < net.nct[0];
+  u32x4 ring[PD][CTH];
+  {
+    f32x16 acc[CTH][2];
+    zero_acc<CTH, 2>(acc);
+    if (act) {
+      prime<CTH, PD>(ring, net.W[0], net.nkb[0], net.nct[0], ct0, lane);
+      mma_layer<BF16, CTH, 2, PD>(acc, ring, ldsX, xpitch, net.nkb[0], net.W[0], net.nct[0], ct0, 0, lane);
+      prime<CTH, PD>(ring, net.W[1], net.nkb[1], net.nct[1], ct0, lane);
+      epilogue_hidden<BF16, CTH, 2>(acc, net.b[0], ldsH, hpitch, net.nct[0], ct0, 0, lane);
+    }
+    __syncthreads();
+    after_l1();
+    zero_acc<CTH, 2>(acc);
+    if (act) mma_layer<BF16, CTH, 2, PD>(acc, ring, ldsH, hpitch, net.nkb[1], net.W[1], net.nct[1], ct0, 0, lane);
+    __syncthreads();  // every wavefront has consumed the layer-1 tile; it is overwritten in place
+    if (act) epilogue_hidden<BF16, CTH, 2>(acc, net.b[1], ldsH, hpitch, net.nct[1], ct0, 0, lane);
+    __syncthreads();
+  }
+  // output layer: few features.  One feature tile: wavefronts 0 and 1 take one 32-row batch tile each.
+  // More feature tiles: split the feature tiles over the wavefronts like the hidden layers.
+  if (!WIDE_OUT) {
+    if (w < 2) {
+      u32x4 r1[4][1];
+      f32x16 acc[1][1];
+      zero_acc<1, 1>(acc);
+      prime<1, 4>(r1, net.W[2], net.nkb[2], 1, 0, lane);
+      mma_layer<BF16, 1, 1, 4>(acc, r1, ldsH, hpitch, net.nkb[2], net.W[2], 1, 0, w, lane);
+      epilogue_out<1, 1>(acc, net.b[2], net.out_dim, net.out_tanh, 1, 0, w, lane, sink);
+    }
+  } else {
+    constexpr int CTO = 4;
+    const int co0 = w * CTO;
+    if (co0 < net.nct[2]) {
+      u32x4 r4[2][CTO];
+      f32x16 acc[CTO][2];
+      zero_acc<CTO, 2>(acc);
+      prime<CTO, 2>(r4, net.W[2], net.nkb[2], net.nct[2], co0, lane);
+      mma_layer<BF16, CTO, 2, 2>(acc, r4, ldsH, hpitch, net.nkb[2], net.W[2], net.nct[2], co0, 0, lane);
+      epilogue_out<CTO, 2>(acc, net.b[2], net.out_dim, net.out_tanh, net.nct[2], co0, 0, lane, sink);
+    }
+  }
+}
+
+// Geometry of the LDS tiles.
+__host__ __device__ inline int tile_pitch(int k_elems_padded, int esz) { return k_elems_padded * esz + 16; }
+
+}  // namespace tile
+}  // namespace pod
