@@ -57,9 +57,10 @@ hipError_t launch_gae(hipStream_t st, int32_t T, int32_t N, const float *reward,
 
 // ---------------------------------------------------------------------- MLP
 // Packed network of one agent set.  Weight blocks are stored in the register
-// layout of the matrix-core instruction: block (ct, kb) holds, for the 64 lanes
-// of a wavefront, the 16 bytes lane l feeds as B operand for output columns
+// layout of the matrix-core instruction: block (kb, ct) holds, for the 64 lanes
+// of a wavefront, the 16 bytes lane l feeds as operand for output features
 // [32 ct, 32 ct + 32) and inputs [KB kb, KB kb + KB); KB = 16 (bf16) or 8 (fp32).
+// Blocks are ordered k-major: [kb][ct][lane].
 struct PackedNet {
   const void *W[3];       // packed weights per layer, agent-major
   const float *b[3];      // biases padded to a multiple of 32, agent-major

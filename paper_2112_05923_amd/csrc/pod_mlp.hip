@@ -92,8 +92,8 @@ struct MlpArgs {
 };
 
 // B-operand block (ct, kb) of a packed layer for this lane.
-__device__ inline u32x4 load_b(const u32x4 *Wp, int nkb, int ct, int kb, int lane) {
-  return Wp[((size_t)ct * nkb + kb) * 64 + lane];
+__device__ inline u32x4 load_b(const u32x4 *Wp, int nct, int ct, int kb, int lane) {
+  return Wp[((size_t)kb * nct + ct) * 64 + lane];
 }
 
 // acc += A(tile in LDS, all k-blocks) * B.  Wavefront-uniform control flow.
@@ -110,7 +110,7 @@ __device__ inline void layer_from_lds(f32x16 (&acc)[RT][CT], const unsigned char
   for (int s = 0; s < PD; ++s)
     if (s < nkb) {
 #pragma unroll
-      for (int c = 0; c < CT; ++c) ring[s][c] = load_b(Wp, nkb, cts[c], s, lane);
+      for (int c = 0; c < CT; ++c) ring[s][c] = load_b(Wp, nct, cts[c], s, lane);
     }
   for (int kb0 = 0; kb0 < nkb; kb0 += PD) {
 #pragma unroll
@@ -127,7 +127,7 @@ __device__ inline void layer_from_lds(f32x16 (&acc)[RT][CT], const unsigned char
           for (int c = 0; c < CT; ++c) O::mma(a[r], ring[s][c], acc[r][c]);
         if (kb + PD < nkb) {
 #pragma unroll
-          for (int c = 0; c < CT; ++c) ring[s][c] = load_b(Wp, nkb, cts[c], kb + PD, lane);
+          for (int c = 0; c < CT; ++c) ring[s][c] = load_b(Wp, nct, cts[c], kb + PD, lane);
         }
       }
     }
@@ -159,7 +159,7 @@ __device__ inline void layer_from_global(f32x16 (&acc)[RT][CT], unsigned char *l
     for (int s = 0; s < PD; ++s)
       if (s < nkb) {
 #pragma unroll
-        for (int c = 0; c < CT; ++c) ring[s][c] = load_b(Wp, nkb, cts[c], s, lane);
+        for (int c = 0; c < CT; ++c) ring[s][c] = load_b(Wp, nct, cts[c], s, lane);
       }
   }
 
@@ -203,7 +203,7 @@ __device__ inline void layer_from_global(f32x16 (&acc)[RT][CT], unsigned char *l
             for (int c = 0; c < CT; ++c) O::mma(a[r], ring[s][c], acc[r][c]);
           if (kb + PD < nkb) {
 #pragma unroll
-            for (int c = 0; c < CT; ++c) ring[s][c] = load_b(Wp, nkb, cts[c], kb + PD, lane);
+            for (int c = 0; c < CT; ++c) ring[s][c] = load_b(Wp, nct, cts[c], kb + PD, lane);
           }
         }
       }
@@ -327,76 +327,85 @@ __global__ __launch_bounds__(kThreads) void mlp3_kernel(MlpArgs a) {
 // Used when the rows of X are dense (ldx == S) and a whole 64 x S tile fits in
 // LDS next to the hidden tile.  Each workgroup walks tiles blockIdx.x,
 // blockIdx.x + gridDim.x, ...; the next tile's rows are fetched into registers
-// as flat 16-byte loads (a tile of dense rows is one contiguous segment) while
-// the current tile is in the matrix cores, and dropped into the LDS input tile
-// as soon as layer 1 has finished reading it.
-constexpr int XPRE_MAX = 20;  // 16-byte loads per thread and tile: covers S <= 320
+// (16-byte loads, four columns of one row each) while the current tile is in
+// the matrix cores, and dropped into the LDS input tile, converted to the
+// operand type, once layer 1 has finished reading it.
+constexpr int XPRE_MAX = 10;  // 16-byte loads per thread and tile
 
 struct TileArgs {
   const float *X;
-  int64_t rows;
+  int64_t rows;       // multiple of 64
   float *Y;
   PackedNet net;
   int32_t N, envs_per_agent;
-  int32_t S, s_magic;  // s_magic = ceil(2^32 / S): e / S == umulhi(e, s_magic) for e < 2^32 / S
+  int32_t S;
+  int32_t groups;     // ceil(S / 4): 16-byte groups per row
+  int32_t g_magic;    // ceil(2^32 / groups): i / groups == umulhi(i, g_magic) for the small i used here
   int32_t xpitch, hpitch;
 };
 
-template <bool BF16, int CTH, int TAG>
-__global__ __launch_bounds__(tile::kThreads) void mlp_tiles_kernel(TileArgs a) {
+template <bool BF16, int NW, int CTH, int TAG>
+__global__ __launch_bounds__(NW * 64) void mlp_tiles_kernel(TileArgs a) {
   using namespace tile;
   using O = tile::Op<BF16>;
+  constexpr int NT = NW * 64;
   extern __shared__ __align__(16) unsigned char lds[];
   unsigned char *ldsH = lds;
   unsigned char *ldsX = lds + (size_t)BM * a.hpitch;
+  u32x4 *ldsW3 = reinterpret_cast<u32x4 *>(ldsX + (size_t)BM * a.xpitch);
+  float *ldsBias = reinterpret_cast<float *>(ldsW3 + (size_t)a.net.nkb[2] * 64);
   const int tid = threadIdx.x;
-  const int S = a.S;
-  const int64_t ntiles = a.rows / BM;  // a.rows is a multiple of BM
-  const int nx = (BM * S / 4 + kThreads - 1) / kThreads;  // 16-byte loads per thread for a full tile
+  const int S = a.S, G = a.groups;
+  const int64_t ntiles = a.rows / BM;
+  const int ngroups = BM * G;
+  const int nx = (ngroups + NT - 1) / NT;
 
-  for (int i = tid; i < BM * a.xpitch / 4; i += kThreads) reinterpret_cast<uint32_t *>(ldsX)[i] = 0u;
-  __syncthreads();
-
-  // Full tiles only (the launcher sends a ragged tail to the chunked kernel): a tile is BM * S floats,
-  // a multiple of four, so every 16-byte load is either wholly inside the tile or wholly outside.
   f32x4 pre[XPRE_MAX];
-  const int nelem = BM * S;
   auto fetch = [&](int64_t t) {
     const float *src = a.X + t * BM * S;
 #pragma unroll
     for (int i = 0; i < XPRE_MAX; ++i) {
       if (i < nx) {
-        const int e0 = 4 * (tid + kThreads * i);
-        if (e0 < nelem) pre[i] = *reinterpret_cast<const f32x4 *>(src + e0);
-      }
-    }
-  };
-  auto stash = [&]() {
-    // the LDS addresses are loop invariant; recompute them per call instead of letting the compiler keep
-    // eighty of them in registers across the matrix-core loops
-    int tid_opaque = tid;
-    asm volatile("" : "+v"(tid_opaque));
+        const int idx = tid + NT * i;
+        if (idx < ngroups) {
+          const int row = (int)__umulhi((unsigned)idx, (unsigned)a.g_magic);
+          const int c4 = 4 * (idx - row * G);
+          const float *p = src + (size_t)row * S + c4;
+          if (c4 + 3 < S) {
+            pre[i] = *reinterpret_cast<const f32x4 *>(p);  // needs 4-byte alignment only
+          } else {
 #pragma unroll
-    for (int i = 0; i < XPRE_MAX; ++i) {
-      if (i < nx) {
-        const int e0 = 4 * (tid_opaque + kThreads * i);
-        if (e0 < nelem) {
-          int row = (int)__umulhi((unsigned)e0, (unsigned)a.s_magic);
-          int col = e0 - row * S;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            O::store1(ldsX + (size_t)row * a.xpitch + col * O::ESZ, pre[i][j]);
-            if (++col == S) {
-              col = 0;
-              ++row;
-            }
+            for (int j = 0; j < 4; ++j) pre[i][j] = (c4 + j < S) ? p[j] : 0.0f;
           }
         }
       }
     }
   };
+  auto stash = [&]() {
+    // the LDS addresses are loop invariant; recompute them per call instead of letting the compiler keep
+    // them in registers across the matrix-core loops
+    int tid_opaque = tid;
+    asm volatile("" : "+v"(tid_opaque));
+#pragma unroll
+    for (int i = 0; i < XPRE_MAX; ++i) {
+      if (i < nx) {
+        const int idx = tid_opaque + NT * i;
+        if (idx < ngroups) {
+          const int row = (int)__umulhi((unsigned)idx, (unsigned)a.g_magic);
+          const int c4 = 4 * (idx - row * G);
+          // the group that straddles S also writes the zero padding of the k columns
+          O::store4(ldsX + (size_t)row * a.xpitch + c4 * O::ESZ, pre[i][0], pre[i][1], pre[i][2], pre[i][3]);
+        }
+      }
+    }
+  };
+
+  // k columns beyond the last group (when Kp > 4 * groups) are never written by stash: clear the tile once
+  for (int i = tid; i < BM * a.xpitch / 4; i += NT) reinterpret_cast<uint32_t *>(ldsX)[i] = 0u;
+  __syncthreads();
 
   int64_t t = blockIdx.x;
+  int staged_agent = -1;
   if (t < ntiles) {
     fetch(t);
     stash();
@@ -405,13 +414,21 @@ __global__ __launch_bounds__(tile::kThreads) void mlp_tiles_kernel(TileArgs a) {
     const int64_t row0 = t * BM;
     const int64_t tn = t + gridDim.x;
     const bool more = tn < ntiles;
-    if (more) fetch(tn);
-    __syncthreads();  // input tile complete; previous tile's output layer is done with ldsH
-    const Net net = net_of(a.net, (int)((row0 % a.N) / a.envs_per_agent));
+    const int agent = (int)((row0 % a.N) / a.envs_per_agent);
+    const Net net = net_of(a.net, agent);
+    if (agent != staged_agent) {
+      __syncthreads();  // the previous tile's output layer may still read its weights and biases
+      stage_net<NT>(net, ldsBias, ldsW3, tid);
+      staged_agent = agent;
+    }
+    __syncthreads();  // input tile, biases and W3 complete; previous tile's output layer is done with ldsH
     const int O_dim = net.out_dim;
     float *Y = a.Y + row0 * O_dim;
-    mlp_tile<BF16, CTH, false>(
-        net, ldsX, a.xpitch, ldsH, a.hpitch, tid,
+    mlp_tile<BF16, NW, CTH, false>(
+        net, ldsX, a.xpitch, ldsH, a.hpitch, ldsBias, ldsW3, tid,
+        [&]() {
+          if (more) fetch(tn);
+        },
         [&]() {
           if (more) stash();
         },
@@ -429,8 +446,8 @@ __global__ void pack_layer_kernel(const float *__restrict__ W, const float *__re
     const int agent = (int)(i / per_agent);
     const size_t j = i - (size_t)agent * per_agent;
     const int lane = (int)(j & 63);
-    const int kb = (int)((j >> 6) % nkb);
-    const int ct = (int)((j >> 6) / nkb);
+    const int ct = (int)((j >> 6) % nct);
+    const int kb = (int)((j >> 6) / nct);
     const int col = ct * 32 + (lane & 31), g = lane >> 5;
     const float *Wa = W + (size_t)agent * in_dim * out_dim;
     if (bf16) {
@@ -528,9 +545,9 @@ static hipError_t launch_one(hipStream_t st, const MlpArgs &a, unsigned blocks, 
 }
 
 
-template <bool BF16, int CTH, int TAG>
+template <bool BF16, int NW, int CTH, int TAG>
 static hipError_t launch_tiles_tagged(hipStream_t st, const TileArgs &a, unsigned blocks, size_t lds) {
-  auto kern = mlp_tiles_kernel<BF16, CTH, TAG>;
+  auto kern = mlp_tiles_kernel<BF16, NW, CTH, TAG>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -538,14 +555,14 @@ static hipError_t launch_tiles_tagged(hipStream_t st, const TileArgs &a, unsigne
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(blocks), dim3(tile::kThreads), lds, st, a);
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, st, a);
   return hipGetLastError();
 }
 
-template <bool BF16, int CTH>
+template <bool BF16, int NW, int CTH>
 static hipError_t launch_tiles(hipStream_t st, const TileArgs &a, unsigned blocks, size_t lds) {
-  return a.rows > a.N ? launch_tiles_tagged<BF16, CTH, 1>(st, a, blocks, lds)
-                      : launch_tiles_tagged<BF16, CTH, 0>(st, a, blocks, lds);
+  return a.rows > a.N ? launch_tiles_tagged<BF16, NW, CTH, 1>(st, a, blocks, lds)
+                      : launch_tiles_tagged<BF16, NW, CTH, 0>(st, a, blocks, lds);
 }
 
 int compute_units() {
@@ -560,12 +577,18 @@ int compute_units() {
   return n;
 }
 
-// The whole-tile kernel covers dense rows with S <= 320 and hidden widths up to 512.
+// The whole-tile kernel covers dense rows, one output feature tile, hidden widths up to 512 and S up to 320.
+// `rows` must be a multiple of 64.
 static bool try_launch_tiles(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx, float *Y,
-                             int32_t N, int32_t envs_per_agent, const Shape &s, hipError_t *err) {
-  const int S = net.in_dim[0];
-  if (ldx != S || (reinterpret_cast<uintptr_t>(X) & 15u) || s.cth > 4 || net.nct[2] != 1) return false;
-  if ((tile::BM * S / 4 + tile::kThreads - 1) / tile::kThreads > XPRE_MAX) return false;
+                             int32_t N, int32_t envs_per_agent, hipError_t *err) {
+  const int S = net.in_dim[0], Hd = net.out_dim[0];
+  if (ldx != S || (reinterpret_cast<uintptr_t>(X) & 3u) || net.nct[2] != 1 || Hd > 512) return false;
+  const int G = (S + 3) / 4;
+  // eight wavefronts when every one of them gets at least one feature tile
+  const int nct = net.nct[0];
+  const int NW = nct >= 8 ? 8 : 4;
+  const int cth = (nct + NW - 1) / NW;
+  if ((tile::BM * G + NW * 64 - 1) / (NW * 64) > XPRE_MAX) return false;
   const int esz = net.bf16 ? 2 : 4, KB = kblock(net.bf16);
   TileArgs a;
   a.X = X;
@@ -575,20 +598,20 @@ static bool try_launch_tiles(hipStream_t st, const PackedNet &net, int64_t rows,
   a.N = N;
   a.envs_per_agent = envs_per_agent;
   a.S = S;
-  a.s_magic = (int32_t)(uint32_t)((0x100000000ull + (uint64_t)S - 1) / (uint64_t)S);
+  a.groups = G;
+  a.g_magic = (int32_t)(uint32_t)((0x100000000ull + (uint64_t)G - 1) / (uint64_t)G);
   a.xpitch = tile::tile_pitch(net.nkb[0] * KB, esz);
-  a.hpitch = tile::tile_pitch(net.out_dim[0], esz);
-  const size_t lds = (size_t)tile::BM * (a.xpitch + a.hpitch);
+  a.hpitch = tile::tile_pitch(Hd, esz);
+  const size_t lds = (size_t)tile::BM * (a.xpitch + a.hpitch) + (size_t)net.nkb[2] * 1024 +
+                     (size_t)(net.nct[0] + net.nct[1] + net.nct[2]) * 32 * 4;
   if (lds > 160 * 1024) return false;
-  const int64_t ntiles = (rows + tile::BM - 1) / tile::BM;
+  const int64_t ntiles = rows / tile::BM;
   const unsigned blocks = (unsigned)(ntiles < compute_units() ? ntiles : compute_units());
   const bool bf = net.bf16 != 0;
-  if (bf && s.cth == 1) *err = launch_tiles<true, 1>(st, a, blocks, lds);
-  else if (bf && s.cth == 2) *err = launch_tiles<true, 2>(st, a, blocks, lds);
-  else if (bf && s.cth == 4) *err = launch_tiles<true, 4>(st, a, blocks, lds);
-  else if (!bf && s.cth == 1) *err = launch_tiles<false, 1>(st, a, blocks, lds);
-  else if (!bf && s.cth == 2) *err = launch_tiles<false, 2>(st, a, blocks, lds);
-  else if (!bf && s.cth == 4) *err = launch_tiles<false, 4>(st, a, blocks, lds);
+  if (NW == 8 && cth == 2) *err = bf ? launch_tiles<true, 8, 2>(st, a, blocks, lds) : launch_tiles<false, 8, 2>(st, a, blocks, lds);
+  else if (NW == 8 && cth == 1) *err = bf ? launch_tiles<true, 8, 1>(st, a, blocks, lds) : launch_tiles<false, 8, 1>(st, a, blocks, lds);
+  else if (NW == 4 && cth == 1) *err = bf ? launch_tiles<true, 4, 1>(st, a, blocks, lds) : launch_tiles<false, 4, 1>(st, a, blocks, lds);
+  else if (NW == 4 && cth == 2) *err = bf ? launch_tiles<true, 4, 2>(st, a, blocks, lds) : launch_tiles<false, 4, 2>(st, a, blocks, lds);
   else return false;
   return true;
 }
@@ -603,7 +626,7 @@ hipError_t launch_mlp(hipStream_t st, const PackedNet &net, int64_t rows, const 
     // full tiles through the persistent whole-tile kernel when it covers the shape; the ragged tail below
     hipError_t terr = hipSuccess;
     const int64_t full = rows / BM * BM;
-    if (try_launch_tiles(st, net, full, X, ldx, Y, N, envs_per_agent, s, &terr)) {
+    if (try_launch_tiles(st, net, full, X, ldx, Y, N, envs_per_agent, &terr)) {
       if (terr != hipSuccess || full == rows) return terr;
       X += full * ldx;
       Y += full * net.out_dim[2];

@@ -12,9 +12,12 @@
 // (fp32) LDS store into the row-major [batch][feature] tile the next layer
 // reads its B operand from.
 //
-// The four wavefronts of a workgroup split the output features; each streams
+// The NW wavefronts of a workgroup split the output features; each streams
 // its own weight blocks from global/L2 through a small register ring that is
-// primed for the next layer before the current layer's epilogue starts.
+// primed for the next layer before the current layer's epilogue starts.  With
+// NW = 8 two wavefronts share a SIMD, so one's waits on weight loads or its
+// epilogue arithmetic overlap with the other's matrix instructions.  The small
+// output layer's weights sit in LDS.
 #pragma once
 
 #include "pod_internal.h"
@@ -29,8 +32,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kWaves = 4;
-constexpr int kThreads = kWaves * 64;
 constexpr int BM = 64;  // batch rows per tile (two 32-row MFMA tiles)
 
 template <bool BF16>
@@ -114,9 +115,11 @@ __device__ inline Net net_of(const PackedNet &p, int agent) {
   return n;
 }
 
-// Weight block (feature tile ct, k-block kb) for this lane.
-__device__ inline u32x4 load_w(const u32x4 *W, int nkb, int ct, int kb, int lane) {
-  return W[((size_t)ct * nkb + kb) * 64 + lane];
+// Weight block (feature tile ct, k-block kb) for this lane.  Blocks are stored k-major ([kb][ct][lane]):
+// the blocks a workgroup needs for one k-block are one contiguous run, so the requests of a k-step spread
+// over all L2 channels instead of piling onto the few channels a power-of-two stride would select.
+__device__ inline u32x4 load_w(const u32x4 *W, int nct, int ct, int kb, int lane) {
+  return W[((size_t)kb * nct + ct) * 64 + lane];
 }
 
 // Fill the ring with k-blocks 0..PD-1 of a layer (feature tiles ct0..ct0+CT-1, clamped to the last tile).
@@ -126,36 +129,52 @@ __device__ inline void prime(u32x4 (&ring)[PD][CT], const u32x4 *W, int nkb, int
   for (int s = 0; s < PD; ++s)
     if (s < nkb) {
 #pragma unroll
-      for (int c = 0; c < CT; ++c) ring[s][c] = load_w(W, nkb, min(ct0 + c, nct - 1), s, lane);
+      for (int c = 0; c < CT; ++c) ring[s][c] = load_w(W, nct, min(ct0 + c, nct - 1), s, lane);
     }
 }
 
 // acc[c][t] += W(feature tile ct0 + c) * X(batch tile bt0 + t) over all k-blocks.  The activation tile is
 // row-major [batch][k] in LDS with `pitch` bytes per row.  The ring must be primed for this layer.
+// The main loop has no branches (refills past the end re-read the last block), so the compiler's wait
+// counters stay exact and PD k-blocks of weights are really in flight behind the matrix instructions.
 template <bool BF16, int CT, int NBT, int PD>
 __device__ inline void mma_layer(f32x16 (&acc)[CT][NBT], u32x4 (&ring)[PD][CT], const unsigned char *ldsX, int pitch,
                                  int nkb, const u32x4 *W, int nct, int ct0, int bt0, int lane) {
   using O = Op<BF16>;
   const int brow = lane & 31, g = lane >> 5;
   const unsigned char *xbase = ldsX + (size_t)(bt0 * 32 + brow) * pitch + 16 * g;
-  for (int kb0 = 0; kb0 < nkb; kb0 += PD) {
+  const u32x4 *wp[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) wp[c] = W + (size_t)min(ct0 + c, nct - 1) * 64 + lane;
+  int kb0 = 0;
+  for (; kb0 + PD <= nkb; kb0 += PD) {
 #pragma unroll
     for (int s = 0; s < PD; ++s) {
       const int kb = kb0 + s;
-      if (kb < nkb) {
-        u32x4 x[NBT];
+      u32x4 x[NBT];
 #pragma unroll
-        for (int t = 0; t < NBT; ++t)
-          x[t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)t * 32 * pitch + kb * 32);
+      for (int t = 0; t < NBT; ++t) x[t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)t * 32 * pitch + kb * 32);
 #pragma unroll
-        for (int c = 0; c < CT; ++c)
+      for (int c = 0; c < CT; ++c)
 #pragma unroll
-          for (int t = 0; t < NBT; ++t) O::mma(ring[s][c], x[t], acc[c][t]);
-        if (kb + PD < nkb) {
+        for (int t = 0; t < NBT; ++t) O::mma(ring[s][c], x[t], acc[c][t]);
+      const int kn = min(kb + PD, nkb - 1);
 #pragma unroll
-          for (int c = 0; c < CT; ++c) ring[s][c] = load_w(W, nkb, min(ct0 + c, nct - 1), kb + PD, lane);
-        }
-      }
+      for (int c = 0; c < CT; ++c) ring[s][c] = wp[c][(size_t)kn * nct * 64];
+    }
+  }
+  const int rem = nkb - kb0;  // < PD blocks left, already in ring[0 .. rem-1]
+#pragma unroll
+  for (int s = 0; s < PD - 1; ++s) {
+    if (s < rem) {
+      const int kb = kb0 + s;
+      u32x4 x[NBT];
+#pragma unroll
+      for (int t = 0; t < NBT; ++t) x[t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)t * 32 * pitch + kb * 32);
+#pragma unroll
+      for (int c = 0; c < CT; ++c)
+#pragma unroll
+        for (int t = 0; t < NBT; ++t) O::mma(ring[s][c], x[t], acc[c][t]);
     }
   }
 }
@@ -195,8 +214,6 @@ __device__ inline void epilogue_hidden(const f32x16 (&acc)[CT][NBT], const float
           }
           O::store4(ldsH + (size_t)((bt0 + t) * 32 + brow) * hpitch + f0 * O::ESZ, h[0], h[1], h[2], h[3]);
         }
-        // keep the scheduler from interleaving all groups at once (it would need a register per value)
-        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
@@ -227,18 +244,53 @@ __device__ inline void epilogue_out(const f32x16 (&acc)[CT][NBT], const float *b
   }
 }
 
-// WIDE_OUT = false: the output layer has at most 32 features (one feature tile).
+// Copy one agent's three bias vectors (padded to multiples of 32) into LDS: [b1 | b2 | b3], and, when the
+// output layer is a single feature tile, its packed weights (nkb[2] blocks of 1 KiB) into ldsW3.
+template <int NT>
+__device__ inline void stage_net(const Net &net, float *ldsBias, u32x4 *ldsW3, int tid) {
+  int off = 0;
+#pragma unroll
+  for (int l = 0; l < 3; ++l) {
+    const int n = net.nct[l] * 32;
+    for (int i = tid; i < n; i += NT) ldsBias[off + i] = net.b[l][i];
+    off += n;
+  }
+  if (ldsW3 && net.nct[2] == 1)
+    for (int i = tid; i < net.nkb[2] * 64; i += NT) ldsW3[i] = net.W[2][i];
+}
+
+// Output layer with one feature tile: weights from LDS (block kb = 64 lanes x 16 B), activations from ldsH.
+template <bool BF16>
+__device__ inline void mma_out_lds(f32x16 &acc, const u32x4 *ldsW3, const unsigned char *ldsH, int hpitch, int nkb,
+                                   int bt, int lane) {
+  using O = Op<BF16>;
+  const int brow = lane & 31, g = lane >> 5;
+  const unsigned char *xbase = ldsH + (size_t)(bt * 32 + brow) * hpitch + 16 * g;
+
+  for (int kb = 0; kb < nkb; ++kb) {
+    const u32x4 wv = ldsW3[kb * 64 + lane];
+    const u32x4 xv = *reinterpret_cast<const u32x4 *>(xbase + kb * 32);
+    O::mma(wv, xv, acc);
+  }
+}
+
 // Layers 1-3 for the 64-row tile whose layer-1 input already sits in ldsX (row-major, xpitch bytes per row,
-// padded k columns zero).  ldsH receives the hidden tiles.  `after_l1()` runs once the layer-1 reads of ldsX
-// are complete workgroup-wide (ldsX may be refilled from there on).  Ends without a trailing barrier: the
-// caller must synchronise before ldsH or ldsX are written again.
-template <bool BF16, int CTH, bool WIDE_OUT, class AfterL1, class Sink>
+// padded k columns zero).  ldsH receives the hidden tiles; ldsBias / ldsW3 as filled by stage_net.
+// NW wavefronts (4 or 8); CTH = feature tiles per wavefront in the hidden layers.
+// WIDE_OUT = false: the output layer has at most 32 features (one feature tile, weights in ldsW3).
+// Hooks: early() runs after layer 1's matrix work, before its epilogue -- the place to issue global loads that
+// are not needed soon.  late() runs once layer 2's epilogue is complete workgroup-wide; ldsX has been free
+// since layer 1 and may be refilled there.
+// Ends without a trailing barrier: the caller must synchronise before ldsH or ldsX are read or written again.
+template <bool BF16, int NW, int CTH, bool WIDE_OUT, class Early, class Late, class Sink>
 __device__ inline void mlp_tile(const Net &net, const unsigned char *ldsX, int xpitch, unsigned char *ldsH,
-                                int hpitch, int tid, AfterL1 after_l1, Sink sink) {
+                                int hpitch, const float *ldsBias, const u32x4 *ldsW3, int tid, Early early, Late late,
+                                Sink sink) {
   constexpr int PD = CTH >= 8 ? 2 : 4;
   const int lane = tid & 63, w = tid >> 6;
   const int ct0 = w * CTH;
   const bool act = ct0 < net.nct[0];
+  const float *lb1 = ldsBias, *lb2 = ldsBias + net.nct[0] * 32, *lb3 = lb2 + net.nct[1] * 32;
   u32x4 ring[PD][CTH];
   {
     f32x16 acc[CTH][2];
@@ -247,28 +299,28 @@ __device__ inline void mlp_tile(const Net &net, const unsigned char *ldsX, int x
       prime<CTH, PD>(ring, net.W[0], net.nkb[0], net.nct[0], ct0, lane);
       mma_layer<BF16, CTH, 2, PD>(acc, ring, ldsX, xpitch, net.nkb[0], net.W[0], net.nct[0], ct0, 0, lane);
       prime<CTH, PD>(ring, net.W[1], net.nkb[1], net.nct[1], ct0, lane);
-      epilogue_hidden<BF16, CTH, 2>(acc, net.b[0], ldsH, hpitch, net.nct[0], ct0, 0, lane);
     }
+    early();
+    if (act) epilogue_hidden<BF16, CTH, 2>(acc, lb1, ldsH, hpitch, net.nct[0], ct0, 0, lane);
     __syncthreads();
-    after_l1();
     zero_acc<CTH, 2>(acc);
     if (act) mma_layer<BF16, CTH, 2, PD>(acc, ring, ldsH, hpitch, net.nkb[1], net.W[1], net.nct[1], ct0, 0, lane);
     __syncthreads();  // every wavefront has consumed the layer-1 tile; it is overwritten in place
-    if (act) epilogue_hidden<BF16, CTH, 2>(acc, net.b[1], ldsH, hpitch, net.nct[1], ct0, 0, lane);
+    if (act) epilogue_hidden<BF16, CTH, 2>(acc, lb2, ldsH, hpitch, net.nct[1], ct0, 0, lane);
     __syncthreads();
   }
-  // output layer: few features.  One feature tile: wavefronts 0 and 1 take one 32-row batch tile each.
-  // More feature tiles: split the feature tiles over the wavefronts like the hidden layers.
+  // output layer: few features.  One feature tile: wavefronts 0 and 1 take one 32-row batch tile each while
+  // the others run late().  More feature tiles: split them over the wavefronts like the hidden layers.
   if (!WIDE_OUT) {
     if (w < 2) {
-      u32x4 r1[4][1];
       f32x16 acc[1][1];
       zero_acc<1, 1>(acc);
-      prime<1, 4>(r1, net.W[2], net.nkb[2], 1, 0, lane);
-      mma_layer<BF16, 1, 1, 4>(acc, r1, ldsH, hpitch, net.nkb[2], net.W[2], 1, 0, w, lane);
-      epilogue_out<1, 1>(acc, net.b[2], net.out_dim, net.out_tanh, 1, 0, w, lane, sink);
+      mma_out_lds<BF16>(acc[0][0], ldsW3, ldsH, hpitch, net.nkb[2], w, lane);
+      epilogue_out<1, 1>(acc, lb3, net.out_dim, net.out_tanh, 1, 0, w, lane, sink);
     }
+    late();
   } else {
+    late();
     constexpr int CTO = 4;
     const int co0 = w * CTO;
     if (co0 < net.nct[2]) {
@@ -277,7 +329,7 @@ __device__ inline void mlp_tile(const Net &net, const unsigned char *ldsX, int x
       zero_acc<CTO, 2>(acc);
       prime<CTO, 2>(r4, net.W[2], net.nkb[2], net.nct[2], co0, lane);
       mma_layer<BF16, CTO, 2, 2>(acc, r4, ldsH, hpitch, net.nkb[2], net.W[2], net.nct[2], co0, 0, lane);
-      epilogue_out<CTO, 2>(acc, net.b[2], net.out_dim, net.out_tanh, net.nct[2], co0, 0, lane, sink);
+      epilogue_out<CTO, 2>(acc, lb3, net.out_dim, net.out_tanh, net.nct[2], co0, 0, lane, sink);
     }
   }
 }
