@@ -344,7 +344,7 @@ struct TileArgs {
   int32_t xpitch, hpitch;
 };
 
-template <bool BF16, int NW, int CTH, int TAG>
+template <bool BF16, int NW, int CTH, int NKB1, int NKB2, int TAG>
 __global__ __launch_bounds__(NW * 64) void mlp_tiles_kernel(TileArgs a) {
   using namespace tile;
   using O = tile::Op<BF16>;
@@ -360,24 +360,20 @@ __global__ __launch_bounds__(NW * 64) void mlp_tiles_kernel(TileArgs a) {
   const int ngroups = BM * G;
   const int nx = (ngroups + NT - 1) / NT;
 
+  // Branch-free fetch: every thread issues nx unconditional 16-byte loads (threads past the last group
+  // re-read the last group).  The group that straddles the end of a row is read as the four floats that
+  // END at the row end and is shifted into place, with zeros behind, when it is stored.
   f32x4 pre[XPRE_MAX];
   auto fetch = [&](int64_t t) {
     const float *src = a.X + t * BM * S;
 #pragma unroll
     for (int i = 0; i < XPRE_MAX; ++i) {
       if (i < nx) {
-        const int idx = tid + NT * i;
-        if (idx < ngroups) {
-          const int row = (int)__umulhi((unsigned)idx, (unsigned)a.g_magic);
-          const int c4 = 4 * (idx - row * G);
-          const float *p = src + (size_t)row * S + c4;
-          if (c4 + 3 < S) {
-            pre[i] = *reinterpret_cast<const f32x4 *>(p);  // needs 4-byte alignment only
-          } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) pre[i][j] = (c4 + j < S) ? p[j] : 0.0f;
-          }
-        }
+        const int idx = min(tid + NT * i, ngroups - 1);
+        const int row = (int)__umulhi((unsigned)idx, (unsigned)a.g_magic);
+        const int c4 = 4 * (idx - row * G);
+        const int shift = max(0, c4 + 4 - S);
+        pre[i] = *reinterpret_cast<const f32x4 *>(src + (size_t)row * S + c4 - shift);  // 4-byte aligned
       }
     }
   };
@@ -390,12 +386,17 @@ __global__ __launch_bounds__(NW * 64) void mlp_tiles_kernel(TileArgs a) {
     for (int i = 0; i < XPRE_MAX; ++i) {
       if (i < nx) {
         const int idx = tid_opaque + NT * i;
-        if (idx < ngroups) {
-          const int row = (int)__umulhi((unsigned)idx, (unsigned)a.g_magic);
-          const int c4 = 4 * (idx - row * G);
-          // the group that straddles S also writes the zero padding of the k columns
-          O::store4(ldsX + (size_t)row * a.xpitch + c4 * O::ESZ, pre[i][0], pre[i][1], pre[i][2], pre[i][3]);
-        }
+        const int idc = min(idx, ngroups - 1);
+        const int row = (int)__umulhi((unsigned)idc, (unsigned)a.g_magic);
+        const int c4 = 4 * (idc - row * G);
+        const int shift = max(0, c4 + 4 - S);
+        const f32x4 v = pre[i];
+        const float o0 = shift == 0 ? v[0] : shift == 1 ? v[1] : shift == 2 ? v[2] : v[3];
+        const float o1 = shift == 0 ? v[1] : shift == 1 ? v[2] : shift == 2 ? v[3] : 0.0f;
+        const float o2 = shift == 0 ? v[2] : shift == 1 ? v[3] : 0.0f;
+        const float o3 = shift == 0 ? v[3] : 0.0f;
+        // the group that straddles S also writes the zero padding of the k columns
+        if (idx < ngroups) O::store4(ldsX + (size_t)row * a.xpitch + c4 * O::ESZ, o0, o1, o2, o3);
       }
     }
   };
@@ -424,7 +425,7 @@ __global__ __launch_bounds__(NW * 64) void mlp_tiles_kernel(TileArgs a) {
     __syncthreads();  // input tile, biases and W3 complete; previous tile's output layer is done with ldsH
     const int O_dim = net.out_dim;
     float *Y = a.Y + row0 * O_dim;
-    mlp_tile<BF16, NW, CTH, false>(
+    mlp_tile<BF16, NW, CTH, false, NKB1, NKB2>(
         net, ldsX, a.xpitch, ldsH, a.hpitch, ldsBias, ldsW3, tid,
         [&]() {
           if (more) fetch(tn);
@@ -545,9 +546,9 @@ static hipError_t launch_one(hipStream_t st, const MlpArgs &a, unsigned blocks, 
 }
 
 
-template <bool BF16, int NW, int CTH, int TAG>
+template <bool BF16, int NW, int CTH, int NKB1, int NKB2, int TAG>
 static hipError_t launch_tiles_tagged(hipStream_t st, const TileArgs &a, unsigned blocks, size_t lds) {
-  auto kern = mlp_tiles_kernel<BF16, NW, CTH, TAG>;
+  auto kern = mlp_tiles_kernel<BF16, NW, CTH, NKB1, NKB2, TAG>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -559,10 +560,10 @@ static hipError_t launch_tiles_tagged(hipStream_t st, const TileArgs &a, unsigne
   return hipGetLastError();
 }
 
-template <bool BF16, int NW, int CTH>
+template <bool BF16, int NW, int CTH, int NKB1 = 0, int NKB2 = 0>
 static hipError_t launch_tiles(hipStream_t st, const TileArgs &a, unsigned blocks, size_t lds) {
-  return a.rows > a.N ? launch_tiles_tagged<BF16, NW, CTH, 1>(st, a, blocks, lds)
-                      : launch_tiles_tagged<BF16, NW, CTH, 0>(st, a, blocks, lds);
+  return a.rows > a.N ? launch_tiles_tagged<BF16, NW, CTH, NKB1, NKB2, 1>(st, a, blocks, lds)
+                      : launch_tiles_tagged<BF16, NW, CTH, NKB1, NKB2, 0>(st, a, blocks, lds);
 }
 
 int compute_units() {
@@ -582,7 +583,7 @@ int compute_units() {
 static bool try_launch_tiles(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx, float *Y,
                              int32_t N, int32_t envs_per_agent, hipError_t *err) {
   const int S = net.in_dim[0], Hd = net.out_dim[0];
-  if (ldx != S || (reinterpret_cast<uintptr_t>(X) & 3u) || net.nct[2] != 1 || Hd > 512) return false;
+  if (ldx != S || S < 4 || (reinterpret_cast<uintptr_t>(X) & 3u) || net.nct[2] != 1 || Hd > 512) return false;
   const int G = (S + 3) / 4;
   // eight wavefronts when every one of them gets at least one feature tile
   const int nct = net.nct[0];
@@ -608,7 +609,10 @@ static bool try_launch_tiles(hipStream_t st, const PackedNet &net, int64_t rows,
   const int64_t ntiles = rows / tile::BM;
   const unsigned blocks = (unsigned)(ntiles < compute_units() ? ntiles : compute_units());
   const bool bf = net.bf16 != 0;
-  if (NW == 8 && cth == 2) *err = bf ? launch_tiles<true, 8, 2>(st, a, blocks, lds) : launch_tiles<false, 8, 2>(st, a, blocks, lds);
+  // shapes of the named workloads get straight-line k loops (S = 301: 19 bf16 / 38 fp32 k-blocks)
+  if (bf && NW == 8 && cth == 2 && net.nkb[0] == 19 && net.nkb[1] == 32) *err = launch_tiles<true, 8, 2, 19, 32>(st, a, blocks, lds);
+  else if (!bf && NW == 8 && cth == 1 && net.nkb[0] == 38 && net.nkb[1] == 32) *err = launch_tiles<false, 8, 1, 38, 32>(st, a, blocks, lds);
+  else if (NW == 8 && cth == 2) *err = bf ? launch_tiles<true, 8, 2>(st, a, blocks, lds) : launch_tiles<false, 8, 2>(st, a, blocks, lds);
   else if (NW == 8 && cth == 1) *err = bf ? launch_tiles<true, 8, 1>(st, a, blocks, lds) : launch_tiles<false, 8, 1>(st, a, blocks, lds);
   else if (NW == 4 && cth == 1) *err = bf ? launch_tiles<true, 4, 1>(st, a, blocks, lds) : launch_tiles<false, 4, 1>(st, a, blocks, lds);
   else if (NW == 4 && cth == 2) *err = bf ? launch_tiles<true, 4, 2>(st, a, blocks, lds) : launch_tiles<false, 4, 2>(st, a, blocks, lds);

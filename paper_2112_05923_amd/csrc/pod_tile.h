@@ -161,6 +161,9 @@ __device__ inline void mma_layer(f32x16 (&acc)[CT][NBT], u32x4 (&ring)[PD][CT], 
       const int kn = min(kb + PD, nkb - 1);
 #pragma unroll
       for (int c = 0; c < CT; ++c) ring[s][c] = wp[c][(size_t)kn * nct * 64];
+      // keep each refill right behind the matrix instructions that freed its slot: left alone, the
+      // scheduler sinks all refills to the end of the loop body and the ring is one k-group deep
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
   const int rem = nkb - kb0;  // < PD blocks left, already in ring[0 .. rem-1]
@@ -176,6 +179,38 @@ __device__ inline void mma_layer(f32x16 (&acc)[CT][NBT], u32x4 (&ring)[PD][CT], 
 #pragma unroll
         for (int t = 0; t < NBT; ++t) O::mma(ring[s][c], x[t], acc[c][t]);
     }
+  }
+}
+
+// The same with the number of k-blocks known at compile time: straight-line code, so every wait on a
+// weight load is placed exactly (across a loop back-edge the compiler falls back to waiting for all loads,
+// which exposes one L2 round trip per loop iteration).
+template <bool BF16, int CT, int NBT, int PD, int NKB>
+__device__ inline void mma_layer_static(f32x16 (&acc)[CT][NBT], u32x4 (&ring)[PD][CT], const unsigned char *ldsX,
+                                        int pitch, const u32x4 *W, int nct, int ct0, int bt0, int lane) {
+  using O = Op<BF16>;
+  const int brow = lane & 31, g = lane >> 5;
+  const unsigned char *xbase = ldsX + (size_t)(bt0 * 32 + brow) * pitch + 16 * g;
+  const u32x4 *wp[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) wp[c] = W + (size_t)min(ct0 + c, nct - 1) * 64 + lane;
+#pragma unroll
+  for (int kb = 0; kb < NKB; ++kb) {
+    constexpr int dummy = 0;
+    (void)dummy;
+    const int s = kb % PD;
+    u32x4 x[NBT];
+#pragma unroll
+    for (int t = 0; t < NBT; ++t) x[t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)t * 32 * pitch + kb * 32);
+#pragma unroll
+    for (int c = 0; c < CT; ++c)
+#pragma unroll
+      for (int t = 0; t < NBT; ++t) O::mma(ring[s][c], x[t], acc[c][t]);
+    if (kb + PD < NKB) {
+#pragma unroll
+      for (int c = 0; c < CT; ++c) ring[s][c] = wp[c][(size_t)(kb + PD) * nct * 64];
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -276,18 +311,20 @@ __device__ inline void mma_out_lds(f32x16 &acc, const u32x4 *ldsW3, const unsign
 
 // Layers 1-3 for the 64-row tile whose layer-1 input already sits in ldsX (row-major, xpitch bytes per row,
 // padded k columns zero).  ldsH receives the hidden tiles; ldsBias / ldsW3 as filled by stage_net.
-// NW wavefronts (4 or 8); CTH = feature tiles per wavefront in the hidden layers.
+// NW wavefronts (4 or 8); CTH = feature tiles per wavefront in the hidden layers; NKB1 / NKB2 = k-blocks
+// of layers 1 / 2 when known at compile time (0: read them from `net`).
 // WIDE_OUT = false: the output layer has at most 32 features (one feature tile, weights in ldsW3).
 // Hooks: early() runs after layer 1's matrix work, before its epilogue -- the place to issue global loads that
 // are not needed soon.  late() runs once layer 2's epilogue is complete workgroup-wide; ldsX has been free
 // since layer 1 and may be refilled there.
 // Ends without a trailing barrier: the caller must synchronise before ldsH or ldsX are read or written again.
-template <bool BF16, int NW, int CTH, bool WIDE_OUT, class Early, class Late, class Sink>
+template <bool BF16, int NW, int CTH, bool WIDE_OUT, int NKB1, int NKB2, class Early, class Late, class Sink>
 __device__ inline void mlp_tile(const Net &net, const unsigned char *ldsX, int xpitch, unsigned char *ldsH,
                                 int hpitch, const float *ldsBias, const u32x4 *ldsW3, int tid, Early early, Late late,
                                 Sink sink) {
   constexpr int PD = CTH >= 8 ? 2 : 4;
-  const int lane = tid & 63, w = tid >> 6;
+  // the wavefront index is uniform: tell the compiler, so that block addresses live in scalar registers
+  const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ct0 = w * CTH;
   const bool act = ct0 < net.nct[0];
   const float *lb1 = ldsBias, *lb2 = ldsBias + net.nct[0] * 32, *lb3 = lb2 + net.nct[1] * 32;
@@ -297,14 +334,22 @@ __device__ inline void mlp_tile(const Net &net, const unsigned char *ldsX, int x
     zero_acc<CTH, 2>(acc);
     if (act) {
       prime<CTH, PD>(ring, net.W[0], net.nkb[0], net.nct[0], ct0, lane);
-      mma_layer<BF16, CTH, 2, PD>(acc, ring, ldsX, xpitch, net.nkb[0], net.W[0], net.nct[0], ct0, 0, lane);
+      if (NKB1 > 0)
+        mma_layer_static<BF16, CTH, 2, PD, NKB1>(acc, ring, ldsX, xpitch, net.W[0], net.nct[0], ct0, 0, lane);
+      else
+        mma_layer<BF16, CTH, 2, PD>(acc, ring, ldsX, xpitch, net.nkb[0], net.W[0], net.nct[0], ct0, 0, lane);
       prime<CTH, PD>(ring, net.W[1], net.nkb[1], net.nct[1], ct0, lane);
     }
     early();
     if (act) epilogue_hidden<BF16, CTH, 2>(acc, lb1, ldsH, hpitch, net.nct[0], ct0, 0, lane);
     __syncthreads();
     zero_acc<CTH, 2>(acc);
-    if (act) mma_layer<BF16, CTH, 2, PD>(acc, ring, ldsH, hpitch, net.nkb[1], net.W[1], net.nct[1], ct0, 0, lane);
+    if (act) {
+      if (NKB2 > 0)
+        mma_layer_static<BF16, CTH, 2, PD, NKB2>(acc, ring, ldsH, hpitch, net.W[1], net.nct[1], ct0, 0, lane);
+      else
+        mma_layer<BF16, CTH, 2, PD>(acc, ring, ldsH, hpitch, net.nkb[1], net.W[1], net.nct[1], ct0, 0, lane);
+    }
     __syncthreads();  // every wavefront has consumed the layer-1 tile; it is overwritten in place
     if (act) epilogue_hidden<BF16, CTH, 2>(acc, lb2, ldsH, hpitch, net.nct[1], ct0, 0, lane);
     __syncthreads();
