@@ -74,7 +74,7 @@ int validate_config(const pr_config *c) {
   if (!mlp_supported(S, c->hidden, c->n_stocks, c->mlp_dtype) || !mlp_supported(S, c->hidden, 1, c->mlp_dtype))
     return PR_EUNSUPPORTED;
   if (c->n_agents > 1 && (c->n_envs / c->n_agents) % 64 != 0) return PR_EUNSUPPORTED;
-  if (c->schedule == PR_SCHED_FUSED) return PR_EUNSUPPORTED;
+  if (c->schedule == PR_SCHED_FUSED && !fused_supported(*c)) return PR_EUNSUPPORTED;
   return PR_OK;
 }
 
@@ -262,13 +262,18 @@ int rollout_step_T(pr_handle *h, int32_t T, const float *noise, const pr_buffers
   if (rc != PR_OK) return rc;
   const size_t N = (size_t)h->cfg.n_envs, D = (size_t)h->cfg.n_stocks, S = (size_t)h->S;
   const int32_t per_agent = h->cfg.n_envs / h->cfg.n_agents;
-  POD_HIP(launch_observe(h->stream, h->dims, h->st, h->market.price, h->market.ind, out->obs));
-  for (int t = 0; t < T; ++t) {
-    float *mu = out->mu ? out->mu + (size_t)t * N * D : h->mu_scratch;
-    POD_HIP(launch_mlp(h->stream, h->actor, (int64_t)N, out->obs + (size_t)t * N * S, (int64_t)S, mu, (int32_t)N,
-                       per_agent));
-    POD_HIP(launch_env_step(h->stream, h->dims, h->st, h->market.price, h->market.ind,
-                            step_io(h, out, t, mu, noise)));
+  if (h->cfg.schedule == PR_SCHED_FUSED) {
+    POD_HIP(launch_rollout_fused(h->stream, h->cfg, h->dims, h->st, h->market.price, h->market.ind, h->actor,
+                                 per_agent, T, noise, nullptr, *out));
+  } else {
+    POD_HIP(launch_observe(h->stream, h->dims, h->st, h->market.price, h->market.ind, out->obs));
+    for (int t = 0; t < T; ++t) {
+      float *mu = out->mu ? out->mu + (size_t)t * N * D : h->mu_scratch;
+      POD_HIP(launch_mlp(h->stream, h->actor, (int64_t)N, out->obs + (size_t)t * N * S, (int64_t)S, mu, (int32_t)N,
+                         per_agent));
+      POD_HIP(launch_env_step(h->stream, h->dims, h->st, h->market.price, h->market.ind,
+                              step_io(h, out, t, mu, noise)));
+    }
   }
   if (out->value)
     POD_HIP(launch_mlp(h->stream, h->critic, (int64_t)(T + 1) * (int64_t)N, out->obs, (int64_t)S, out->value,
@@ -281,6 +286,11 @@ int rollout_step_forced(pr_handle *h, int32_t T, const float *mu, const float *n
   int rc = check_buffers(out);
   if (rc != PR_OK) return rc;
   const size_t N = (size_t)h->cfg.n_envs, D = (size_t)h->cfg.n_stocks;
+  if (h->cfg.schedule == PR_SCHED_FUSED) {
+    POD_HIP(launch_rollout_fused(h->stream, h->cfg, h->dims, h->st, h->market.price, h->market.ind, h->actor,
+                                 h->cfg.n_envs / h->cfg.n_agents, T, noise, mu, *out));
+    return PR_OK;
+  }
   POD_HIP(launch_observe(h->stream, h->dims, h->st, h->market.price, h->market.ind, out->obs));
   for (int t = 0; t < T; ++t)
     POD_HIP(launch_env_step(h->stream, h->dims, h->st, h->market.price, h->market.ind,

@@ -1,0 +1,514 @@
+// Persistent rollout kernel: one workgroup keeps a tile of 64 envs on its
+// compute unit for all T steps of a rollout (the worker of Sec. 4.2: actor x
+// batched environment; stock-trading task of Table 1 / Sec. 5.3).
+//
+// Envs are independent, so no grid-wide synchronisation is needed: each
+// workgroup loops   obs_t (LDS) -> actor (matrix cores) -> sample -> trade ->
+// reward / done / reset -> obs_{t+1} (LDS + HBM)   on its own.  The env state
+// (cash, cursor, episode sums: registers of 64 "ledger" lanes; holdings and
+// current prices: LDS) never leaves the compute unit during the rollout, and
+// the next observation is assembled directly in the LDS tile the actor reads
+// its input from.  Per env-step the kernel therefore moves only the bytes the
+// method itself needs: noise and the next market row in, observation, raw
+// action, reward / done / log-prob out.
+//
+// Trade execution reproduces, operation for operation in binary32, the serial
+// rule "all sales in stock order, then all purchases in stock order, each
+// limited by the cash left": everything that does not depend on the running
+// cash (wanted shares, sale quantities and proceeds, unit costs, full-purchase
+// outlays) is computed by all 512 lanes in parallel; one ledger lane per env
+// then walks the cash chain.  A purchase takes the division path only when the
+// cash is between one share and the full wish; outside that range the result
+// of the division path is known without dividing (see buy_step).
+//
+// Compiled with floating-point contraction off (integer decisions depend on
+// one rounding per operation); the network code uses explicit fmaf.
+#include "pod_internal.h"
+#include "pod_tile.h"
+
+namespace pod {
+
+namespace {
+
+using namespace tile;
+
+constexpr int NW = 8;
+constexpr int NT = NW * 64;
+constexpr int E = BM;            // envs per workgroup
+constexpr int PAIRS_MAX = 4;     // (env, stock) pairs per lane: D <= 32
+constexpr int IND_MAX = 35;      // indicator values per lane (lanes 64..511): D*K <= 245
+constexpr int NT_IND = NT - 64;  // lanes that carry indicator values
+
+struct Row {
+  int32_t row_val;  // market row the portfolio is valued at (cursor + 1)
+  int32_t row_obs;  // market row of the next observation (row 0 of the path after an episode end)
+  int32_t done;
+  int32_t pad;
+};
+
+struct FusedArgs {
+  EnvDims d;
+  EnvState st;
+  const float *price, *ind;
+  PackedNet actor;
+  int32_t envs_per_agent;
+  int32_t T;
+  const float *noise;      // [T, N, D]
+  const float *mu_forced;  // [T, N, D] or null (then the actor runs)
+  float *obs;              // [T+1, N, S]
+  float *act_raw;          // [T, N, D]
+  float *reward;           // [T, N]
+  uint8_t *done;           // [T, N]
+  float *logp;             // opt [T, N]
+  float *mu_out;           // opt [T, N, D]
+  int32_t *shares;         // opt [T, N, D]
+  int32_t xpitch, hpitch;
+  uint32_t d_magic, dk_magic;  // ceil(2^32 / D), ceil(2^32 / (D K))
+};
+
+__device__ inline Row row_of(const EnvDims &d, int32_t tau, int32_t n) {
+  const int32_t m = d.M == 1 ? 0 : n;
+  Row r;
+  r.row_val = (tau + 1) * d.M + m;
+  r.done = (tau + 1 == d.H);
+  r.row_obs = r.done ? m : r.row_val;
+  r.pad = 0;
+  return r;
+}
+
+// One purchase of the ledger: k > 0 wanted shares at unit cost u (price * (1 + c)).
+// Reference rule (binary32):  m = floor(cash / u); q = min(k, max(m, 0)); if (q * u > cash) q -= 1.
+//  - cash >= fl((k+1) u)  implies cash >= k u exactly, hence fl(cash / u) >= k and q = k; the outlay fl(k u)
+//    is <= fl((k+1) u) <= cash, so the guard cannot fire.
+//  - cash < u  implies fl(cash / u) <= 1, and if it rounds to 1 the guard (u > cash) takes the share back: q = 0.
+//  - otherwise the division is executed.
+__device__ inline void buy_step(float &cash, int32_t k, float u, float full_outlay, float full_thresh, int32_t &q) {
+  if (cash >= full_thresh) {
+    q = k;
+    cash = cash - full_outlay;
+  } else if (cash < u) {
+    q = 0;
+  } else {
+    const float ratio = cash / u;
+    int32_t m = (int32_t)floorf(ratio);
+    m = max(m, 0);
+    q = min(k, m);
+    float outlay = (float)q * u;
+    if (outlay > cash) {
+      q -= 1;
+      outlay = (float)q * u;
+    }
+    cash = cash - outlay;
+  }
+}
+
+template <bool BF16, int CTH, int NKB1, int NKB2, bool ACTOR>
+__global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
+  using O = tile::Op<BF16>;
+  extern __shared__ __align__(16) unsigned char lds[];
+  const EnvDims &d = a.d;
+  const int D = d.D, Dp = D | 1, DK = D * d.K, S = d.S;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n0 = blockIdx.x * E;
+  const size_t N = (size_t)d.N;
+
+  // ---- LDS carve-up.  The env scratch arrays alias the hidden tile: they live between the end of the output
+  // layer and the next step's first epilogue.  The policy means alias the head of the input tile, which is dead
+  // between layer 1 and the write of the next observation.
+  unsigned char *ldsH = lds;
+  unsigned char *ldsX = ldsH + (size_t)BM * a.hpitch;
+  u32x4 *ldsW3 = reinterpret_cast<u32x4 *>(ldsX + (size_t)BM * a.xpitch);
+  float *ldsBias = reinterpret_cast<float *>(ldsW3 + (ACTOR ? (size_t)a.actor.nkb[2] * 64 : 0));
+  int32_t *s_h = reinterpret_cast<int32_t *>(ldsBias + (ACTOR ? (a.actor.nct[0] + a.actor.nct[1] + a.actor.nct[2]) * 32 : 0));
+  float *s_p = reinterpret_cast<float *>(s_h + E * Dp);  // prices the trades execute at
+  Row *s_row = reinterpret_cast<Row *>(s_p + E * Dp);
+  float *s_cash = reinterpret_cast<float *>(s_row + E);
+  // scratch in the hidden tile
+  int32_t *s_k = reinterpret_cast<int32_t *>(ldsH);        // wanted shares
+  float *s_val = reinterpret_cast<float *>(s_k + E * Dp);   // sale proceeds (k < 0) or unit cost (k > 0)
+  float *s_out = s_val + E * Dp;                            // outlay of the full purchase
+  float *s_thr = s_out + E * Dp;                            // cash from which the full purchase is certain
+  int32_t *s_q = reinterpret_cast<int32_t *>(s_thr + E * Dp);  // executed shares, signed
+  float *s_pv = reinterpret_cast<float *>(s_q + E * Dp);    // valuation prices
+  float *s_e2 = s_pv + E * Dp;                              // squared noise
+  float *s_mu = reinterpret_cast<float *>(ldsX);            // [E][32] policy means (actor variant)
+
+  // ---- ledger lanes (wavefront 0): per-env scalars in registers for the whole rollout
+  float cash = 0.0f;
+  int32_t tau = 0, ep_cnt = 0;
+  double asset = 0.0, ep_ret = 0.0, ep_sum = 0.0, ep_sqsum = 0.0;
+
+  Net net;
+  if (ACTOR) {
+    net = net_of(a.actor, (n0 % d.N) / a.envs_per_agent);
+    stage_net<NT>(net, ldsBias, ldsW3, tid);
+    // padded k columns of the input tile must read as zero
+    for (int i = tid; i < BM * a.xpitch / 4; i += NT) reinterpret_cast<uint32_t *>(ldsX)[i] = 0u;
+  }
+  __syncthreads();
+
+  // ---- prologue: load the state, emit observation 0
+  if (wave == 0) {
+    const int n = n0 + lane;
+    cash = a.st.cash[n];
+    tau = a.st.tau[n];
+    ep_ret = a.st.ep_ret[n];
+    ep_sum = a.st.ep_sum[n];
+    ep_sqsum = a.st.ep_sqsum[n];
+    ep_cnt = a.st.ep_cnt[n];
+    Row r;  // "next observation" of a virtual step before the rollout = the current cursor
+    const int32_t m = d.M == 1 ? 0 : n;
+    r.row_val = tau * d.M + m;
+    r.row_obs = r.row_val;
+    r.done = 0;
+    r.pad = 0;
+    s_row[lane] = r;
+    s_cash[lane] = cash;
+  }
+  for (int idx = tid; idx < E * D; idx += NT) {
+    const int dd = idx / E, e = idx - dd * E;
+    s_h[e * Dp + dd] = a.st.h[(size_t)dd * N + n0 + e];
+  }
+  __syncthreads();
+
+  // Writes the market part of an observation (prices, indicators at row_obs) to HBM row `obs_row` and into the
+  // LDS input tile, and refreshes the execution prices.  `pv_obs` / `ind_v`: values already in registers.
+  // (Each helper starts from an opaque copy of the thread index: the (env, column) decompositions and the
+  // addresses derived from them are loop invariant, and the compiler would otherwise keep a hundred of them
+  // in registers across the matrix-core code instead of recomputing a few integer operations.)
+  auto emit_market = [&](float *obs_row, const float (&p_obs)[PAIRS_MAX], const float (&ind_v)[IND_MAX]) {
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+#pragma unroll
+    for (int i = 0; i < PAIRS_MAX; ++i) {
+      const int idx = tid + NT * i;
+      if (idx < E * D) {
+        const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
+        const float v = p_obs[i];
+        s_p[e * Dp + dd] = v;
+        const float sv = v * d.s_price;
+        obs_row[(size_t)(n0 + e) * S + 1 + dd] = sv;
+        if (ACTOR) O::store1(ldsX + (size_t)e * a.xpitch + (1 + dd) * O::ESZ, sv);
+      }
+    }
+    if (tid >= 64) {
+#pragma unroll
+      for (int i = 0; i < IND_MAX; ++i) {
+        const int idx = (tid - 64) + NT_IND * i;
+        if (idx < E * DK) {
+          const int e = (int)__umulhi((unsigned)idx, a.dk_magic), j = idx - e * DK;
+          const float sv = ind_v[i] * d.s_ind;
+          obs_row[(size_t)(n0 + e) * S + 1 + 2 * D + j] = sv;
+          if (ACTOR) O::store1(ldsX + (size_t)e * a.xpitch + (1 + 2 * D + j) * O::ESZ, sv);
+        }
+      }
+    }
+  };
+  // Portfolio part of an observation: cash and holdings from the ledger.
+  auto emit_portfolio = [&](float *obs_row) {
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    if (tid < E) {
+      const float sv = s_cash[tid] * d.s_cash;
+      obs_row[(size_t)(n0 + tid) * S] = sv;
+      if (ACTOR) {
+        O::store1(ldsX + (size_t)tid * a.xpitch, sv);
+        // the policy means were parked over the head of this tile: restore the zero k padding of every row
+        const int kp = (a.xpitch - 16) / O::ESZ;
+        for (int c = S; c < kp; ++c) O::store1(ldsX + (size_t)tid * a.xpitch + c * O::ESZ, 0.0f);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < PAIRS_MAX; ++i) {
+      const int idx = tid + NT * i;
+      if (idx < E * D) {
+        const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
+        const float sv = (float)s_h[e * Dp + dd] * d.s_hold;
+        obs_row[(size_t)(n0 + e) * S + 1 + D + dd] = sv;
+        if (ACTOR) O::store1(ldsX + (size_t)e * a.xpitch + (1 + D + dd) * O::ESZ, sv);
+      }
+    }
+  };
+  // Loads of the market rows named in s_row, into registers (issued early, consumed after the actor).
+  float r_eps[PAIRS_MAX], r_mu[PAIRS_MAX], r_pv[PAIRS_MAX], r_po[PAIRS_MAX], r_ind[IND_MAX];
+  auto fetch_market = [&]() {
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+#pragma unroll
+    for (int i = 0; i < PAIRS_MAX; ++i) {
+      const int idx = min(tid + NT * i, E * D - 1);
+      const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
+      const Row r = s_row[e];
+      r_pv[i] = a.price[(size_t)r.row_val * D + dd];
+      r_po[i] = a.price[(size_t)r.row_obs * D + dd];
+    }
+    if (tid >= 64) {
+#pragma unroll
+      for (int i = 0; i < IND_MAX; ++i) {
+        const int idx = min((tid - 64) + NT_IND * i, max(E * DK - 1, 0));
+        const int e = (int)__umulhi((unsigned)idx, a.dk_magic), j = idx - e * DK;
+        if (DK > 0) r_ind[i] = a.ind[(size_t)s_row[e].row_obs * DK + j];
+      }
+    }
+  };
+  auto fetch_step_inputs = [&](int t) {
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const size_t g0 = ((size_t)t * N + n0) * D;
+#pragma unroll
+    for (int i = 0; i < PAIRS_MAX; ++i) {
+      const int idx = min(tid + NT * i, E * D - 1);
+      r_eps[i] = a.noise[g0 + idx];
+      if (!ACTOR) r_mu[i] = a.mu_forced[g0 + idx];
+    }
+  };
+
+  {
+    fetch_market();
+    emit_market(a.obs, r_po, r_ind);
+    emit_portfolio(a.obs);
+  }
+  __syncthreads();
+  if (wave == 0) {
+    // account value the first reward is measured against; cursor rows of step 0
+    const int e = lane;
+    double v = (double)cash;
+    for (int dd = 0; dd < D; ++dd) v += (double)s_h[e * Dp + dd] * (double)s_p[e * Dp + dd];
+    asset = v;
+    s_row[e] = row_of(d, tau, n0 + e);
+  }
+
+  for (int t = 0; t < a.T; ++t) {
+    __syncthreads();  // observation t complete in LDS; ledger rows of step t visible
+    float *obs_next = a.obs + (size_t)(t + 1) * N * S;
+    const size_t g0 = ((size_t)t * N + n0) * D;
+
+    if (ACTOR) {
+      mlp_tile<BF16, NW, CTH, false, NKB1, NKB2>(
+          net, ldsX, a.xpitch, ldsH, a.hpitch, ldsBias, ldsW3, tid,
+          [&]() {
+            fetch_step_inputs(t);
+            fetch_market();
+          },
+          [&]() {},
+          [&](int b, int f, float y) { s_mu[b * 32 + f] = y; });
+    } else {
+      fetch_step_inputs(t);
+      fetch_market();
+    }
+    __syncthreads();  // means in LDS; the hidden tile is free for the env scratch
+
+    // ---- everything that does not depend on the running cash, all lanes
+    int tid_p = threadIdx.x;
+    asm volatile("" : "+v"(tid_p));
+#pragma unroll
+    for (int i = 0; i < PAIRS_MAX; ++i) {
+      const int idx = tid_p + NT * i;
+      if (idx < E * D) {
+        const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
+        const int o = e * Dp + dd;
+        const float mu = ACTOR ? s_mu[e * 32 + dd] : r_mu[i];
+        const float eps = r_eps[i];
+        const float a_raw = mu + d.sigma * eps;
+        a.act_raw[g0 + idx] = a_raw;
+        if (ACTOR && a.mu_out) a.mu_out[g0 + idx] = mu;
+        const float ac = fminf(1.0f, fmaxf(-1.0f, a_raw));
+        const int32_t k = (int32_t)truncf(ac * d.hmax);
+        const float p = s_p[o];
+        int32_t q = 0;
+        float val = 0.0f, outl = 0.0f, thr = 0.0f;
+        if (k < 0) {
+          const int32_t h = s_h[o];
+          q = min(-k, h);
+          s_h[o] = h - q;
+          const float gross = p * (float)q;
+          val = gross * d.one_minus_c;
+          q = -q;
+        } else if (k > 0) {
+          val = p * d.one_plus_c;
+          outl = (float)k * val;
+          thr = (float)(k + 1) * val;
+        }
+        s_k[o] = k;
+        s_val[o] = val;
+        s_out[o] = outl;
+        s_thr[o] = thr;
+        s_q[o] = q;
+        s_pv[o] = r_pv[i];
+        s_e2[o] = eps * eps;
+      }
+    }
+    __syncthreads();
+
+    if (wave == 0) {
+      // ---- the ledger: one lane per env walks the cash chain in stock order
+      const int e = lane, n = n0 + e, o0 = e * Dp;
+      float e2 = 0.0f;
+      for (int dd = 0; dd < D; ++dd) {
+        const int32_t k = s_k[o0 + dd];
+        const float v = s_val[o0 + dd];
+        e2 += s_e2[o0 + dd];
+        cash = k < 0 ? cash + v : cash;
+      }
+      for (int dd = 0; dd < D; ++dd) {
+        const int32_t k = s_k[o0 + dd];
+        if (k > 0) {
+          int32_t q;
+          buy_step(cash, k, s_val[o0 + dd], s_out[o0 + dd], s_thr[o0 + dd], q);
+          s_h[o0 + dd] += q;
+          s_q[o0 + dd] = q;
+        }
+      }
+      double asset1 = (double)cash;
+      for (int dd = 0; dd < D; ++dd) asset1 += (double)s_h[o0 + dd] * (double)s_pv[o0 + dd];
+      const double r = (asset1 - asset) * (double)d.rho;
+      asset = asset1;
+      ep_ret += r;
+      const int dn = s_row[e].done;
+      const size_t tn = (size_t)t * N + n;
+      a.reward[tn] = (float)r;
+      a.done[tn] = (uint8_t)dn;
+      if (a.logp) a.logp[tn] = fmaf(-0.5f, e2, d.logp_const);
+      if (dn) {
+        ep_sum += ep_ret;
+        ep_sqsum += ep_ret * ep_ret;
+        ep_cnt += 1;
+        ep_ret = 0.0;
+        cash = d.cash0;
+        asset = (double)d.cash0;
+        tau = 0;
+      } else {
+        tau += 1;
+      }
+      s_cash[e] = cash;
+    }
+    // ---- meanwhile (and the ledger lanes afterwards): market part of observation t+1
+    emit_market(obs_next, r_po, r_ind);
+    __syncthreads();
+
+    // ---- executed trades out; episode ends clear the holdings; portfolio part of observation t+1
+    int tid_q = threadIdx.x;
+    asm volatile("" : "+v"(tid_q));
+#pragma unroll
+    for (int i = 0; i < PAIRS_MAX; ++i) {
+      const int idx = tid_q + NT * i;
+      if (idx < E * D) {
+        const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
+        if (a.shares) a.shares[g0 + idx] = s_q[e * Dp + dd];
+        if (s_row[e].done) s_h[e * Dp + dd] = 0;
+      }
+    }
+    __syncthreads();
+    emit_portfolio(obs_next);
+    if (wave == 0) s_row[lane] = row_of(d, tau, n0 + lane);
+  }
+
+  // ---- epilogue: state back to the workspace
+  __syncthreads();
+  if (wave == 0) {
+    const int n = n0 + lane;
+    a.st.cash[n] = cash;
+    a.st.tau[n] = tau;
+    a.st.ep_ret[n] = ep_ret;
+    a.st.ep_sum[n] = ep_sum;
+    a.st.ep_sqsum[n] = ep_sqsum;
+    a.st.ep_cnt[n] = ep_cnt;
+  }
+  for (int idx = tid; idx < E * D; idx += NT) {
+    const int dd = idx / E, e = idx - dd * E;
+    a.st.h[(size_t)dd * N + n0 + e] = s_h[e * Dp + dd];
+  }
+}
+
+struct FusedShape {
+  int cth, nkb1, nkb2;
+};
+
+}  // namespace
+
+// Shapes the persistent kernel covers: bf16 networks whose whole input tile, hidden tile and output-layer
+// weights fit in LDS next to the env arrays; N a multiple of 64; D <= 32; D K <= 245; one output feature tile.
+bool fused_supported(const pr_config &c) {
+  const int D = c.n_stocks, DK = c.n_stocks * c.n_ind, S = 1 + 2 * D + DK, Hd = c.hidden;
+  if (c.n_envs % 64 != 0 || D > 32 || DK > 245 || DK < 1 || S < 4) return false;
+  if (c.mlp_dtype != PR_MLP_BF16) return false;
+  if (Hd % 32 != 0 || Hd < 256 || Hd > 512 || (Hd / 32) % NW != 0) return false;
+  if (c.n_agents > 1 && (c.n_envs / c.n_agents) % 64 != 0) return false;
+  return fused_lds_bytes(c, true) + 1024 <= 160 * 1024;
+}
+
+size_t fused_lds_bytes(const pr_config &c, bool with_actor) {
+  const int D = c.n_stocks, DK = c.n_stocks * c.n_ind, S = 1 + 2 * D + DK, Hd = c.hidden, Dp = D | 1;
+  const int bf = c.mlp_dtype == PR_MLP_BF16, esz = bf ? 2 : 4, KB = bf ? 16 : 8;
+  const int kp = (S + KB - 1) / KB * KB;
+  size_t env_scratch = (size_t)7 * E * Dp * 4;
+  size_t hid = (size_t)BM * tile_pitch(Hd, esz);
+  if (hid < env_scratch) hid = env_scratch;
+  size_t n = hid + (size_t)BM * tile_pitch(kp, esz);
+  if (with_actor) n += (size_t)(Hd / KB) * 1024 + (size_t)(2 * (Hd / 32) + 1) * 32 * 4;
+  n += (size_t)2 * E * Dp * 4 + (size_t)E * (sizeof(Row) + sizeof(float));
+  return n;
+}
+
+template <bool ACTOR, int CTH, int NKB1, int NKB2>
+static hipError_t launch_fused_inst(hipStream_t st, const FusedArgs &a, unsigned blocks, size_t lds) {
+  auto kern = rollout_fused_kernel<true, CTH, NKB1, NKB2, ACTOR>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(NT), lds, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_rollout_fused(hipStream_t st, const pr_config &c, const EnvDims &d, const EnvState &s,
+                                const float *price, const float *ind, const PackedNet &actor, int32_t envs_per_agent,
+                                int32_t T, const float *noise, const float *mu_forced, const pr_buffers &out) {
+  if (!fused_supported(c)) return hipErrorInvalidValue;
+  FusedArgs a;
+  a.d = d;
+  a.st = s;
+  a.price = price;
+  a.ind = ind;
+  a.actor = actor;
+  a.envs_per_agent = envs_per_agent;
+  a.T = T;
+  a.noise = noise;
+  a.mu_forced = mu_forced;
+  a.obs = out.obs;
+  a.act_raw = out.act_raw;
+  a.reward = out.reward;
+  a.done = out.done;
+  a.logp = out.logp;
+  a.mu_out = mu_forced ? nullptr : out.mu;
+  a.shares = out.shares;
+  const int KB = 16, esz = 2;
+  const int DK = d.D * d.K;
+  a.xpitch = tile_pitch(actor.nkb[0] * KB, esz);
+  a.hpitch = tile_pitch(c.hidden, esz);
+  // the env scratch must fit in the hidden tile
+  const size_t env_scratch = (size_t)7 * E * (d.D | 1) * 4;
+  if ((size_t)BM * a.hpitch < env_scratch) a.hpitch = (int32_t)((env_scratch + BM - 1) / BM + 15) / 16 * 16;
+  a.d_magic = (uint32_t)((0x100000000ull + (uint64_t)d.D - 1) / (uint64_t)d.D);
+  a.dk_magic = (uint32_t)((0x100000000ull + (uint64_t)DK - 1) / (uint64_t)DK);
+  const bool with_actor = mu_forced == nullptr;
+  // must mirror the carve-up at the top of the kernel
+  size_t lds = (size_t)BM * a.hpitch + (size_t)BM * a.xpitch;
+  if (with_actor) lds += (size_t)actor.nkb[2] * 1024 + (size_t)(actor.nct[0] + actor.nct[1] + actor.nct[2]) * 32 * 4;
+  lds += (size_t)2 * E * (d.D | 1) * 4 + (size_t)E * (sizeof(Row) + sizeof(float));
+  if (lds > 160 * 1024) return hipErrorInvalidValue;
+  const unsigned blocks = (unsigned)(d.N / E);
+  const int cth = (c.hidden / 32) / NW;
+  if (!with_actor) return launch_fused_inst<false, 1, 0, 0>(st, a, blocks, lds);
+  if (cth == 2 && actor.nkb[0] == 19 && actor.nkb[1] == 32) return launch_fused_inst<true, 2, 19, 32>(st, a, blocks, lds);
+  if (cth == 2) return launch_fused_inst<true, 2, 0, 0>(st, a, blocks, lds);
+  if (cth == 1) return launch_fused_inst<true, 1, 0, 0>(st, a, blocks, lds);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace pod

@@ -81,4 +81,13 @@ hipError_t launch_mlp(hipStream_t st, const PackedNet &net, int64_t rows, const 
                       int32_t N, int32_t envs_per_agent);
 bool mlp_supported(int S, int Hd, int O, int bf16);
 
+// ------------------------------------------------------- persistent rollout
+// One launch for T steps: each workgroup keeps 64 envs on its compute unit (actor forward, sampling, trading
+// step, observation assembly).  mu_forced != null replaces the actor by caller-supplied means.
+bool fused_supported(const pr_config &c);
+size_t fused_lds_bytes(const pr_config &c, bool with_actor);
+hipError_t launch_rollout_fused(hipStream_t st, const pr_config &c, const EnvDims &d, const EnvState &s,
+                                const float *price, const float *ind, const PackedNet &actor, int32_t envs_per_agent,
+                                int32_t T, const float *noise, const float *mu_forced, const pr_buffers &out);
+
 }  // namespace pod

@@ -21,10 +21,10 @@ def _dev(d):
     return {k: torch.from_numpy(np.ascontiguousarray(v)).to(DEV) for k, v in d.items()}
 
 
-def _make(w, horizon=None, n_market=None, steps=None):
+def _make(w, horizon=None, n_market=None, steps=None, schedule=pr.PR_SCHED_STEPWISE):
     H = w.steps if horizon is None else horizon
     d = inputs.make_all(w, horizon=H, n_market=n_market, steps=steps)
-    cfg = pr.make_config(w, horizon=H, n_market=n_market)
+    cfg = pr.make_config(w, horizon=H, n_market=n_market, schedule=schedule)
     ro = pr.Rollout(cfg, torch.from_numpy(d["price"]).to(DEV), torch.from_numpy(d["ind"]).to(DEV), _dev(d["actor"]),
                     _dev(d["critic"]))
     return d, ro, oracle.cfg_from_workload(w, horizon=H)
@@ -299,3 +299,69 @@ def test_leaderboard_ties_and_unfinished_agents():
     assert parity.to_np(rank).tolist() == [1, 2, 0, 3]
     assert parity.to_np(mean).tolist() == [-1.0, 2.5, 2.5, -np.inf]
     assert parity.to_np(var).tolist() == [0.0, 0.0, 0.0, 0.0]
+
+
+# ------------------------------------------------- persistent (fused) schedule
+
+FUSED = pr.PR_SCHED_FUSED
+
+
+def _run(w, H, T, schedule, n_market=None, forced_mu=None, calls=1):
+    d, ro, ocfg = _make(w, horizon=H, n_market=n_market, steps=T, schedule=schedule)
+    noise = torch.from_numpy(d["noise"]).to(DEV)
+    outs = []
+    per = T // calls
+    for c in range(calls):
+        sl = slice(c * per, (c + 1) * per)
+        out = ro.alloc_buffers(per, value=forced_mu is None, logp=True, mu=forced_mu is None, shares=True)
+        if forced_mu is None:
+            ro.step_T(per, noise[sl].contiguous(), out)
+        else:
+            ro.step_forced(per, torch.from_numpy(forced_mu[sl]).to(DEV).contiguous(), noise[sl].contiguous(), out)
+        outs.append(out)
+    state = ro.get_state()
+    torch.cuda.synchronize()
+    return d, ro, ocfg, outs, state
+
+
+@pytest.mark.parametrize("hidden,N,agents,H,n_market", [(512, 128, 1, 10, None), (256, 192, 1, 24, None),
+                                                         (512, 128, 2, 7, None), (512, 64, 1, 24, 1)])
+def test_fused_schedule_equals_stepwise_bit_for_bit(hidden, N, agents, H, n_market):
+    T = 24
+    w = inputs.WORKLOADS["large"].replace(n_envs=N, n_agents=agents, hidden=hidden, steps=T)
+    _, _, _, (a,), sa = _run(w, H, T, pr.PR_SCHED_STEPWISE, n_market)
+    _, _, _, (b,), sb = _run(w, H, T, FUSED, n_market)
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+    for k in sa:
+        assert torch.equal(sa[k], sb[k]), k
+    assert int(a["done"].sum()) == (T // H) * N
+
+
+def test_fused_forced_env_stage_matches_checker_with_resets_and_cash_starved():
+    T, H = 40, 16
+    w = inputs.WORKLOADS["large"].replace(n_envs=128, steps=T, cash0=20000.0)
+    rng = np.random.default_rng(21)
+    mu = rng.uniform(-1, 1, (T, w.n_envs, w.n_stocks)).astype(np.float32)
+    d, ro, ocfg, (out,), st = _run(w, H, T, FUSED, forced_mu=mu)
+    rec = _rec(out)
+    chk, ost = parity.check_env_record(w, ocfg, rec, d["price"], d["ind"], d["noise"], mu)
+    assert np.array_equal(parity.to_np(st["cash"]), ost.cash) and np.array_equal(parity.to_np(st["holdings"]), ost.h)
+    assert np.array_equal(parity.to_np(st["cursor"]), ost.tau) and np.array_equal(parity.to_np(st["ep_count"]), ost.ep_cnt)
+    np.testing.assert_allclose(parity.to_np(st["ep_sum"]), ost.ep_sum, rtol=1e-9, atol=1e-9)
+    wanted = np.trunc(np.clip(rec["act_raw"], -1, 1) * np.float32(100.0))
+    assert ((wanted > 0) & (rec["shares"] < wanted) & (rec["shares"] > 0)).any()   # the division path ran
+    assert ((wanted > 0) & (rec["shares"] == 0)).any()                               # and the cannot-afford-one path
+    assert (chk["flags"] & oracle.FLAG_GUARD).sum() >= 0
+
+
+def test_fused_rollout_stagewise_against_checker_and_carry_across_calls():
+    T, H = 32, 12
+    w = inputs.WORKLOADS["large"].replace(n_envs=128, steps=T)
+    d, ro, ocfg, outs, st = _run(w, H, T, FUSED, calls=2)
+    ra, rb = _rec(outs[0]), _rec(outs[1])
+    assert np.array_equal(ra["obs"][-1], rb["obs"][0])
+    rec = {k: np.concatenate([ra[k], rb[k]]) for k in ("act_raw", "reward", "done", "shares", "logp", "mu")}
+    rec["obs"] = np.concatenate([ra["obs"], rb["obs"][1:]])
+    rec["value"] = np.concatenate([ra["value"], rb["value"][1:]])
+    _stagewise(w, d, ro, ocfg, T, rec)
