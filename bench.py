@@ -92,7 +92,7 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="large")
-    ap.add_argument("--schedule", default="stepwise", choices=["stepwise", "fused"])
+    ap.add_argument("--schedule", default="fused", choices=["stepwise", "fused"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-envs", type=int, default=192)
     ap.add_argument("--cpu-steps", type=int, default=1024)
