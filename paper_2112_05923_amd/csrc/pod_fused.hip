@@ -344,25 +344,85 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
 
     if (wave == 0) {
       // ---- the ledger: one lane per env walks the cash chain in stock order
-      const int e = lane, n = n0 + e, o0 = e * Dp;
+      // Each pass stages a chunk of the lane's row in registers first, so that the LDS reads of a chunk are
+      // all in flight together and the dependent chain on `cash` runs on registers only.
+      int e = lane;
+      asm volatile("" : "+v"(e));  // per-step opaque, or the chunk addresses are hoisted out of the step loop
+      const int n = n0 + e, o0 = e * Dp;
+      constexpr int CH = 16, DMAX = 32;
       float e2 = 0.0f;
-      for (int dd = 0; dd < D; ++dd) {
-        const int32_t k = s_k[o0 + dd];
-        const float v = s_val[o0 + dd];
-        e2 += s_e2[o0 + dd];
-        cash = k < 0 ? cash + v : cash;
+#pragma unroll
+      for (int c0 = 0; c0 < DMAX; c0 += CH) {
+        if (c0 < D) {
+          int32_t kk[CH];
+          float vv[CH], ee[CH];
+#pragma unroll
+          for (int j = 0; j < CH; ++j) {
+            const bool ok = c0 + j < D;
+            const int o = o0 + min(c0 + j, D - 1);
+            kk[j] = ok ? s_k[o] : 0;
+            vv[j] = s_val[o];
+            ee[j] = ok ? s_e2[o] : 0.0f;
+          }
+#pragma unroll
+          for (int j = 0; j < CH; ++j) {
+            e2 += ee[j];
+            cash = kk[j] < 0 ? cash + vv[j] : cash;
+          }
+        }
       }
-      for (int dd = 0; dd < D; ++dd) {
-        const int32_t k = s_k[o0 + dd];
-        if (k > 0) {
-          int32_t q;
-          buy_step(cash, k, s_val[o0 + dd], s_out[o0 + dd], s_thr[o0 + dd], q);
-          s_h[o0 + dd] += q;
-          s_q[o0 + dd] = q;
+#pragma unroll
+      for (int c0 = 0; c0 < DMAX; c0 += CH) {
+        if (c0 < D) {
+          int32_t kk[CH], hh[CH];
+          float uu[CH], oo[CH], tt[CH];
+#pragma unroll
+          for (int j = 0; j < CH; ++j) {
+            const bool ok = c0 + j < D;
+            const int o = o0 + min(c0 + j, D - 1);
+            kk[j] = ok ? s_k[o] : 0;
+            uu[j] = s_val[o];
+            oo[j] = s_out[o];
+            tt[j] = s_thr[o];
+            hh[j] = s_h[o];
+          }
+#pragma unroll
+          for (int j = 0; j < CH; ++j) {
+            const int32_t k = kk[j];
+            if (k > 0) {  // (a sale or a hold leaves its slot as the first pass wrote it)
+              const bool full = cash >= tt[j], none = cash < uu[j];
+              int32_t q = full ? k : 0;
+              float outlay = full ? oo[j] : 0.0f;
+              if (!full && !none) {
+                // between one share and the full wish: the division decides (see buy_step)
+                buy_step(cash, k, uu[j], oo[j], tt[j], q);
+              } else {
+                cash = cash - outlay;
+              }
+              s_h[o0 + c0 + j] = hh[j] + q;
+              s_q[o0 + c0 + j] = q;
+            }
+          }
         }
       }
       double asset1 = (double)cash;
-      for (int dd = 0; dd < D; ++dd) asset1 += (double)s_h[o0 + dd] * (double)s_pv[o0 + dd];
+#pragma unroll
+      for (int c0 = 0; c0 < DMAX; c0 += CH) {
+        if (c0 < D) {
+          int32_t hh[CH];
+          float pp[CH];
+#pragma unroll
+          for (int j = 0; j < CH; ++j) {
+            const bool ok = c0 + j < D;
+            const int o = o0 + min(c0 + j, D - 1);
+            hh[j] = ok ? s_h[o] : 0;
+            pp[j] = s_pv[o];
+          }
+#pragma unroll
+          for (int j = 0; j < CH; ++j)
+            if (c0 + j < D) asset1 += (double)hh[j] * (double)pp[j];
+        }
+      }
       const double r = (asset1 - asset) * (double)d.rho;
       asset = asset1;
       ep_ret += r;

@@ -295,17 +295,35 @@ __device__ inline void stage_net(const Net &net, float *ldsBias, u32x4 *ldsW3, i
 }
 
 // Output layer with one feature tile: weights from LDS (block kb = 64 lanes x 16 B), activations from ldsH.
-template <bool BF16>
+// NKB > 0: straight-line code over a compile-time number of k-blocks with two accumulators (even / odd
+// k-blocks), which halves the dependent chain of matrix instructions and lets the LDS reads run ahead.
+template <bool BF16, int NKB>
 __device__ inline void mma_out_lds(f32x16 &acc, const u32x4 *ldsW3, const unsigned char *ldsH, int hpitch, int nkb,
                                    int bt, int lane) {
   using O = Op<BF16>;
   const int brow = lane & 31, g = lane >> 5;
   const unsigned char *xbase = ldsH + (size_t)(bt * 32 + brow) * hpitch + 16 * g;
-
-  for (int kb = 0; kb < nkb; ++kb) {
-    const u32x4 wv = ldsW3[kb * 64 + lane];
-    const u32x4 xv = *reinterpret_cast<const u32x4 *>(xbase + kb * 32);
-    O::mma(wv, xv, acc);
+  if (NKB > 0) {
+    f32x16 acc2;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc2[i] = 0.0f;
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) {
+      const u32x4 wv = ldsW3[kb * 64 + lane];
+      const u32x4 xv = *reinterpret_cast<const u32x4 *>(xbase + kb * 32);
+      if (kb & 1)
+        O::mma(wv, xv, acc2);
+      else
+        O::mma(wv, xv, acc);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] += acc2[i];
+  } else {
+    for (int kb = 0; kb < nkb; ++kb) {
+      const u32x4 wv = ldsW3[kb * 64 + lane];
+      const u32x4 xv = *reinterpret_cast<const u32x4 *>(xbase + kb * 32);
+      O::mma(wv, xv, acc);
+    }
   }
 }
 
@@ -360,7 +378,7 @@ __device__ inline void mlp_tile(const Net &net, const unsigned char *ldsX, int x
     if (w < 2) {
       f32x16 acc[1][1];
       zero_acc<1, 1>(acc);
-      mma_out_lds<BF16>(acc[0][0], ldsW3, ldsH, hpitch, net.nkb[2], w, lane);
+      mma_out_lds<BF16, NKB2>(acc[0][0], ldsW3, ldsH, hpitch, net.nkb[2], w, lane);  // nkb[2] == nkb[1]
       epilogue_out<1, 1>(acc, lb3, net.out_dim, net.out_tanh, 1, 0, w, lane, sink);
     }
     late();
