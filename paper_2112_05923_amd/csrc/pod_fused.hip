@@ -36,6 +36,8 @@ constexpr int NW = 8;
 constexpr int NT = NW * 64;
 constexpr int E = BM;            // envs per workgroup
 constexpr int PAIRS_MAX = 4;     // (env, stock) pairs per lane: D <= 32
+constexpr int DMAX = 32;         // stock slots per env row in LDS; slots D..31 hold neutral values (k = 0, h = 0)
+constexpr int kDp = DMAX + 1;    // odd row pitch: the per-env serial walks of the ledger hit distinct banks
 constexpr int IND_MAX = 35;      // indicator values per lane (lanes 64..511): D*K <= 245
 constexpr int NT_IND = NT - 64;  // lanes that carry indicator values
 
@@ -107,7 +109,8 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   using O = tile::Op<BF16>;
   extern __shared__ __align__(16) unsigned char lds[];
   const EnvDims &d = a.d;
-  const int D = d.D, Dp = D | 1, DK = D * d.K, S = d.S;
+  const int D = d.D, DK = D * d.K, S = d.S;
+  constexpr int Dp = kDp;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -171,6 +174,11 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     const int dd = idx / E, e = idx - dd * E;
     s_h[e * Dp + dd] = a.st.h[(size_t)dd * N + n0 + e];
   }
+  if (tid < E)
+    for (int dd = D; dd < DMAX; ++dd) {
+      s_h[tid * Dp + dd] = 0;
+      s_p[tid * Dp + dd] = 0.0f;
+    }
   __syncthreads();
 
   // Writes the market part of an observation (prices, indicators at row_obs) to HBM row `obs_row` and into the
@@ -340,6 +348,17 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         s_e2[o] = eps * eps;
       }
     }
+    if (tid_p < E)
+      for (int dd = D; dd < DMAX; ++dd) {
+        const int o = tid_p * Dp + dd;
+        s_k[o] = 0;
+        s_val[o] = 0.0f;
+        s_out[o] = 0.0f;
+        s_thr[o] = 0.0f;
+        s_q[o] = 0;
+        s_pv[o] = 0.0f;
+        s_e2[o] = 0.0f;
+      }
     __syncthreads();
 
     if (wave == 0) {
@@ -349,79 +368,67 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       int e = lane;
       asm volatile("" : "+v"(e));  // per-step opaque, or the chunk addresses are hoisted out of the step loop
       const int n = n0 + e, o0 = e * Dp;
-      constexpr int CH = 16, DMAX = 32;
+      constexpr int CH = 16;
       float e2 = 0.0f;
 #pragma unroll
       for (int c0 = 0; c0 < DMAX; c0 += CH) {
-        if (c0 < D) {
-          int32_t kk[CH];
-          float vv[CH], ee[CH];
+        int32_t kk[CH];
+        float vv[CH], ee[CH];
 #pragma unroll
-          for (int j = 0; j < CH; ++j) {
-            const bool ok = c0 + j < D;
-            const int o = o0 + min(c0 + j, D - 1);
-            kk[j] = ok ? s_k[o] : 0;
-            vv[j] = s_val[o];
-            ee[j] = ok ? s_e2[o] : 0.0f;
-          }
+        for (int j = 0; j < CH; ++j) {
+          kk[j] = s_k[o0 + c0 + j];
+          vv[j] = s_val[o0 + c0 + j];
+          ee[j] = s_e2[o0 + c0 + j];
+        }
 #pragma unroll
-          for (int j = 0; j < CH; ++j) {
-            e2 += ee[j];
-            cash = kk[j] < 0 ? cash + vv[j] : cash;
-          }
+        for (int j = 0; j < CH; ++j) {
+          e2 += ee[j];
+          cash = kk[j] < 0 ? cash + vv[j] : cash;
         }
       }
 #pragma unroll
       for (int c0 = 0; c0 < DMAX; c0 += CH) {
-        if (c0 < D) {
-          int32_t kk[CH], hh[CH];
-          float uu[CH], oo[CH], tt[CH];
+        int32_t kk[CH], hh[CH];
+        float uu[CH], oo[CH], tt[CH];
 #pragma unroll
-          for (int j = 0; j < CH; ++j) {
-            const bool ok = c0 + j < D;
-            const int o = o0 + min(c0 + j, D - 1);
-            kk[j] = ok ? s_k[o] : 0;
-            uu[j] = s_val[o];
-            oo[j] = s_out[o];
-            tt[j] = s_thr[o];
-            hh[j] = s_h[o];
+        for (int j = 0; j < CH; ++j) {
+          kk[j] = s_k[o0 + c0 + j];
+          uu[j] = s_val[o0 + c0 + j];
+          oo[j] = s_out[o0 + c0 + j];
+          tt[j] = s_thr[o0 + c0 + j];
+          hh[j] = s_h[o0 + c0 + j];
+        }
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+          const int32_t k = kk[j];
+          const bool buy = k > 0;
+          const bool full = cash >= tt[j], none = cash < uu[j];
+          int32_t q = full ? k : 0;
+          float c_fast = cash - (full ? oo[j] : 0.0f);
+          if (buy && !full && !none) {
+            // between one share and the full wish: the division decides (see buy_step)
+            c_fast = cash;
+            buy_step(c_fast, k, uu[j], oo[j], tt[j], q);
           }
-#pragma unroll
-          for (int j = 0; j < CH; ++j) {
-            const int32_t k = kk[j];
-            if (k > 0) {  // (a sale or a hold leaves its slot as the first pass wrote it)
-              const bool full = cash >= tt[j], none = cash < uu[j];
-              int32_t q = full ? k : 0;
-              float outlay = full ? oo[j] : 0.0f;
-              if (!full && !none) {
-                // between one share and the full wish: the division decides (see buy_step)
-                buy_step(cash, k, uu[j], oo[j], tt[j], q);
-              } else {
-                cash = cash - outlay;
-              }
-              s_h[o0 + c0 + j] = hh[j] + q;
-              s_q[o0 + c0 + j] = q;
-            }
+          if (buy) {  // (a sale or a hold leaves its slot as the first pass wrote it)
+            cash = c_fast;
+            s_h[o0 + c0 + j] = hh[j] + q;
+            s_q[o0 + c0 + j] = q;
           }
         }
       }
       double asset1 = (double)cash;
 #pragma unroll
       for (int c0 = 0; c0 < DMAX; c0 += CH) {
-        if (c0 < D) {
-          int32_t hh[CH];
-          float pp[CH];
+        int32_t hh[CH];
+        float pp[CH];
 #pragma unroll
-          for (int j = 0; j < CH; ++j) {
-            const bool ok = c0 + j < D;
-            const int o = o0 + min(c0 + j, D - 1);
-            hh[j] = ok ? s_h[o] : 0;
-            pp[j] = s_pv[o];
-          }
-#pragma unroll
-          for (int j = 0; j < CH; ++j)
-            if (c0 + j < D) asset1 += (double)hh[j] * (double)pp[j];
+        for (int j = 0; j < CH; ++j) {
+          hh[j] = s_h[o0 + c0 + j];
+          pp[j] = s_pv[o0 + c0 + j];
         }
+#pragma unroll
+        for (int j = 0; j < CH; ++j) asset1 += (double)hh[j] * (double)pp[j];  // empty slots add +0
       }
       const double r = (asset1 - asset) * (double)d.rho;
       asset = asset1;
@@ -500,7 +507,7 @@ bool fused_supported(const pr_config &c) {
 }
 
 size_t fused_lds_bytes(const pr_config &c, bool with_actor) {
-  const int D = c.n_stocks, DK = c.n_stocks * c.n_ind, S = 1 + 2 * D + DK, Hd = c.hidden, Dp = D | 1;
+  const int D = c.n_stocks, DK = c.n_stocks * c.n_ind, S = 1 + 2 * D + DK, Hd = c.hidden, Dp = kDp;
   const int bf = c.mlp_dtype == PR_MLP_BF16, esz = bf ? 2 : 4, KB = bf ? 16 : 8;
   const int kp = (S + KB - 1) / KB * KB;
   size_t env_scratch = (size_t)7 * E * Dp * 4;
@@ -552,7 +559,7 @@ hipError_t launch_rollout_fused(hipStream_t st, const pr_config &c, const EnvDim
   a.xpitch = tile_pitch(actor.nkb[0] * KB, esz);
   a.hpitch = tile_pitch(c.hidden, esz);
   // the env scratch must fit in the hidden tile
-  const size_t env_scratch = (size_t)7 * E * (d.D | 1) * 4;
+  const size_t env_scratch = (size_t)7 * E * kDp * 4;
   if ((size_t)BM * a.hpitch < env_scratch) a.hpitch = (int32_t)((env_scratch + BM - 1) / BM + 15) / 16 * 16;
   a.d_magic = (uint32_t)((0x100000000ull + (uint64_t)d.D - 1) / (uint64_t)d.D);
   a.dk_magic = (uint32_t)((0x100000000ull + (uint64_t)DK - 1) / (uint64_t)DK);
@@ -560,7 +567,7 @@ hipError_t launch_rollout_fused(hipStream_t st, const pr_config &c, const EnvDim
   // must mirror the carve-up at the top of the kernel
   size_t lds = (size_t)BM * a.hpitch + (size_t)BM * a.xpitch;
   if (with_actor) lds += (size_t)actor.nkb[2] * 1024 + (size_t)(actor.nct[0] + actor.nct[1] + actor.nct[2]) * 32 * 4;
-  lds += (size_t)2 * E * (d.D | 1) * 4 + (size_t)E * (sizeof(Row) + sizeof(float));
+  lds += (size_t)2 * E * kDp * 4 + (size_t)E * (sizeof(Row) + sizeof(float));
   if (lds > 160 * 1024) return hipErrorInvalidValue;
   const unsigned blocks = (unsigned)(d.N / E);
   const int cth = (c.hidden / 32) / NW;
