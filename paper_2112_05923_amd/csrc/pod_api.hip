@@ -186,6 +186,8 @@ int rollout_init(const pr_config *cfg, const pr_market *market, const pr_weights
   if (!market || !market->price || (cfg->n_ind > 0 && !market->ind)) return PR_EINVAL;
   if (!weights_ok(actor) || !weights_ok(critic)) return PR_EINVAL;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return PR_EINVAL;
+  // the persistent kernel moves indicator rows in 16-byte groups
+  if (cfg->schedule == PR_SCHED_FUSED && (reinterpret_cast<uintptr_t>(market->ind) & 15u)) return PR_EINVAL;
   const Layout L = make_layout(*cfg);
   if (workspace_bytes < L.total) return PR_ENOMEM;
 

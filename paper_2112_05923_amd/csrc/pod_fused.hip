@@ -38,7 +38,7 @@ constexpr int E = BM;            // envs per workgroup
 constexpr int PAIRS_MAX = 4;     // (env, stock) pairs per lane: D <= 32
 constexpr int DMAX = 32;         // stock slots per env row in LDS; slots D..31 hold neutral values (k = 0, h = 0)
 constexpr int kDp = DMAX + 1;    // odd row pitch: the per-env serial walks of the ledger hit distinct banks
-constexpr int IND_MAX = 35;      // indicator values per lane (lanes 64..511): D*K <= 245
+constexpr int IND_MAX = 9;       // 16-byte indicator groups per lane (lanes 64..511): D*K <= 252, D*K % 4 == 0
 constexpr int NT_IND = NT - 64;  // lanes that carry indicator values
 
 struct Row {
@@ -65,7 +65,7 @@ struct FusedArgs {
   float *mu_out;           // opt [T, N, D]
   int32_t *shares;         // opt [T, N, D]
   int32_t xpitch, hpitch;
-  uint32_t d_magic, dk_magic;  // ceil(2^32 / D), ceil(2^32 / (D K))
+  uint32_t d_magic, g_magic;  // ceil(2^32 / D), ceil(2^32 / (D K / 4))
 };
 
 __device__ inline Row row_of(const EnvDims &d, int32_t tau, int32_t n) {
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   // (Each helper starts from an opaque copy of the thread index: the (env, column) decompositions and the
   // addresses derived from them are loop invariant, and the compiler would otherwise keep a hundred of them
   // in registers across the matrix-core code instead of recomputing a few integer operations.)
-  auto emit_market = [&](float *obs_row, const float (&p_obs)[PAIRS_MAX], const float (&ind_v)[IND_MAX]) {
+  auto emit_market = [&](float *obs_row, const float (&p_obs)[PAIRS_MAX], const f32x4 (&ind_v)[IND_MAX]) {
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
 #pragma unroll
@@ -202,14 +202,26 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       }
     }
     if (tid >= 64) {
+      const int G = DK >> 2;
 #pragma unroll
       for (int i = 0; i < IND_MAX; ++i) {
         const int idx = (tid - 64) + NT_IND * i;
-        if (idx < E * DK) {
-          const int e = (int)__umulhi((unsigned)idx, a.dk_magic), j = idx - e * DK;
-          const float sv = ind_v[i] * d.s_ind;
-          obs_row[(size_t)(n0 + e) * S + 1 + 2 * D + j] = sv;
-          if (ACTOR) O::store1(ldsX + (size_t)e * a.xpitch + (1 + 2 * D + j) * O::ESZ, sv);
+        if (idx < E * G) {
+          const int e = (int)__umulhi((unsigned)idx, a.g_magic), j = 4 * (idx - e * G);
+          f32x4 sv = ind_v[i];
+          sv[0] *= d.s_ind;
+          sv[1] *= d.s_ind;
+          sv[2] *= d.s_ind;
+          sv[3] *= d.s_ind;
+          // observation rows are 4-byte aligned only; a 16-byte store needs no more than that
+          *reinterpret_cast<f32x4 *>(obs_row + (size_t)(n0 + e) * S + 1 + 2 * D + j) = sv;
+          if (ACTOR) {
+            unsigned char *x = ldsX + (size_t)e * a.xpitch + (1 + 2 * D + j) * O::ESZ;
+            O::store1(x, sv[0]);
+            O::store1(x + O::ESZ, sv[1]);
+            O::store1(x + 2 * O::ESZ, sv[2]);
+            O::store1(x + 3 * O::ESZ, sv[3]);
+          }
         }
       }
     }
@@ -240,7 +252,8 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     }
   };
   // Loads of the market rows named in s_row, into registers (issued early, consumed after the actor).
-  float r_eps[PAIRS_MAX], r_mu[PAIRS_MAX], r_pv[PAIRS_MAX], r_po[PAIRS_MAX], r_ind[IND_MAX];
+  float r_eps[PAIRS_MAX], r_mu[PAIRS_MAX], r_pv[PAIRS_MAX], r_po[PAIRS_MAX];
+  f32x4 r_ind[IND_MAX];
   auto fetch_market = [&]() {
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
@@ -253,11 +266,12 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       r_po[i] = a.price[(size_t)r.row_obs * D + dd];
     }
     if (tid >= 64) {
+      const int G = DK >> 2;
 #pragma unroll
       for (int i = 0; i < IND_MAX; ++i) {
-        const int idx = min((tid - 64) + NT_IND * i, max(E * DK - 1, 0));
-        const int e = (int)__umulhi((unsigned)idx, a.dk_magic), j = idx - e * DK;
-        if (DK > 0) r_ind[i] = a.ind[(size_t)s_row[e].row_obs * DK + j];
+        const int idx = min((tid - 64) + NT_IND * i, E * G - 1);
+        const int e = (int)__umulhi((unsigned)idx, a.g_magic), j = 4 * (idx - e * G);
+        r_ind[i] = *reinterpret_cast<const f32x4 *>(a.ind + (size_t)s_row[e].row_obs * DK + j);
       }
     }
   };
@@ -288,20 +302,26 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     s_row[e] = row_of(d, tau, n0 + e);
   }
 
+  // Weight ring of the actor.  Layer 1's first blocks are requested a phase early (here, and after each step's
+  // ledger) so that they are in flight while the observation is completed.
+  u32x4 ring[ring_depth(CTH)][CTH];
+  const float *lb3 = ldsBias + (ACTOR ? (a.actor.nct[0] + a.actor.nct[1]) * 32 : 0);
+  if (ACTOR) prime<CTH, ring_depth(CTH)>(ring, net.W[0], net.nkb[0], net.nct[0], wave * CTH, lane);
+
   for (int t = 0; t < a.T; ++t) {
     __syncthreads();  // observation t complete in LDS; ledger rows of step t visible
     float *obs_next = a.obs + (size_t)(t + 1) * N * S;
     const size_t g0 = ((size_t)t * N + n0) * D;
 
     if (ACTOR) {
-      mlp_tile<BF16, NW, CTH, false, NKB1, NKB2>(
-          net, ldsX, a.xpitch, ldsH, a.hpitch, ldsBias, ldsW3, tid,
+      mlp_tile<BF16, NW, CTH, false, NKB1, NKB2, true, true>(
+          net, ring, ldsX, a.xpitch, ldsH, a.hpitch, ldsBias, ldsW3, tid,
           [&]() {
             fetch_step_inputs(t);
             fetch_market();
           },
           [&]() {},
-          [&](int b, int f, float y) { s_mu[b * 32 + f] = y; });
+          [&](int b, int f, float z) { s_mu[b * 32 + f] = z; });  // bare accumulators, finished below
     } else {
       fetch_step_inputs(t);
       fetch_market();
@@ -317,7 +337,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       if (idx < E * D) {
         const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
         const int o = e * Dp + dd;
-        const float mu = ACTOR ? s_mu[e * 32 + dd] : r_mu[i];
+        const float mu = ACTOR ? finish_out(s_mu[e * 32 + dd], lb3[dd], 1) : r_mu[i];
         const float eps = r_eps[i];
         const float a_raw = mu + d.sigma * eps;
         a.act_raw[g0 + idx] = a_raw;
@@ -454,6 +474,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     // ---- meanwhile (and the ledger lanes afterwards): market part of observation t+1
     emit_market(obs_next, r_po, r_ind);
     __syncthreads();
+    if (ACTOR && t + 1 < a.T) prime<CTH, ring_depth(CTH)>(ring, net.W[0], net.nkb[0], net.nct[0], wave * CTH, lane);
 
     // ---- executed trades out; episode ends clear the holdings; portfolio part of observation t+1
     int tid_q = threadIdx.x;
@@ -496,10 +517,11 @@ struct FusedShape {
 }  // namespace
 
 // Shapes the persistent kernel covers: bf16 networks whose whole input tile, hidden tile and output-layer
-// weights fit in LDS next to the env arrays; N a multiple of 64; D <= 32; D K <= 245; one output feature tile.
+// weights fit in LDS next to the env arrays; N a multiple of 64; D <= 32; D K <= 252 and a multiple of 4 (the
+// indicator rows are moved in 16-byte groups; the market tensors must be 16-byte aligned); one output feature tile.
 bool fused_supported(const pr_config &c) {
   const int D = c.n_stocks, DK = c.n_stocks * c.n_ind, S = 1 + 2 * D + DK, Hd = c.hidden;
-  if (c.n_envs % 64 != 0 || D > 32 || DK > 245 || DK < 1 || S < 4) return false;
+  if (c.n_envs % 64 != 0 || D > 32 || DK > 252 || DK < 4 || DK % 4 != 0 || S < 4) return false;
   if (c.mlp_dtype != PR_MLP_BF16) return false;
   if (Hd % 32 != 0 || Hd < 256 || Hd > 512 || (Hd / 32) % NW != 0) return false;
   if (c.n_agents > 1 && (c.n_envs / c.n_agents) % 64 != 0) return false;
@@ -562,7 +584,8 @@ hipError_t launch_rollout_fused(hipStream_t st, const pr_config &c, const EnvDim
   const size_t env_scratch = (size_t)7 * E * kDp * 4;
   if ((size_t)BM * a.hpitch < env_scratch) a.hpitch = (int32_t)((env_scratch + BM - 1) / BM + 15) / 16 * 16;
   a.d_magic = (uint32_t)((0x100000000ull + (uint64_t)d.D - 1) / (uint64_t)d.D);
-  a.dk_magic = (uint32_t)((0x100000000ull + (uint64_t)DK - 1) / (uint64_t)DK);
+  a.g_magic = (uint32_t)((0x100000000ull + (uint64_t)(DK / 4) - 1) / (uint64_t)(DK / 4));
+  if (reinterpret_cast<uintptr_t>(ind) & 15u) return hipErrorInvalidValue;  // 16-byte indicator loads
   const bool with_actor = mu_forced == nullptr;
   // must mirror the carve-up at the top of the kernel
   size_t lds = (size_t)BM * a.hpitch + (size_t)BM * a.xpitch;

@@ -425,8 +425,9 @@ __global__ __launch_bounds__(NW * 64) void mlp_tiles_kernel(TileArgs a) {
     __syncthreads();  // input tile, biases and W3 complete; previous tile's output layer is done with ldsH
     const int O_dim = net.out_dim;
     float *Y = a.Y + row0 * O_dim;
-    mlp_tile<BF16, NW, CTH, false, NKB1, NKB2>(
-        net, ldsX, a.xpitch, ldsH, a.hpitch, ldsBias, ldsW3, tid,
+    u32x4 ring[ring_depth(CTH)][CTH];
+    mlp_tile<BF16, NW, CTH, false, NKB1, NKB2, false, false>(
+        net, ring, ldsX, a.xpitch, ldsH, a.hpitch, ldsBias, ldsW3, tid,
         [&]() {
           if (more) fetch(tn);
         },

@@ -254,8 +254,16 @@ __device__ inline void epilogue_hidden(const f32x16 (&acc)[CT][NBT], const float
   }
 }
 
+// Bias and activation of the last layer.
+__device__ inline float finish_out(float acc, float bias, int out_tanh) {
+  const float z = acc + bias;
+  return out_tanh ? tanh_accurate(z) : z;
+}
+
 // Last layer: y = acc + bias (tanh for the actor) handed to sink(batch_row_in_tile, feature, value).
-template <int CT, int NBT, class Sink>
+// RAW: hand over the bare accumulator instead; the caller applies finish_out itself (spread over more lanes
+// than the two wavefronts that hold the accumulators).
+template <int CT, int NBT, bool RAW, class Sink>
 __device__ inline void epilogue_out(const f32x16 (&acc)[CT][NBT], const float *bias, int out_dim, int out_tanh,
                                     int nct, int ct0, int bt0, int lane, Sink sink) {
   const int brow = lane & 31, g = lane >> 5;
@@ -270,8 +278,7 @@ __device__ inline void epilogue_out(const f32x16 (&acc)[CT][NBT], const float *b
         for (int t = 0; t < NBT; ++t)
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float z = acc[c][t][4 * j + i] + bv[i];
-            const float y = out_tanh ? tanh_accurate(z) : z;
+            const float y = RAW ? acc[c][t][4 * j + i] : finish_out(acc[c][t][4 * j + i], bv[i], out_tanh);
             if (f0 + i < out_dim) sink((bt0 + t) * 32 + brow, f0 + i, y);
           }
       }
@@ -336,22 +343,26 @@ __device__ inline void mma_out_lds(f32x16 &acc, const u32x4 *ldsW3, const unsign
 // are not needed soon.  late() runs once layer 2's epilogue is complete workgroup-wide; ldsX has been free
 // since layer 1 and may be refilled there.
 // Ends without a trailing barrier: the caller must synchronise before ldsH or ldsX are read or written again.
-template <bool BF16, int NW, int CTH, bool WIDE_OUT, int NKB1, int NKB2, class Early, class Late, class Sink>
-__device__ inline void mlp_tile(const Net &net, const unsigned char *ldsX, int xpitch, unsigned char *ldsH,
-                                int hpitch, const float *ldsBias, const u32x4 *ldsW3, int tid, Early early, Late late,
-                                Sink sink) {
-  constexpr int PD = CTH >= 8 ? 2 : 4;
+constexpr int ring_depth(int cth) { return cth >= 8 ? 2 : 4; }
+
+// PRIMED: the caller has already called prime() for layer 1 on `ring` (to get the first weight blocks in flight
+// before the input tile is complete).  RAW_OUT: see epilogue_out.
+template <bool BF16, int NW, int CTH, bool WIDE_OUT, int NKB1, int NKB2, bool PRIMED, bool RAW_OUT, class Early,
+          class Late, class Sink>
+__device__ inline void mlp_tile(const Net &net, u32x4 (&ring)[ring_depth(CTH)][CTH], const unsigned char *ldsX,
+                                int xpitch, unsigned char *ldsH, int hpitch, const float *ldsBias,
+                                const u32x4 *ldsW3, int tid, Early early, Late late, Sink sink) {
+  constexpr int PD = ring_depth(CTH);
   // the wavefront index is uniform: tell the compiler, so that block addresses live in scalar registers
   const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ct0 = w * CTH;
   const bool act = ct0 < net.nct[0];
   const float *lb1 = ldsBias, *lb2 = ldsBias + net.nct[0] * 32, *lb3 = lb2 + net.nct[1] * 32;
-  u32x4 ring[PD][CTH];
   {
     f32x16 acc[CTH][2];
     zero_acc<CTH, 2>(acc);
     if (act) {
-      prime<CTH, PD>(ring, net.W[0], net.nkb[0], net.nct[0], ct0, lane);
+      if (!PRIMED) prime<CTH, PD>(ring, net.W[0], net.nkb[0], net.nct[0], ct0, lane);
       if (NKB1 > 0)
         mma_layer_static<BF16, CTH, 2, PD, NKB1>(acc, ring, ldsX, xpitch, net.W[0], net.nct[0], ct0, 0, lane);
       else
@@ -379,7 +390,7 @@ __device__ inline void mlp_tile(const Net &net, const unsigned char *ldsX, int x
       f32x16 acc[1][1];
       zero_acc<1, 1>(acc);
       mma_out_lds<BF16, NKB2>(acc[0][0], ldsW3, ldsH, hpitch, net.nkb[2], w, lane);  // nkb[2] == nkb[1]
-      epilogue_out<1, 1>(acc, lb3, net.out_dim, net.out_tanh, 1, 0, w, lane, sink);
+      epilogue_out<1, 1, RAW_OUT>(acc, lb3, net.out_dim, net.out_tanh, 1, 0, w, lane, sink);
     }
     late();
   } else {
@@ -392,7 +403,7 @@ __device__ inline void mlp_tile(const Net &net, const unsigned char *ldsX, int x
       zero_acc<CTO, 2>(acc);
       prime<CTO, 2>(r4, net.W[2], net.nkb[2], net.nct[2], co0, lane);
       mma_layer<BF16, CTO, 2, 2>(acc, r4, ldsH, hpitch, net.nkb[2], net.W[2], net.nct[2], co0, 0, lane);
-      epilogue_out<CTO, 2>(acc, lb3, net.out_dim, net.out_tanh, net.nct[2], co0, 0, lane, sink);
+      epilogue_out<CTO, 2, RAW_OUT>(acc, lb3, net.out_dim, net.out_tanh, net.nct[2], co0, 0, lane, sink);
     }
   }
 }
