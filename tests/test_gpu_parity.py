@@ -339,8 +339,8 @@ def test_fused_schedule_equals_stepwise_bit_for_bit(hidden, N, agents, H, n_mark
 
 
 def test_fused_forced_env_stage_matches_checker_with_resets_and_cash_starved():
-    T, H = 40, 16
-    w = inputs.WORKLOADS["large"].replace(n_envs=128, steps=T, cash0=20000.0)
+    T, H = 96, 40
+    w = inputs.WORKLOADS["large"].replace(n_envs=256, steps=T, cash0=20000.0)
     rng = np.random.default_rng(21)
     mu = rng.uniform(-1, 1, (T, w.n_envs, w.n_stocks)).astype(np.float32)
     d, ro, ocfg, (out,), st = _run(w, H, T, FUSED, forced_mu=mu)
