@@ -82,6 +82,26 @@ def test_mlp_forward_matches_checker(name, rows, agents):
             parity.check_networks(w, d["actor"], d["critic"], X[sel], mu[sel], val[sel], agent=g)
 
 
+@pytest.mark.parametrize("name", ["large", "dow30"])
+def test_value_head_over_many_tiles_matches_checker(name):
+    """Several tiles per compute unit in one persistent launch, plus a ragged tail."""
+    w = inputs.WORKLOADS[name].replace(n_envs=64, steps=2)
+    d, ro, _ = _make(w)
+    rows = 64 * 2 * 256 + 64 * 3 + 40
+    g = torch.Generator(device=DEV)
+    g.manual_seed(7)
+    X = torch.randn((rows, w.state_dim), generator=g, device=DEV)
+    val = ro.mlp_forward(pr.PR_NET_CRITIC, X)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    pick = np.unique(np.concatenate([rng.integers(0, rows, 300), np.arange(64), np.arange(rows - 104, rows)]))
+    parity.check_networks(w, d["actor"], d["critic"], parity.to_np(X[pick]), None, parity.to_np(val[pick]))
+    # the same rows in a smaller call (different tile-to-workgroup assignment) give the same values
+    val2 = ro.mlp_forward(pr.PR_NET_CRITIC, X[:4096].contiguous())
+    torch.cuda.synchronize()
+    assert torch.equal(val[:4096], val2)
+
+
 def test_mlp_forward_strided_input_and_padding_columns():
     w = inputs.WORKLOADS["tiny"].replace(n_envs=64, steps=2)
     d, ro, _ = _make(w)
