@@ -96,6 +96,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-envs", type=int, default=192)
     ap.add_argument("--cpu-steps", type=int, default=1024)
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="also launch one plain elementwise copy of this many MiB (read + write that much each), "
+                         "the known-size kernel hardware traffic counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (envs shard trivially across GPUs; no multi-GPU "
@@ -144,6 +147,13 @@ def main():
         one_step(events[k])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+
+    if args.copy_calibration:
+        src = torch.ones(args.copy_calibration << 18, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 1.0, out=dst)  # one vectorised elementwise kernel: reads and writes copy_calibration MiB
+        torch.cuda.synchronize()
 
     ms = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in events) / args.steps
     t_roll, t_critic, t_gae = ms(0, 1), ms(1, 2), ms(2, 3)

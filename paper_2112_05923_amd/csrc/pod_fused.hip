@@ -197,7 +197,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         const float v = p_obs[i];
         s_p[e * Dp + dd] = v;
         const float sv = v * d.s_price;
-        obs_row[(size_t)(n0 + e) * S + 1 + dd] = sv;
+        __builtin_nontemporal_store(sv, &obs_row[(size_t)(n0 + e) * S + 1 + dd]);
         if (ACTOR) O::store1(ldsX + (size_t)e * a.xpitch + (1 + dd) * O::ESZ, sv);
       }
     }
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
           sv[2] *= d.s_ind;
           sv[3] *= d.s_ind;
           // observation rows are 4-byte aligned only; a 16-byte store needs no more than that
-          *reinterpret_cast<f32x4 *>(obs_row + (size_t)(n0 + e) * S + 1 + 2 * D + j) = sv;
+          __builtin_nontemporal_store(sv, reinterpret_cast<f32x4 *>(obs_row + (size_t)(n0 + e) * S + 1 + 2 * D + j));
           if (ACTOR) {
             unsigned char *x = ldsX + (size_t)e * a.xpitch + (1 + 2 * D + j) * O::ESZ;
             O::store1(x, sv[0]);
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     asm volatile("" : "+v"(tid));
     if (tid < E) {
       const float sv = s_cash[tid] * d.s_cash;
-      obs_row[(size_t)(n0 + tid) * S] = sv;
+      __builtin_nontemporal_store(sv, &obs_row[(size_t)(n0 + tid) * S]);
       if (ACTOR) {
         O::store1(ldsX + (size_t)tid * a.xpitch, sv);
         // the policy means were parked over the head of this tile: restore the zero k padding of every row
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       if (idx < E * D) {
         const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
         const float sv = (float)s_h[e * Dp + dd] * d.s_hold;
-        obs_row[(size_t)(n0 + e) * S + 1 + D + dd] = sv;
+        __builtin_nontemporal_store(sv, &obs_row[(size_t)(n0 + e) * S + 1 + D + dd]);
         if (ACTOR) O::store1(ldsX + (size_t)e * a.xpitch + (1 + D + dd) * O::ESZ, sv);
       }
     }
@@ -262,8 +262,8 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       const int idx = min(tid + NT * i, E * D - 1);
       const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
       const Row r = s_row[e];
-      r_pv[i] = a.price[(size_t)r.row_val * D + dd];
-      r_po[i] = a.price[(size_t)r.row_obs * D + dd];
+      r_pv[i] = __builtin_nontemporal_load(&a.price[(size_t)r.row_val * D + dd]);
+      r_po[i] = __builtin_nontemporal_load(&a.price[(size_t)r.row_obs * D + dd]);
     }
     if (tid >= 64) {
       const int G = DK >> 2;
@@ -271,7 +271,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       for (int i = 0; i < IND_MAX; ++i) {
         const int idx = min((tid - 64) + NT_IND * i, E * G - 1);
         const int e = (int)__umulhi((unsigned)idx, a.g_magic), j = 4 * (idx - e * G);
-        r_ind[i] = *reinterpret_cast<const f32x4 *>(a.ind + (size_t)s_row[e].row_obs * DK + j);
+        r_ind[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.ind + (size_t)s_row[e].row_obs * DK + j));
       }
     }
   };
@@ -282,7 +282,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
 #pragma unroll
     for (int i = 0; i < PAIRS_MAX; ++i) {
       const int idx = min(tid + NT * i, E * D - 1);
-      r_eps[i] = a.noise[g0 + idx];
+      r_eps[i] = __builtin_nontemporal_load(&a.noise[g0 + idx]);
       if (!ACTOR) r_mu[i] = a.mu_forced[g0 + idx];
     }
   };
@@ -340,7 +340,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         const float mu = ACTOR ? finish_out(s_mu[e * 32 + dd], lb3[dd], 1) : r_mu[i];
         const float eps = r_eps[i];
         const float a_raw = mu + d.sigma * eps;
-        a.act_raw[g0 + idx] = a_raw;
+        __builtin_nontemporal_store(a_raw, &a.act_raw[g0 + idx]);
         if (ACTOR && a.mu_out) a.mu_out[g0 + idx] = mu;
         const float ac = fminf(1.0f, fmaxf(-1.0f, a_raw));
         const int32_t k = (int32_t)truncf(ac * d.hmax);

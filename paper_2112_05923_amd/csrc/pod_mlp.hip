@@ -373,7 +373,7 @@ __global__ __launch_bounds__(NW * 64) void mlp_tiles_kernel(TileArgs a) {
         const int row = (int)__umulhi((unsigned)idx, (unsigned)a.g_magic);
         const int c4 = 4 * (idx - row * G);
         const int shift = max(0, c4 + 4 - S);
-        pre[i] = *reinterpret_cast<const f32x4 *>(src + (size_t)row * S + c4 - shift);  // 4-byte aligned
+        pre[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(src + (size_t)row * S + c4 - shift));  // 4-byte aligned
       }
     }
   };
@@ -434,7 +434,7 @@ __global__ __launch_bounds__(NW * 64) void mlp_tiles_kernel(TileArgs a) {
         [&]() {
           if (more) stash();
         },
-        [&](int b, int f, float y) { Y[(size_t)b * O_dim + f] = y; });
+        [&](int b, int f, float y) { __builtin_nontemporal_store(y, &Y[(size_t)b * O_dim + f]); });
   }
 }
 
