@@ -18,6 +18,8 @@
 // feeds row/column (l % 32) and the k-half (l / 32) of a k-block: 16 bytes per
 // lane and operand.
 #include "pod_internal.h"
+#include <type_traits>
+
 #include "pod_tile.h"
 
 namespace pod {
@@ -335,6 +337,7 @@ constexpr int XPRE_MAX = 10;  // 16-byte loads per thread and tile
 struct TileArgs {
   const float *X;
   int64_t rows;       // multiple of 64
+  int64_t row_base;   // index of X's first row in the caller's buffer (selects the agent)
   float *Y;
   PackedNet net;
   int32_t N, envs_per_agent;
@@ -415,7 +418,7 @@ __global__ __launch_bounds__(NW * 64) void mlp_tiles_kernel(TileArgs a) {
     const int64_t row0 = t * BM;
     const int64_t tn = t + gridDim.x;
     const bool more = tn < ntiles;
-    const int agent = (int)((row0 % a.N) / a.envs_per_agent);
+    const int agent = (int)(((a.row_base + row0) % a.N) / a.envs_per_agent);
     const Net net = net_of(a.net, agent);
     if (agent != staged_agent) {
       __syncthreads();  // the previous tile's output layer may still read its weights and biases
@@ -435,6 +438,210 @@ __global__ __launch_bounds__(NW * 64) void mlp_tiles_kernel(TileArgs a) {
           if (more) stash();
         },
         [&](int b, int f, float y) { __builtin_nontemporal_store(y, &Y[(size_t)b * O_dim + f]); });
+  }
+}
+
+
+// ------------------------------------------------ 128-row value-head kernel
+// The critic (one output feature, Sec. 4.1) over a long buffer of observations.
+// A 128-row tile halves the weight traffic per row of the 64-row kernel above:
+// every weight block a wavefront streams from L2 feeds four 32-row batch tiles,
+// which makes the two hidden layers matrix-core bound instead of L2 bound.
+//  - LDS holds one 128-row hidden tile; the input tile aliases its head (layer 1
+//    has consumed it before its epilogue writes the hidden tile).
+//  - The output layer is folded into layer 2's epilogue: each lane multiplies
+//    its bf16-rounded activations by the output weights of its features and the
+//    16 partial sums per row (8 wavefronts x 2 lane halves) meet in LDS.  The
+//    hidden tile is therefore dead after layer 2's matrix work, and the next
+//    tile's rows (fetched into registers behind that matrix work) are dropped
+//    into LDS while the epilogue arithmetic runs.
+constexpr int VBM = 128;
+constexpr int VPRE_MAX = 19;  // 16-byte loads per thread and tile: k-blocks of layer 1
+
+struct ValueArgs {
+  const float *X;
+  int64_t rows;      // multiple of 128
+  float *Y;          // [rows]
+  PackedNet net;
+  int32_t N, envs_per_agent;
+  int32_t S;
+  int32_t groups;    // 16-byte groups per LDS row: padded k columns / 4
+  uint32_t g_magic;  // ceil(2^32 / groups)
+  int32_t xpitch, hpitch;
+};
+
+template <int NKB1, int NKB2>
+__global__ __launch_bounds__(512) void value128_kernel(ValueArgs a) {
+  using namespace tile;
+  using O = tile::Op<true>;
+  constexpr int NT = 512, CTH = 2, NBT = 4, PD = 4;
+  extern __shared__ __align__(16) unsigned char lds[];
+  unsigned char *ldsH = lds;
+  unsigned char *ldsX = lds;  // alias: see above
+  float *ldsBias = reinterpret_cast<float *>(lds + (size_t)VBM * a.hpitch);  // b1 | b2
+  const int nct = a.net.nct[0];
+  float *ldsW3 = ldsBias + 2 * nct * 32;  // output weights, one float per hidden feature
+  float *ldsPart = ldsW3 + nct * 32;      // [16][128] partial sums of the output layer
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ct0 = w * CTH;
+  const int S = a.S, G = a.groups;
+  const int last_c4 = 4 * ((S + 3) / 4 - 1);  // first column of the last group that holds data
+  const int64_t ntiles = a.rows / VBM;
+
+  constexpr int NX = NKB1 > 0 ? NKB1 : VPRE_MAX;  // 16-byte groups per thread and tile
+  const int sh = 4 * ((S + 3) / 4) - S;            // floats the row-end group is shifted by (0..3), uniform
+  f32x4 pre[NX];
+  // Every thread issues its 16-byte loads unconditionally.  The group that straddles the end of a row is read
+  // as the four floats that END at the row end; groups that lie wholly in the k padding re-read it.
+  // (issued in two parts, [0, NX_A) behind layer 2's matrix work and the rest once half of that layer's
+  // accumulators have been consumed, so that registers for the rows in flight are there without spilling)
+  constexpr int NX_A = NX / 2;
+  auto fetch = [&](int64_t t, auto part) {
+    constexpr int I0 = decltype(part)::value ? NX_A : 0, I1 = decltype(part)::value ? NX : NX_A;
+    const float *src = a.X + t * VBM * S;
+    int tid_f = threadIdx.x;
+    asm volatile("" : "+v"(tid_f));
+#pragma unroll
+    for (int i = I0; i < I1; ++i) {
+      const int idx = min(tid_f + NT * i, VBM * G - 1);
+      const int row = (int)__umulhi((unsigned)idx, a.g_magic);
+      const int c4 = min(4 * (idx - row * G), last_c4);
+      const int off = c4 == last_c4 ? c4 - sh : c4;
+      pre[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(src + (size_t)row * S + off));
+    }
+  };
+  auto stash = [&]() {
+    int tid_s = threadIdx.x;
+    asm volatile("" : "+v"(tid_s));  // keeps the LDS addresses out of registers across the matrix-core loops
+#pragma unroll
+    for (int i = 0; i < NX; ++i) {
+      const int idx = tid_s + NT * i;
+      const int idc = min(idx, VBM * G - 1);
+      const int row = (int)__umulhi((unsigned)idc, a.g_magic);
+      const int c4 = 4 * (idc - row * G);
+      const f32x4 v = pre[i];
+      // the row-end group, shifted down by sh with zeros behind (selects on the uniform sh, no branches)
+      f32x4 e;
+      e[0] = sh == 0 ? v[0] : sh == 1 ? v[1] : sh == 2 ? v[2] : v[3];
+      e[1] = sh == 0 ? v[1] : sh == 1 ? v[2] : sh == 2 ? v[3] : 0.0f;
+      e[2] = sh == 0 ? v[2] : sh == 1 ? v[3] : 0.0f;
+      e[3] = sh == 0 ? v[3] : 0.0f;
+      const bool end = c4 == last_c4, pad = c4 > last_c4;
+      f32x4 o;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) o[q] = pad ? 0.0f : end ? e[q] : v[q];
+      if (NKB1 > 0 || idx < VBM * G) O::store4(ldsX + (size_t)row * a.xpitch + c4 * O::ESZ, o[0], o[1], o[2], o[3]);
+    }
+  };
+
+  int64_t t = blockIdx.x;
+  if (t >= ntiles) return;
+  fetch(t, std::false_type{});
+  fetch(t, std::true_type{});
+  int staged_agent = -1;
+  float b3 = 0.0f;
+  stash();
+  u32x4 ring[PD][CTH];
+  for (; t < ntiles; t += gridDim.x) {
+    const int64_t row0 = t * VBM;
+    const int64_t tn = t + gridDim.x;
+    const bool more = tn < ntiles;
+    const int agent = (int)((row0 % a.N) / a.envs_per_agent);
+    const Net net = net_of(a.net, agent);
+    if (agent != staged_agent) {
+      // nothing reads the staged vectors between the barrier that ended the previous tile and the one after
+      // layer 1, so they can be replaced here
+      for (int i = tid; i < nct * 32; i += NT) {
+        ldsBias[i] = net.b[0][i];
+        ldsBias[nct * 32 + i] = net.b[1][i];
+        // output weights of feature 0 out of the packed blocks: k = 16 kb + 8 g + e sits in lane 32 g
+        const int kb = i >> 4, gg = (i >> 3) & 1, e = i & 7;
+        ldsW3[i] = (float)reinterpret_cast<const __bf16 *>(net.W[2])[((size_t)kb * 64 + 32 * gg) * 8 + e];
+      }
+      b3 = net.b[2][0];
+      staged_agent = agent;
+      prime<CTH, PD>(ring, net.W[0], net.nkb[0], nct, ct0, lane);
+    }
+    __syncthreads();  // input tile complete
+    // Each phase works from its own opaque copy of the lane index: every LDS and weight address below is
+    // invariant across tiles, and hoisted out of the tile loop they would occupy (and spill) dozens of registers.
+    f32x16 acc[CTH][NBT];
+    zero_acc<CTH, NBT>(acc);
+    int lane_1 = lane;
+    asm volatile("" : "+v"(lane_1));
+    if (NKB1 > 0)
+      mma_layer_static<true, CTH, NBT, PD, NKB1>(acc, ring, ldsX, a.xpitch, net.W[0], nct, ct0, 0, lane_1);
+    else
+      mma_layer<true, CTH, NBT, PD>(acc, ring, ldsX, a.xpitch, net.nkb[0], net.W[0], nct, ct0, 0, lane_1);
+    prime<CTH, PD>(ring, net.W[1], net.nkb[1], nct, ct0, lane_1);
+    __syncthreads();  // every wavefront has consumed the input tile; the hidden tile goes over it
+    int lane_2 = lane;
+    asm volatile("" : "+v"(lane_2));
+    epilogue_hidden<true, CTH, NBT>(acc, ldsBias, ldsH, a.hpitch, nct, ct0, 0, lane_2);
+    __syncthreads();
+    zero_acc<CTH, NBT>(acc);
+    int lane_3 = lane;
+    asm volatile("" : "+v"(lane_3));
+    if (NKB2 > 0)
+      mma_layer_static<true, CTH, NBT, PD, NKB2>(acc, ring, ldsH, a.hpitch, net.W[1], nct, ct0, 0, lane_3);
+    else
+      mma_layer<true, CTH, NBT, PD>(acc, ring, ldsH, a.hpitch, net.nkb[1], net.W[1], nct, ct0, 0, lane_3);
+    // (unconditional -- the last tile re-reads itself -- so that no register of the previous fetch stays live)
+    const int64_t tf = more ? tn : t;
+    fetch(tf, std::false_type{});
+    __syncthreads();  // every wavefront has consumed the hidden tile
+    {
+      // layer 2's epilogue with the output layer folded in
+      int lane_e = lane;
+      asm volatile("" : "+v"(lane_e));
+      const int ge = lane_e >> 5;
+      const float *lb2 = ldsBias + nct * 32;
+      float part[NBT];
+#pragma unroll
+      for (int q = 0; q < NBT; ++q) part[q] = 0.0f;
+#pragma unroll
+      for (int c = 0; c < CTH; ++c) {
+        if (c == CTH - 1) {
+          // pin the first half's arithmetic above the loads (it has no side effect of its own and would
+          // otherwise be sunk below them, keeping all accumulators alive)
+#pragma unroll
+          for (int q = 0; q < NBT; ++q) asm volatile("" : "+v"(part[q]));
+          fetch(tf, std::true_type{});
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int f0 = (ct0 + c) * 32 + 8 * j + 4 * ge;
+          const f32x4 bv = *reinterpret_cast<const f32x4 *>(lb2 + f0);
+          const f32x4 wv = *reinterpret_cast<const f32x4 *>(ldsW3 + f0);
+#pragma unroll
+          for (int q = 0; q < NBT; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float h = tanh_from_scaled(fmaf(acc[c][q][4 * j + i], kTwoLog2e, bv[i] * kTwoLog2e));
+              part[q] = fmaf((float)(__bf16)h, wv[i], part[q]);
+            }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < NBT; ++q) ldsPart[(2 * w + ge) * VBM + q * 32 + (lane_e & 31)] = part[q];
+    }
+    if (more) {
+      stash();
+      const int agent_n = (int)(((tn * VBM) % a.N) / a.envs_per_agent);
+      int lane_4 = lane;
+      asm volatile("" : "+v"(lane_4));
+      if (agent_n == agent) prime<CTH, PD>(ring, net.W[0], net.nkb[0], nct, ct0, lane_4);
+    }
+    __syncthreads();  // partial sums (and the next input tile) complete
+    int tid_y = threadIdx.x;
+    asm volatile("" : "+v"(tid_y));
+    if (tid_y < VBM) {
+      float y = b3;
+#pragma unroll
+      for (int p = 0; p < 16; ++p) y += ldsPart[p * VBM + tid_y];
+      __builtin_nontemporal_store(y, &a.Y[row0 + tid_y]);
+    }
   }
 }
 
@@ -581,8 +788,8 @@ int compute_units() {
 
 // The whole-tile kernel covers dense rows, one output feature tile, hidden widths up to 512 and S up to 320.
 // `rows` must be a multiple of 64.
-static bool try_launch_tiles(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx, float *Y,
-                             int32_t N, int32_t envs_per_agent, hipError_t *err) {
+static bool try_launch_tiles(hipStream_t st, const PackedNet &net, int64_t rows, int64_t row_base, const float *X,
+                             int64_t ldx, float *Y, int32_t N, int32_t envs_per_agent, hipError_t *err) {
   const int S = net.in_dim[0], Hd = net.out_dim[0];
   if (ldx != S || S < 4 || (reinterpret_cast<uintptr_t>(X) & 3u) || net.nct[2] != 1 || Hd > 512) return false;
   const int G = (S + 3) / 4;
@@ -595,6 +802,7 @@ static bool try_launch_tiles(hipStream_t st, const PackedNet &net, int64_t rows,
   TileArgs a;
   a.X = X;
   a.rows = rows;
+  a.row_base = row_base;
   a.Y = Y;
   a.net = net;
   a.N = N;
@@ -621,21 +829,78 @@ static bool try_launch_tiles(hipStream_t st, const PackedNet &net, int64_t rows,
   return true;
 }
 
+
+template <int NKB1, int NKB2>
+static hipError_t launch_value128(hipStream_t st, const ValueArgs &a, unsigned blocks, size_t lds) {
+  auto kern = value128_kernel<NKB1, NKB2>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(512), lds, st, a);
+  return hipGetLastError();
+}
+
+// The 128-row value kernel covers a bf16 critic with 512 hidden units on dense rows of at most 304 columns,
+// when there are enough rows to give every compute unit several tiles and agents own multiples of 128 envs.
+// `rows` must be a multiple of 128 and X must start at a multiple of N rows of the caller's buffer.
+static bool try_launch_value128(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx,
+                                float *Y, int32_t N, int32_t envs_per_agent, hipError_t *err) {
+  const int S = net.in_dim[0], Hd = net.out_dim[0];
+  if (!net.bf16 || net.out_dim[2] != 1 || Hd != 512 || net.out_dim[1] != 512 || ldx != S || S < 4) return false;
+  if ((reinterpret_cast<uintptr_t>(X) & 3u) || N % VBM != 0 || envs_per_agent % VBM != 0) return false;
+  if (net.nkb[0] > VPRE_MAX || rows < (int64_t)VBM * 4 * compute_units()) return false;
+  ValueArgs a;
+  a.X = X;
+  a.rows = rows;
+  a.Y = Y;
+  a.net = net;
+  a.N = N;
+  a.envs_per_agent = envs_per_agent;
+  a.S = S;
+  a.groups = net.nkb[0] * 4;
+  a.g_magic = (uint32_t)((0x100000000ull + (uint64_t)a.groups - 1) / (uint64_t)a.groups);
+  a.xpitch = tile::tile_pitch(net.nkb[0] * 16, 2);
+  a.hpitch = tile::tile_pitch(Hd, 2);
+  const size_t lds = (size_t)VBM * a.hpitch + (size_t)3 * net.nct[0] * 32 * 4 + (size_t)16 * VBM * 4;
+  if (lds > 160 * 1024) return false;
+  const int64_t ntiles = rows / VBM;
+  const unsigned blocks = (unsigned)(ntiles < compute_units() ? ntiles : compute_units());
+  if (net.nkb[0] == 19 && net.nkb[1] == 32) *err = launch_value128<19, 32>(st, a, blocks, lds);
+  else *err = launch_value128<0, 32>(st, a, blocks, lds);
+  return true;
+}
+
 hipError_t launch_mlp(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx, float *Y,
                       int32_t N, int32_t envs_per_agent) {
   Shape s;
   if (!pick_shape(net.out_dim[0], net.out_dim[2], net.bf16, &s)) return hipErrorInvalidValue;
   constexpr int BM = 64;
   int64_t row_offset = 0;
-  if (rows >= BM) {
-    // full tiles through the persistent whole-tile kernel when it covers the shape; the ragged tail below
+  if (rows >= VBM) {
+    // a long value-head buffer: 128-row tiles first
     hipError_t terr = hipSuccess;
-    const int64_t full = rows / BM * BM;
-    if (try_launch_tiles(st, net, full, X, ldx, Y, N, envs_per_agent, &terr)) {
+    const int64_t full = rows / VBM * VBM;
+    if (try_launch_value128(st, net, full, X, ldx, Y, N, envs_per_agent, &terr)) {
       if (terr != hipSuccess || full == rows) return terr;
       X += full * ldx;
       Y += full * net.out_dim[2];
       row_offset = full;
+      rows -= full;
+    }
+  }
+  if (rows >= BM) {
+    // full tiles through the persistent whole-tile kernel when it covers the shape; the ragged tail below
+    hipError_t terr = hipSuccess;
+    const int64_t full = rows / BM * BM;
+    if (try_launch_tiles(st, net, full, row_offset, X, ldx, Y, N, envs_per_agent, &terr)) {
+      if (terr != hipSuccess || full == rows) return terr;
+      X += full * ldx;
+      Y += full * net.out_dim[2];
+      row_offset += full;
       rows -= full;
     }
   }

@@ -82,24 +82,31 @@ def test_mlp_forward_matches_checker(name, rows, agents):
             parity.check_networks(w, d["actor"], d["critic"], X[sel], mu[sel], val[sel], agent=g)
 
 
-@pytest.mark.parametrize("name", ["large", "dow30"])
-def test_value_head_over_many_tiles_matches_checker(name):
-    """Several tiles per compute unit in one persistent launch, plus a ragged tail."""
-    w = inputs.WORKLOADS[name].replace(n_envs=64, steps=2)
+@pytest.mark.parametrize("name,agents", [("large", 1), ("large", 3), ("dow30", 1)])
+def test_value_head_over_many_tiles_matches_checker(name, agents):
+    """A long critic buffer: many tiles per compute unit in one persistent launch (the 128-row value-head
+    kernel for the bf16 networks), a ragged tail behind it, and agents that change along the buffer."""
+    w = inputs.WORKLOADS[name].replace(n_envs=128 * agents, n_agents=agents, steps=2)
     d, ro, _ = _make(w)
-    rows = 64 * 2 * 256 + 64 * 3 + 40
+    rows = 128 * 4 * 256 + 128 * agents + 64 + 40
     g = torch.Generator(device=DEV)
     g.manual_seed(7)
     X = torch.randn((rows, w.state_dim), generator=g, device=DEV)
     val = ro.mlp_forward(pr.PR_NET_CRITIC, X)
     torch.cuda.synchronize()
     rng = np.random.default_rng(5)
-    pick = np.unique(np.concatenate([rng.integers(0, rows, 300), np.arange(64), np.arange(rows - 104, rows)]))
-    parity.check_networks(w, d["actor"], d["critic"], parity.to_np(X[pick]), None, parity.to_np(val[pick]))
-    # the same rows in a smaller call (different tile-to-workgroup assignment) give the same values
+    pick = np.unique(np.concatenate([rng.integers(0, rows, 400), np.arange(130), np.arange(rows - 240, rows)]))
+    Xp, vp = parity.to_np(X[pick]), parity.to_np(val[pick])
+    for a in range(agents):
+        sel = ((pick % w.n_envs) // 128) == a
+        assert sel.any()
+        parity.check_networks(w, d["actor"], d["critic"], Xp[sel], None, vp[sel], agent=a)
+    # the same rows in a short call (64-row tiles) agree up to the order of the fp32 sums
     val2 = ro.mlp_forward(pr.PR_NET_CRITIC, X[:4096].contiguous())
     torch.cuda.synchronize()
-    assert torch.equal(val[:4096], val2)
+    scale = float(val2.abs().max())
+    tol = (parity.TOL_BF16 if w.mlp_dtype else parity.TOL_F32) * scale
+    assert float((val[:4096] - val2).abs().max()) <= tol
 
 
 def test_mlp_forward_strided_input_and_padding_columns():
