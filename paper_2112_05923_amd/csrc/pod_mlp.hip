@@ -460,7 +460,7 @@ constexpr int VPRE_MAX = 19;  // 16-byte loads per thread and tile: k-blocks of 
 
 struct ValueArgs {
   const float *X;
-  int64_t rows;      // multiple of 128
+  int64_t rows;      // multiple of the tile height
   float *Y;          // [rows]
   PackedNet net;
   int32_t N, envs_per_agent;
@@ -470,26 +470,29 @@ struct ValueArgs {
   int32_t xpitch, hpitch;
 };
 
-template <int NKB1, int NKB2>
-__global__ __launch_bounds__(512) void value128_kernel(ValueArgs a) {
+template <int NKB1, int NKB2, int SS>
+__global__ __launch_bounds__(512) void value_kernel(ValueArgs a) {
   using namespace tile;
   using O = tile::Op<true>;
-  constexpr int NT = 512, CTH = 2, NBT = 4, PD = 4;
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  constexpr int NW = 8, NBT = 4, NT = NW * 64, CTH = 16 / NW, PD = 4;
   extern __shared__ __align__(16) unsigned char lds[];
   unsigned char *ldsH = lds;
   unsigned char *ldsX = lds;  // alias: see above
   float *ldsBias = reinterpret_cast<float *>(lds + (size_t)VBM * a.hpitch);  // b1 | b2
   const int nct = a.net.nct[0];
-  float *ldsW3 = ldsBias + 2 * nct * 32;  // output weights, one float per hidden feature
-  float *ldsPart = ldsW3 + nct * 32;      // [16][128] partial sums of the output layer
+  __bf16 *ldsW3 = reinterpret_cast<__bf16 *>(ldsBias + 2 * nct * 32);  // output weights, one per hidden feature
+  float *ldsPart = reinterpret_cast<float *>(ldsW3 + nct * 32);        // [2 NW][VBM] partial sums of the output layer
   const int tid = threadIdx.x;
   const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ct0 = w * CTH;
-  const int S = a.S, G = a.groups;
+  const int S = SS > 0 ? SS : a.S;           // (compile-time for the named workloads: the index
+  const int G = NKB1 > 0 ? 4 * NKB1 : a.groups;  //  arithmetic of fetch and stash folds into constants)
+  auto row_of_group = [&](int idx) { return NKB1 > 0 ? idx / (4 * (NKB1 > 0 ? NKB1 : 1)) : (int)__umulhi((unsigned)idx, a.g_magic); };
   const int last_c4 = 4 * ((S + 3) / 4 - 1);  // first column of the last group that holds data
   const int64_t ntiles = a.rows / VBM;
 
-  constexpr int NX = NKB1 > 0 ? NKB1 : VPRE_MAX;  // 16-byte groups per thread and tile
+  constexpr int NX = NKB1 > 0 ? VBM * 4 * NKB1 / NT : VPRE_MAX;  // 16-byte groups per thread and tile
   const int sh = 4 * ((S + 3) / 4) - S;            // floats the row-end group is shifted by (0..3), uniform
   f32x4 pre[NX];
   // Every thread issues its 16-byte loads unconditionally.  The group that straddles the end of a row is read
@@ -505,7 +508,7 @@ __global__ __launch_bounds__(512) void value128_kernel(ValueArgs a) {
 #pragma unroll
     for (int i = I0; i < I1; ++i) {
       const int idx = min(tid_f + NT * i, VBM * G - 1);
-      const int row = (int)__umulhi((unsigned)idx, a.g_magic);
+      const int row = row_of_group(idx);
       const int c4 = min(4 * (idx - row * G), last_c4);
       const int off = c4 == last_c4 ? c4 - sh : c4;
       pre[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(src + (size_t)row * S + off));
@@ -518,7 +521,7 @@ __global__ __launch_bounds__(512) void value128_kernel(ValueArgs a) {
     for (int i = 0; i < NX; ++i) {
       const int idx = tid_s + NT * i;
       const int idc = min(idx, VBM * G - 1);
-      const int row = (int)__umulhi((unsigned)idc, a.g_magic);
+      const int row = row_of_group(idc);
       const int c4 = 4 * (idc - row * G);
       const f32x4 v = pre[i];
       // the row-end group, shifted down by sh with zeros behind (selects on the uniform sh, no branches)
@@ -557,7 +560,7 @@ __global__ __launch_bounds__(512) void value128_kernel(ValueArgs a) {
         ldsBias[nct * 32 + i] = net.b[1][i];
         // output weights of feature 0 out of the packed blocks: k = 16 kb + 8 g + e sits in lane 32 g
         const int kb = i >> 4, gg = (i >> 3) & 1, e = i & 7;
-        ldsW3[i] = (float)reinterpret_cast<const __bf16 *>(net.W[2])[((size_t)kb * 64 + 32 * gg) * 8 + e];
+        ldsW3[i] = reinterpret_cast<const __bf16 *>(net.W[2])[((size_t)kb * 64 + 32 * gg) * 8 + e];
       }
       b3 = net.b[2][0];
       staged_agent = agent;
@@ -613,14 +616,20 @@ __global__ __launch_bounds__(512) void value128_kernel(ValueArgs a) {
         for (int j = 0; j < 4; ++j) {
           const int f0 = (ct0 + c) * 32 + 8 * j + 4 * ge;
           const f32x4 bv = *reinterpret_cast<const f32x4 *>(lb2 + f0);
-          const f32x4 wv = *reinterpret_cast<const f32x4 *>(ldsW3 + f0);
+          const u32x2 wv = *reinterpret_cast<const u32x2 *>(ldsW3 + f0);  // four bf16 weights
+          const uint32_t wlo = wv[0], whi = wv[1];  // (scalars first: a bit cast straight from a vector element reads element 0)
+          const bf16x2 w01 = __builtin_bit_cast(bf16x2, wlo), w23 = __builtin_bit_cast(bf16x2, whi);
 #pragma unroll
-          for (int q = 0; q < NBT; ++q)
+          for (int q = 0; q < NBT; ++q) {
+            float h[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const float h = tanh_from_scaled(fmaf(acc[c][q][4 * j + i], kTwoLog2e, bv[i] * kTwoLog2e));
-              part[q] = fmaf((float)(__bf16)h, wv[i], part[q]);
-            }
+            for (int i = 0; i < 4; ++i)
+              h[i] = tanh_from_scaled(fmaf(acc[c][q][4 * j + i], kTwoLog2e, bv[i] * kTwoLog2e));
+            // activations rounded to bf16 as the hidden tile would hold them; products summed in fp32
+            const bf16x2 h01 = {(__bf16)h[0], (__bf16)h[1]}, h23 = {(__bf16)h[2], (__bf16)h[3]};
+            part[q] = __builtin_amdgcn_fdot2_f32_bf16(h01, w01, part[q], false);
+            part[q] = __builtin_amdgcn_fdot2_f32_bf16(h23, w23, part[q], false);
+          }
         }
       }
 #pragma unroll
@@ -639,7 +648,7 @@ __global__ __launch_bounds__(512) void value128_kernel(ValueArgs a) {
     if (tid_y < VBM) {
       float y = b3;
 #pragma unroll
-      for (int p = 0; p < 16; ++p) y += ldsPart[p * VBM + tid_y];
+      for (int p = 0; p < 2 * NW; ++p) y += ldsPart[p * VBM + tid_y];
       __builtin_nontemporal_store(y, &a.Y[row0 + tid_y]);
     }
   }
@@ -830,9 +839,9 @@ static bool try_launch_tiles(hipStream_t st, const PackedNet &net, int64_t rows,
 }
 
 
-template <int NKB1, int NKB2>
-static hipError_t launch_value128(hipStream_t st, const ValueArgs &a, unsigned blocks, size_t lds) {
-  auto kern = value128_kernel<NKB1, NKB2>;
+template <int NKB1, int NKB2, int SS>
+static hipError_t launch_value(hipStream_t st, const ValueArgs &a, unsigned blocks, size_t lds) {
+  auto kern = value_kernel<NKB1, NKB2, SS>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -844,11 +853,11 @@ static hipError_t launch_value128(hipStream_t st, const ValueArgs &a, unsigned b
   return hipGetLastError();
 }
 
-// The 128-row value kernel covers a bf16 critic with 512 hidden units on dense rows of at most 304 columns,
-// when there are enough rows to give every compute unit several tiles and agents own multiples of 128 envs.
+// The value kernel covers a bf16 critic with 512 hidden units on dense rows of at most 304 columns, when
+// there are enough rows to give every compute unit several tiles and agents own multiples of 128 envs.
 // `rows` must be a multiple of 128 and X must start at a multiple of N rows of the caller's buffer.
-static bool try_launch_value128(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx,
-                                float *Y, int32_t N, int32_t envs_per_agent, hipError_t *err) {
+static bool try_launch_value(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx,
+                             float *Y, int32_t N, int32_t envs_per_agent, hipError_t *err) {
   const int S = net.in_dim[0], Hd = net.out_dim[0];
   if (!net.bf16 || net.out_dim[2] != 1 || Hd != 512 || net.out_dim[1] != 512 || ldx != S || S < 4) return false;
   if ((reinterpret_cast<uintptr_t>(X) & 3u) || N % VBM != 0 || envs_per_agent % VBM != 0) return false;
@@ -865,12 +874,13 @@ static bool try_launch_value128(hipStream_t st, const PackedNet &net, int64_t ro
   a.g_magic = (uint32_t)((0x100000000ull + (uint64_t)a.groups - 1) / (uint64_t)a.groups);
   a.xpitch = tile::tile_pitch(net.nkb[0] * 16, 2);
   a.hpitch = tile::tile_pitch(Hd, 2);
-  const size_t lds = (size_t)VBM * a.hpitch + (size_t)3 * net.nct[0] * 32 * 4 + (size_t)16 * VBM * 4;
+  const size_t lds = (size_t)VBM * a.hpitch + (size_t)net.nct[0] * 32 * (4 + 4 + 2) + (size_t)16 * VBM * 4;
   if (lds > 160 * 1024) return false;
   const int64_t ntiles = rows / VBM;
   const unsigned blocks = (unsigned)(ntiles < compute_units() ? ntiles : compute_units());
-  if (net.nkb[0] == 19 && net.nkb[1] == 32) *err = launch_value128<19, 32>(st, a, blocks, lds);
-  else *err = launch_value128<0, 32>(st, a, blocks, lds);
+  // the observation width of the named workloads gets compile-time index arithmetic and k loops
+  if (S == 301) *err = launch_value<19, 32, 301>(st, a, blocks, lds);
+  else *err = launch_value<0, 32, 0>(st, a, blocks, lds);
   return true;
 }
 
@@ -884,7 +894,7 @@ hipError_t launch_mlp(hipStream_t st, const PackedNet &net, int64_t rows, const 
     // a long value-head buffer: 128-row tiles first
     hipError_t terr = hipSuccess;
     const int64_t full = rows / VBM * VBM;
-    if (try_launch_value128(st, net, full, X, ldx, Y, N, envs_per_agent, &terr)) {
+    if (try_launch_value(st, net, full, X, ldx, Y, N, envs_per_agent, &terr)) {
       if (terr != hipSuccess || full == rows) return terr;
       X += full * ldx;
       Y += full * net.out_dim[2];
