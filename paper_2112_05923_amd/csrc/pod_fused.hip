@@ -24,6 +24,8 @@
 // Compiled with floating-point contraction off (integer decisions depend on
 // one rounding per operation); the network code uses explicit fmaf.
 #include "pod_internal.h"
+#include <type_traits>
+
 #include "pod_tile.h"
 
 namespace pod {
@@ -128,6 +130,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   float *s_p = reinterpret_cast<float *>(s_h + E * Dp);  // prices the trades execute at
   Row *s_row = reinterpret_cast<Row *>(s_p + E * Dp);
   float *s_cash = reinterpret_cast<float *>(s_row + E);
+  int32_t *s_done = reinterpret_cast<int32_t *>(s_cash + E);  // episode-end flags of the step just taken
   // scratch in the hidden tile
   int32_t *s_k = reinterpret_cast<int32_t *>(ldsH);        // wanted shares
   float *s_val = reinterpret_cast<float *>(s_k + E * Dp);   // sale proceeds (k < 0) or unit cost (k > 0)
@@ -227,7 +230,10 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     }
   };
   // Portfolio part of an observation: cash and holdings from the ledger.
-  auto emit_portfolio = [&](float *obs_row) {
+  // AFTER_STEP: also writes the executed trades of step t out and clears the holdings of envs whose episode
+  // ended (the same thread owns an (env, stock) slot in both roles, so no barrier is needed in between).
+  auto emit_portfolio = [&](float *obs_row, auto after_step, size_t g0) {
+    constexpr bool AFTER_STEP = decltype(after_step)::value;
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
     if (tid < E) {
@@ -245,7 +251,15 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       const int idx = tid + NT * i;
       if (idx < E * D) {
         const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
-        const float sv = (float)s_h[e * Dp + dd] * d.s_hold;
+        int32_t h = s_h[e * Dp + dd];
+        if (AFTER_STEP) {
+          if (a.shares) a.shares[g0 + idx] = s_q[e * Dp + dd];
+          if (s_done[e]) {
+            h = 0;
+            s_h[e * Dp + dd] = 0;
+          }
+        }
+        const float sv = (float)h * d.s_hold;
         __builtin_nontemporal_store(sv, &obs_row[(size_t)(n0 + e) * S + 1 + D + dd]);
         if (ACTOR) O::store1(ldsX + (size_t)e * a.xpitch + (1 + D + dd) * O::ESZ, sv);
       }
@@ -290,7 +304,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   {
     fetch_market();
     emit_market(a.obs, r_po, r_ind);
-    emit_portfolio(a.obs);
+    emit_portfolio(a.obs, std::false_type{}, 0);
   }
   __syncthreads();
   if (wave == 0) {
@@ -389,22 +403,17 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       asm volatile("" : "+v"(e));  // per-step opaque, or the chunk addresses are hoisted out of the step loop
       const int n = n0 + e, o0 = e * Dp;
       constexpr int CH = 16;
-      float e2 = 0.0f;
 #pragma unroll
       for (int c0 = 0; c0 < DMAX; c0 += CH) {
         int32_t kk[CH];
-        float vv[CH], ee[CH];
+        float vv[CH];
 #pragma unroll
         for (int j = 0; j < CH; ++j) {
           kk[j] = s_k[o0 + c0 + j];
           vv[j] = s_val[o0 + c0 + j];
-          ee[j] = s_e2[o0 + c0 + j];
         }
 #pragma unroll
-        for (int j = 0; j < CH; ++j) {
-          e2 += ee[j];
-          cash = kk[j] < 0 ? cash + vv[j] : cash;
-        }
+        for (int j = 0; j < CH; ++j) cash = kk[j] < 0 ? cash + vv[j] : cash;
       }
 #pragma unroll
       for (int c0 = 0; c0 < DMAX; c0 += CH) {
@@ -457,7 +466,6 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       const size_t tn = (size_t)t * N + n;
       a.reward[tn] = (float)r;
       a.done[tn] = (uint8_t)dn;
-      if (a.logp) a.logp[tn] = fmaf(-0.5f, e2, d.logp_const);
       if (dn) {
         ep_sum += ep_ret;
         ep_sqsum += ep_ret * ep_ret;
@@ -470,6 +478,23 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         tau += 1;
       }
       s_cash[e] = cash;
+      s_done[e] = dn;
+      s_row[e] = row_of(d, tau, n);  // cursor rows of step t + 1 (nobody reads the old ones any more)
+    } else if (wave == 1 && a.logp) {
+      // ---- log-probability of the sampled action: squared noise summed in stock order, one lane per env
+      int e = lane;
+      asm volatile("" : "+v"(e));
+      const int o0 = e * Dp;
+      float e2 = 0.0f;
+#pragma unroll
+      for (int c0 = 0; c0 < DMAX; c0 += 16) {
+        float ee[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) ee[j] = s_e2[o0 + c0 + j];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) e2 += ee[j];  // empty slots add +0
+      }
+      a.logp[(size_t)t * N + n0 + e] = fmaf(-0.5f, e2, d.logp_const);
     }
     // ---- meanwhile (and the ledger lanes afterwards): market part of observation t+1
     emit_market(obs_next, r_po, r_ind);
@@ -477,20 +502,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     if (ACTOR && t + 1 < a.T) prime<CTH, ring_depth(CTH)>(ring, net.W[0], net.nkb[0], net.nct[0], wave * CTH, lane);
 
     // ---- executed trades out; episode ends clear the holdings; portfolio part of observation t+1
-    int tid_q = threadIdx.x;
-    asm volatile("" : "+v"(tid_q));
-#pragma unroll
-    for (int i = 0; i < PAIRS_MAX; ++i) {
-      const int idx = tid_q + NT * i;
-      if (idx < E * D) {
-        const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
-        if (a.shares) a.shares[g0 + idx] = s_q[e * Dp + dd];
-        if (s_row[e].done) s_h[e * Dp + dd] = 0;
-      }
-    }
-    __syncthreads();
-    emit_portfolio(obs_next);
-    if (wave == 0) s_row[lane] = row_of(d, tau, n0 + lane);
+    emit_portfolio(obs_next, std::true_type{}, g0);
   }
 
   // ---- epilogue: state back to the workspace
@@ -537,7 +549,7 @@ size_t fused_lds_bytes(const pr_config &c, bool with_actor) {
   if (hid < env_scratch) hid = env_scratch;
   size_t n = hid + (size_t)BM * tile_pitch(kp, esz);
   if (with_actor) n += (size_t)(Hd / KB) * 1024 + (size_t)(2 * (Hd / 32) + 1) * 32 * 4;
-  n += (size_t)2 * E * Dp * 4 + (size_t)E * (sizeof(Row) + sizeof(float));
+  n += (size_t)2 * E * Dp * 4 + (size_t)E * (sizeof(Row) + sizeof(float) + sizeof(int32_t));
   return n;
 }
 
