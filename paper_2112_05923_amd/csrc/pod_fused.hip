@@ -15,11 +15,10 @@
 // Trade execution reproduces, operation for operation in binary32, the serial
 // rule "all sales in stock order, then all purchases in stock order, each
 // limited by the cash left": everything that does not depend on the running
-// cash (wanted shares, sale quantities and proceeds, unit costs, full-purchase
-// outlays) is computed by all 512 lanes in parallel; one ledger lane per env
-// then walks the cash chain.  A purchase takes the division path only when the
-// cash is between one share and the full wish; outside that range the result
-// of the division path is known without dividing (see buy_step).
+// cash (wanted shares, sale quantities and proceeds, unit costs) is computed
+// by all 512 lanes in parallel; one ledger lane per env then walks the cash
+// chain in branch-free code, where the latency of the dependent operations on
+// the running cash is what bounds the step.
 //
 // Compiled with floating-point contraction off (integer decisions depend on
 // one rounding per operation); the network code uses explicit fmaf.
@@ -80,32 +79,6 @@ __device__ inline Row row_of(const EnvDims &d, int32_t tau, int32_t n) {
   return r;
 }
 
-// One purchase of the ledger: k > 0 wanted shares at unit cost u (price * (1 + c)).
-// Reference rule (binary32):  m = floor(cash / u); q = min(k, max(m, 0)); if (q * u > cash) q -= 1.
-//  - cash >= fl((k+1) u)  implies cash >= k u exactly, hence fl(cash / u) >= k and q = k; the outlay fl(k u)
-//    is <= fl((k+1) u) <= cash, so the guard cannot fire.
-//  - cash < u  implies fl(cash / u) <= 1, and if it rounds to 1 the guard (u > cash) takes the share back: q = 0.
-//  - otherwise the division is executed.
-__device__ inline void buy_step(float &cash, int32_t k, float u, float full_outlay, float full_thresh, int32_t &q) {
-  if (cash >= full_thresh) {
-    q = k;
-    cash = cash - full_outlay;
-  } else if (cash < u) {
-    q = 0;
-  } else {
-    const float ratio = cash / u;
-    int32_t m = (int32_t)floorf(ratio);
-    m = max(m, 0);
-    q = min(k, m);
-    float outlay = (float)q * u;
-    if (outlay > cash) {
-      q -= 1;
-      outlay = (float)q * u;
-    }
-    cash = cash - outlay;
-  }
-}
-
 template <bool BF16, int CTH, int NKB1, int NKB2, bool ACTOR>
 __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   using O = tile::Op<BF16>;
@@ -134,9 +107,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   // scratch in the hidden tile
   int32_t *s_k = reinterpret_cast<int32_t *>(ldsH);        // wanted shares
   float *s_val = reinterpret_cast<float *>(s_k + E * Dp);   // sale proceeds (k < 0) or unit cost (k > 0)
-  float *s_out = s_val + E * Dp;                            // outlay of the full purchase
-  float *s_thr = s_out + E * Dp;                            // cash from which the full purchase is certain
-  int32_t *s_q = reinterpret_cast<int32_t *>(s_thr + E * Dp);  // executed shares, signed
+  int32_t *s_q = reinterpret_cast<int32_t *>(s_val + E * Dp);  // executed shares, signed
   float *s_pv = reinterpret_cast<float *>(s_q + E * Dp);    // valuation prices
   float *s_e2 = s_pv + E * Dp;                              // squared noise
   float *s_mu = reinterpret_cast<float *>(ldsX);            // [E][32] policy means (actor variant)
@@ -360,7 +331,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         const int32_t k = (int32_t)truncf(ac * d.hmax);
         const float p = s_p[o];
         int32_t q = 0;
-        float val = 0.0f, outl = 0.0f, thr = 0.0f;
+        float val = 0.0f;
         if (k < 0) {
           const int32_t h = s_h[o];
           q = min(-k, h);
@@ -370,13 +341,9 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
           q = -q;
         } else if (k > 0) {
           val = p * d.one_plus_c;
-          outl = (float)k * val;
-          thr = (float)(k + 1) * val;
         }
         s_k[o] = k;
         s_val[o] = val;
-        s_out[o] = outl;
-        s_thr[o] = thr;
         s_q[o] = q;
         s_pv[o] = r_pv[i];
         s_e2[o] = eps * eps;
@@ -387,8 +354,6 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         const int o = tid_p * Dp + dd;
         s_k[o] = 0;
         s_val[o] = 0.0f;
-        s_out[o] = 0.0f;
-        s_thr[o] = 0.0f;
         s_q[o] = 0;
         s_pv[o] = 0.0f;
         s_e2[o] = 0.0f;
@@ -415,35 +380,38 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
 #pragma unroll
         for (int j = 0; j < CH; ++j) cash = kk[j] < 0 ? cash + vv[j] : cash;
       }
+      // Purchases in stock order, the rule of the reference in straight-line code:
+      //   m = floor(cash / u); q = min(k, max(m, 0)); if (q u > cash) q -= 1; cash -= q u        (binary32)
+      // One lane per env walks a dependent chain on `cash`, so what counts is the length of that chain, not
+      // the instruction count: no data-dependent branches (a branch taken for one lane costs all 64 the round
+      // trip through the scalar unit), and everything that does not depend on `cash` sits off the chain.
 #pragma unroll
       for (int c0 = 0; c0 < DMAX; c0 += CH) {
-        int32_t kk[CH], hh[CH];
-        float uu[CH], oo[CH], tt[CH];
+        int32_t kk[CH], hh[CH], qq[CH];
+        float uu[CH];
 #pragma unroll
         for (int j = 0; j < CH; ++j) {
           kk[j] = s_k[o0 + c0 + j];
           uu[j] = s_val[o0 + c0 + j];
-          oo[j] = s_out[o0 + c0 + j];
-          tt[j] = s_thr[o0 + c0 + j];
           hh[j] = s_h[o0 + c0 + j];
+          qq[j] = s_q[o0 + c0 + j];
         }
 #pragma unroll
         for (int j = 0; j < CH; ++j) {
           const int32_t k = kk[j];
           const bool buy = k > 0;
-          const bool full = cash >= tt[j], none = cash < uu[j];
-          int32_t q = full ? k : 0;
-          float c_fast = cash - (full ? oo[j] : 0.0f);
-          if (buy && !full && !none) {
-            // between one share and the full wish: the division decides (see buy_step)
-            c_fast = cash;
-            buy_step(c_fast, k, uu[j], oo[j], tt[j], q);
-          }
-          if (buy) {  // (a sale or a hold leaves its slot as the first pass wrote it)
-            cash = c_fast;
-            s_h[o0 + c0 + j] = hh[j] + q;
-            s_q[o0 + c0 + j] = q;
-          }
+          const float u = buy ? uu[j] : 1.0f;  // (sales and holds keep the slot as the first pass wrote it)
+          const float ratio = cash / u;
+          int32_t m = (int32_t)floorf(ratio);
+          m = max(m, 0);
+          int32_t q = min(k, m);
+          const float out_q = (float)q * u, out_q1 = (float)(q - 1) * u;
+          const bool over = out_q > cash;
+          q = over ? q - 1 : q;
+          const float outlay = over ? out_q1 : out_q;
+          cash = buy ? cash - outlay : cash;
+          s_h[o0 + c0 + j] = hh[j] + (buy ? q : 0);
+          s_q[o0 + c0 + j] = buy ? q : qq[j];
         }
       }
       double asset1 = (double)cash;
@@ -544,7 +512,7 @@ size_t fused_lds_bytes(const pr_config &c, bool with_actor) {
   const int D = c.n_stocks, DK = c.n_stocks * c.n_ind, S = 1 + 2 * D + DK, Hd = c.hidden, Dp = kDp;
   const int bf = c.mlp_dtype == PR_MLP_BF16, esz = bf ? 2 : 4, KB = bf ? 16 : 8;
   const int kp = (S + KB - 1) / KB * KB;
-  size_t env_scratch = (size_t)7 * E * Dp * 4;
+  size_t env_scratch = (size_t)5 * E * Dp * 4;
   size_t hid = (size_t)BM * tile_pitch(Hd, esz);
   if (hid < env_scratch) hid = env_scratch;
   size_t n = hid + (size_t)BM * tile_pitch(kp, esz);
