@@ -16,6 +16,8 @@ struct pr_handle {
   EnvState st;
   pr_market market;
   PackedNet actor, critic;
+  PackedNet actor_fused;  // the actor with layer 1 packed in the input order of the persistent rollout kernel
+  void *w1_fused;
   void *w_packed[2][3];   // device, per net and layer
   float *b_packed[2][3];
   float *mu_scratch;      // [N, D]
@@ -47,6 +49,7 @@ bool is_pow2_float(float x) {
 
 struct Layout {
   size_t w[2][3], b[2][3];
+  size_t w1_fused;
   size_t cash, tau, h, ep_ret, ep_sum, ep_sqsum, ep_cnt, mu;
   size_t total;
 };
@@ -96,6 +99,7 @@ Layout make_layout(const pr_config &c) {
       L.b[net][l] = take((size_t)padded_out(out_dim[l]) * 4 * P);
     }
   }
+  L.w1_fused = c.schedule == PR_SCHED_FUSED ? take(packed_weight_bytes(S, Hd, bf) * P) : 0;
   L.cash = take(N * 4);
   L.tau = take(N * 4);
   L.h = take(N * D * 4);
@@ -140,9 +144,14 @@ int pack_nets(pr_handle *h, const pr_weights *actor, const pr_weights *critic) {
     const int in_dim[3] = {S, Hd, Hd};
     const int out_dim[3] = {Hd, Hd, net == 0 ? D : 1};
     for (int l = 0; l < 3; ++l)
-      POD_HIP(launch_pack_layer(h->stream, W[l], b[l], P, in_dim[l], out_dim[l], bf, h->w_packed[net][l],
+      POD_HIP(launch_pack_layer(h->stream, W[l], b[l], P, in_dim[l], out_dim[l], bf, 0, h->w_packed[net][l],
                                 h->b_packed[net][l]));
   }
+  // The persistent rollout kernel keeps its observation tile as [indicators | cash | prices | holdings]:
+  // the same layer-1 weights with their rows rotated by the D K indicator columns (biases are shared).
+  if (c.schedule == PR_SCHED_FUSED)
+    POD_HIP(launch_pack_layer(h->stream, actor->W1, actor->b1, P, S, Hd, bf, D * c.n_ind, h->w1_fused,
+                              h->b_packed[0][0]));
   return PR_OK;
 }
 
@@ -233,6 +242,9 @@ int rollout_init(const pr_config *cfg, const pr_market *market, const pr_weights
   d.s_ind = cfg->obs_scale[3];
 
   fill_net(h->actor, h, 0);
+  h->w1_fused = cfg->schedule == PR_SCHED_FUSED ? static_cast<void *>(ws + L.w1_fused) : nullptr;
+  h->actor_fused = h->actor;
+  h->actor_fused.W[0] = h->w1_fused;
   fill_net(h->critic, h, 1);
   int prc = pack_nets(h, actor, critic);
   if (prc == PR_OK) {
@@ -265,7 +277,7 @@ int rollout_step_T(pr_handle *h, int32_t T, const float *noise, const pr_buffers
   const size_t N = (size_t)h->cfg.n_envs, D = (size_t)h->cfg.n_stocks, S = (size_t)h->S;
   const int32_t per_agent = h->cfg.n_envs / h->cfg.n_agents;
   if (h->cfg.schedule == PR_SCHED_FUSED) {
-    POD_HIP(launch_rollout_fused(h->stream, h->cfg, h->dims, h->st, h->market.price, h->market.ind, h->actor,
+    POD_HIP(launch_rollout_fused(h->stream, h->cfg, h->dims, h->st, h->market.price, h->market.ind, h->actor_fused,
                                  per_agent, T, noise, nullptr, *out));
   } else {
     POD_HIP(launch_observe(h->stream, h->dims, h->st, h->market.price, h->market.ind, out->obs));
@@ -289,8 +301,8 @@ int rollout_step_forced(pr_handle *h, int32_t T, const float *mu, const float *n
   if (rc != PR_OK) return rc;
   const size_t N = (size_t)h->cfg.n_envs, D = (size_t)h->cfg.n_stocks;
   if (h->cfg.schedule == PR_SCHED_FUSED) {
-    POD_HIP(launch_rollout_fused(h->stream, h->cfg, h->dims, h->st, h->market.price, h->market.ind, h->actor,
-                                 h->cfg.n_envs / h->cfg.n_agents, T, noise, mu, *out));
+    POD_HIP(launch_rollout_fused(h->stream, h->cfg, h->dims, h->st, h->market.price, h->market.ind,
+                                 h->actor_fused, h->cfg.n_envs / h->cfg.n_agents, T, noise, mu, *out));
     return PR_OK;
   }
   POD_HIP(launch_observe(h->stream, h->dims, h->st, h->market.price, h->market.ind, out->obs));

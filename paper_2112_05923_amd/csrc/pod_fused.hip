@@ -110,6 +110,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   int32_t *s_q = reinterpret_cast<int32_t *>(s_val + E * Dp);  // executed shares, signed
   float *s_pv = reinterpret_cast<float *>(s_q + E * Dp);    // valuation prices
   float *s_e2 = s_pv + E * Dp;                              // squared noise
+  double *s_rcp = reinterpret_cast<double *>(s_e2 + E * Dp);  // 1 / unit cost of a purchase, binary64
   float *s_mu = reinterpret_cast<float *>(ldsX);            // [E][32] policy means (actor variant)
 
   // ---- ledger lanes (wavefront 0): per-env scalars in registers for the whole rollout
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         s_p[e * Dp + dd] = v;
         const float sv = v * d.s_price;
         __builtin_nontemporal_store(sv, &obs_row[(size_t)(n0 + e) * S + 1 + dd]);
-        if (ACTOR) O::store1(ldsX + (size_t)e * a.xpitch + (1 + dd) * O::ESZ, sv);
+        if (ACTOR) O::store1(ldsX + (size_t)e * a.xpitch + (DK + 1 + dd) * O::ESZ, sv);
       }
     }
     if (tid >= 64) {
@@ -189,13 +190,8 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
           sv[3] *= d.s_ind;
           // observation rows are 4-byte aligned only; a 16-byte store needs no more than that
           __builtin_nontemporal_store(sv, reinterpret_cast<f32x4 *>(obs_row + (size_t)(n0 + e) * S + 1 + 2 * D + j));
-          if (ACTOR) {
-            unsigned char *x = ldsX + (size_t)e * a.xpitch + (1 + 2 * D + j) * O::ESZ;
-            O::store1(x, sv[0]);
-            O::store1(x + O::ESZ, sv[1]);
-            O::store1(x + 2 * O::ESZ, sv[2]);
-            O::store1(x + 3 * O::ESZ, sv[3]);
-          }
+          // (indicators lead the LDS tile, so a group of four is one aligned store)
+          if (ACTOR) O::store4(ldsX + (size_t)e * a.xpitch + j * O::ESZ, sv[0], sv[1], sv[2], sv[3]);
         }
       }
     }
@@ -211,7 +207,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       const float sv = s_cash[tid] * d.s_cash;
       __builtin_nontemporal_store(sv, &obs_row[(size_t)(n0 + tid) * S]);
       if (ACTOR) {
-        O::store1(ldsX + (size_t)tid * a.xpitch, sv);
+        O::store1(ldsX + (size_t)tid * a.xpitch + DK * O::ESZ, sv);
         // the policy means were parked over the head of this tile: restore the zero k padding of every row
         const int kp = (a.xpitch - 16) / O::ESZ;
         for (int c = S; c < kp; ++c) O::store1(ldsX + (size_t)tid * a.xpitch + c * O::ESZ, 0.0f);
@@ -232,7 +228,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         }
         const float sv = (float)h * d.s_hold;
         __builtin_nontemporal_store(sv, &obs_row[(size_t)(n0 + e) * S + 1 + D + dd]);
-        if (ACTOR) O::store1(ldsX + (size_t)e * a.xpitch + (1 + D + dd) * O::ESZ, sv);
+        if (ACTOR) O::store1(ldsX + (size_t)e * a.xpitch + (DK + 1 + D + dd) * O::ESZ, sv);
       }
     }
   };
@@ -332,6 +328,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         const float p = s_p[o];
         int32_t q = 0;
         float val = 0.0f;
+        double rcp = 0.0;
         if (k < 0) {
           const int32_t h = s_h[o];
           q = min(-k, h);
@@ -341,9 +338,11 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
           q = -q;
         } else if (k > 0) {
           val = p * d.one_plus_c;
+          rcp = 1.0 / (double)val;
         }
         s_k[o] = k;
         s_val[o] = val;
+        s_rcp[o] = rcp;
         s_q[o] = q;
         s_pv[o] = r_pv[i];
         s_e2[o] = eps * eps;
@@ -354,6 +353,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         const int o = tid_p * Dp + dd;
         s_k[o] = 0;
         s_val[o] = 0.0f;
+        s_rcp[o] = 0.0;
         s_q[o] = 0;
         s_pv[o] = 0.0f;
         s_e2[o] = 0.0f;
@@ -385,33 +385,38 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       // One lane per env walks a dependent chain on `cash`, so what counts is the length of that chain, not
       // the instruction count: no data-dependent branches (a branch taken for one lane costs all 64 the round
       // trip through the scalar unit), and everything that does not depend on `cash` sits off the chain.
+      // The binary32 quotient comes from one binary64 product with the reciprocal of u prepared by the other
+      // lanes: the product is within 2^-52 of cash / u, a quotient of two binary32 numbers is at least 2^-49
+      // (relative) away from every binary32 rounding boundary it does not hit exactly, so rounding the product
+      // to binary32 gives the correctly rounded cash / u -- the same value as the division, in 3 dependent
+      // operations instead of 11.
 #pragma unroll
       for (int c0 = 0; c0 < DMAX; c0 += CH) {
         int32_t kk[CH], hh[CH], qq[CH];
         float uu[CH];
+        double rr[CH];
 #pragma unroll
         for (int j = 0; j < CH; ++j) {
           kk[j] = s_k[o0 + c0 + j];
           uu[j] = s_val[o0 + c0 + j];
+          rr[j] = s_rcp[o0 + c0 + j];
           hh[j] = s_h[o0 + c0 + j];
           qq[j] = s_q[o0 + c0 + j];
         }
 #pragma unroll
         for (int j = 0; j < CH; ++j) {
-          const int32_t k = kk[j];
-          const bool buy = k > 0;
-          const float u = buy ? uu[j] : 1.0f;  // (sales and holds keep the slot as the first pass wrote it)
-          const float ratio = cash / u;
-          int32_t m = (int32_t)floorf(ratio);
-          m = max(m, 0);
-          int32_t q = min(k, m);
+          const bool buy = kk[j] > 0;
+          const int32_t k = max(kk[j], 0);  // sales and holds: k = 0 and reciprocal 0 give q = 0, outlay 0
+          const float u = uu[j];
+          const float ratio = (float)((double)cash * rr[j]);
+          const int32_t m = (int32_t)ratio;  // (toward zero: floor for ratio >= 0, and negatives end at 0 below)
+          int32_t q = min(k, max(m, 0));
           const float out_q = (float)q * u, out_q1 = (float)(q - 1) * u;
-          const bool over = out_q > cash;
+          const bool over = buy && out_q > cash;
           q = over ? q - 1 : q;
-          const float outlay = over ? out_q1 : out_q;
-          cash = buy ? cash - outlay : cash;
-          s_h[o0 + c0 + j] = hh[j] + (buy ? q : 0);
-          s_q[o0 + c0 + j] = buy ? q : qq[j];
+          cash = cash - (over ? out_q1 : out_q);
+          s_h[o0 + c0 + j] = hh[j] + q;
+          s_q[o0 + c0 + j] = qq[j] + q;  // (a purchase slot held 0)
         }
       }
       double asset1 = (double)cash;
@@ -512,7 +517,7 @@ size_t fused_lds_bytes(const pr_config &c, bool with_actor) {
   const int D = c.n_stocks, DK = c.n_stocks * c.n_ind, S = 1 + 2 * D + DK, Hd = c.hidden, Dp = kDp;
   const int bf = c.mlp_dtype == PR_MLP_BF16, esz = bf ? 2 : 4, KB = bf ? 16 : 8;
   const int kp = (S + KB - 1) / KB * KB;
-  size_t env_scratch = (size_t)5 * E * Dp * 4;
+  size_t env_scratch = (size_t)7 * E * Dp * 4;
   size_t hid = (size_t)BM * tile_pitch(Hd, esz);
   if (hid < env_scratch) hid = env_scratch;
   size_t n = hid + (size_t)BM * tile_pitch(kp, esz);

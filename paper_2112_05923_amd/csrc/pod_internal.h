@@ -74,8 +74,10 @@ struct PackedNet {
 
 size_t packed_weight_bytes(int in_dim, int out_dim, int bf16);
 int padded_out(int out_dim);
+// k_rot > 0: packed k row k' holds input row (k' < k_rot ? in_dim - k_rot + k' : k' - k_rot), i.e. the last k_rot
+// inputs come first.
 hipError_t launch_pack_layer(hipStream_t st, const float *W, const float *b, int P, int in_dim, int out_dim, int bf16,
-                             void *Wp, float *bp);
+                             int k_rot, void *Wp, float *bp);
 // rows of X [rows, ldx] -> Y [rows, out_dim[2]]; row r uses agent ((r % N) / envs_per_agent).
 hipError_t launch_mlp(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx, float *Y,
                       int32_t N, int32_t envs_per_agent);

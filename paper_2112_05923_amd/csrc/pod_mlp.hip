@@ -656,7 +656,7 @@ __global__ __launch_bounds__(512) void value_kernel(ValueArgs a) {
 
 // ------------------------------------------------------------- weight packing
 __global__ void pack_layer_kernel(const float *__restrict__ W, const float *__restrict__ b, int P, int in_dim,
-                                  int out_dim, int bf16, int nkb, int nct, void *__restrict__ Wp,
+                                  int out_dim, int bf16, int k_rot, int nkb, int nct, void *__restrict__ Wp,
                                   float *__restrict__ bp) {
   const size_t per_agent = (size_t)nct * nkb * 64;
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -673,7 +673,8 @@ __global__ void pack_layer_kernel(const float *__restrict__ W, const float *__re
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int k = kb * 16 + 8 * g + e;
-        v[e] = (__bf16)((k < in_dim && col < out_dim) ? Wa[(size_t)k * out_dim + col] : 0.0f);
+        const int ks = k < k_rot ? in_dim - k_rot + k : k - k_rot;
+        v[e] = (__bf16)((k < in_dim && col < out_dim) ? Wa[(size_t)ks * out_dim + col] : 0.0f);
       }
       __bf16 *dst = reinterpret_cast<__bf16 *>(Wp) + i * 8;
 #pragma unroll
@@ -683,7 +684,8 @@ __global__ void pack_layer_kernel(const float *__restrict__ W, const float *__re
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int k = kb * 8 + 4 * g + e;
-        dst[e] = (k < in_dim && col < out_dim) ? Wa[(size_t)k * out_dim + col] : 0.0f;
+        const int ks = k < k_rot ? in_dim - k_rot + k : k - k_rot;
+        dst[e] = (k < in_dim && col < out_dim) ? Wa[(size_t)ks * out_dim + col] : 0.0f;
       }
     }
   }
@@ -731,14 +733,14 @@ size_t packed_weight_bytes(int in_dim, int out_dim, int bf16) {
 }
 
 hipError_t launch_pack_layer(hipStream_t st, const float *W, const float *b, int P, int in_dim, int out_dim, int bf16,
-                             void *Wp, float *bp) {
+                             int k_rot, void *Wp, float *bp) {
   const int KB = kblock(bf16);
   const int nkb = (in_dim + KB - 1) / KB, nct = (out_dim + 31) / 32;
   const size_t n = (size_t)P * nct * nkb * 64;
   const size_t nb = (size_t)P * nct * 32;
   const size_t total = n > nb ? n : nb;
   hipLaunchKernelGGL(pack_layer_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, W, b, P, in_dim,
-                     out_dim, bf16, nkb, nct, Wp, bp);
+                     out_dim, bf16, k_rot, nkb, nct, Wp, bp);
   return hipGetLastError();
 }
 

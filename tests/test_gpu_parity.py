@@ -353,16 +353,30 @@ def _run(w, H, T, schedule, n_market=None, forced_mu=None, calls=1):
 
 @pytest.mark.parametrize("hidden,N,agents,H,n_market", [(512, 128, 1, 10, None), (256, 192, 1, 24, None),
                                                          (512, 128, 2, 7, None), (512, 64, 1, 24, 1)])
-def test_fused_schedule_equals_stepwise_bit_for_bit(hidden, N, agents, H, n_market):
+def test_fused_schedule_equals_stepwise_given_the_same_means(hidden, N, agents, H, n_market):
+    """The persistent kernel feeds its actor the observation columns in another order than the per-step
+    kernels, so the two schedules' policy means agree to the order of fp32 sums only.  Everything downstream
+    of the means must agree bit for bit: the per-step schedule, forced onto the means the persistent kernel
+    produced, has to reproduce its whole record and final state."""
     T = 24
     w = inputs.WORKLOADS["large"].replace(n_envs=N, n_agents=agents, hidden=hidden, steps=T)
-    _, _, _, (a,), sa = _run(w, H, T, pr.PR_SCHED_STEPWISE, n_market)
-    _, _, _, (b,), sb = _run(w, H, T, FUSED, n_market)
+    _, ro_f, _, (b,), sb = _run(w, H, T, FUSED, n_market)
+    mu_f = parity.to_np(b["mu"])
+    _, ro_s, _, (a,), sa = _run(w, H, T, pr.PR_SCHED_STEPWISE, n_market, forced_mu=mu_f)
     for k in a:
-        assert torch.equal(a[k], b[k]), k
+        if a[k] is not None:
+            assert torch.equal(a[k], b[k]), k
     for k in sa:
         assert torch.equal(sa[k], sb[k]), k
     assert int(a["done"].sum()) == (T // H) * N
+    # the means themselves, against the per-step actor kernel on the same observations
+    S = w.state_dim
+    mu_s = ro_s.mlp_forward(pr.PR_NET_ACTOR, b["obs"][:T].reshape(T * N, S)).reshape(T, N, w.n_stocks)
+    val_s = ro_s.mlp_forward(pr.PR_NET_CRITIC, b["obs"].reshape((T + 1) * N, S)).reshape(T + 1, N)
+    torch.cuda.synchronize()
+    err = (mu_s - b["mu"]).abs().amax(dim=-1) / mu_s.abs().amax(dim=-1).clamp_min(1e-30)
+    assert float(err.max()) <= parity.TOL_BF16
+    assert torch.equal(val_s, b["value"].reshape(T + 1, N))
 
 
 def test_fused_forced_env_stage_matches_checker_with_resets_and_cash_starved():
