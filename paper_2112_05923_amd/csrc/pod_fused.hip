@@ -111,7 +111,10 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   float *s_pv = reinterpret_cast<float *>(s_q + E * Dp);    // valuation prices
   float *s_e2 = s_pv + E * Dp;                              // squared noise
   double *s_rcp = reinterpret_cast<double *>(s_e2 + E * Dp);  // 1 / unit cost of a purchase, binary64
-  float *s_mu = reinterpret_cast<float *>(ldsX);            // [E][32] policy means (actor variant)
+  // output-layer accumulators of the actor, one [E][32] plane per k part of that layer (summed in the pre-compute)
+  constexpr int KS = (NKB2 > 0 && NKB2 % 4 == 0) ? 4 : 1;
+  constexpr int MUP = 33;  // row pitch of a plane (lanes of one store differ in the row: 32 would hit one bank)
+  float *s_mu = reinterpret_cast<float *>(ldsX);
 
   // ---- ledger lanes (wavefront 0): per-env scalars in registers for the whole rollout
   float cash = 0.0f;
@@ -295,14 +298,14 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     const size_t g0 = ((size_t)t * N + n0) * D;
 
     if (ACTOR) {
-      mlp_tile<BF16, NW, CTH, false, NKB1, NKB2, true, true>(
+      mlp_tile<BF16, NW, CTH, false, NKB1, NKB2, true, true, KS>(
           net, ring, ldsX, a.xpitch, ldsH, a.hpitch, ldsBias, ldsW3, tid,
           [&]() {
             fetch_step_inputs(t);
             fetch_market();
           },
           [&]() {},
-          [&](int b, int f, float z) { s_mu[b * 32 + f] = z; });  // bare accumulators, finished below
+          [&](int b, int f, float z, int part = 0) { s_mu[part * (E * MUP) + b * MUP + f] = z; });  // finished below
     } else {
       fetch_step_inputs(t);
       fetch_market();
@@ -318,7 +321,15 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       if (idx < E * D) {
         const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
         const int o = e * Dp + dd;
-        const float mu = ACTOR ? finish_out(s_mu[e * 32 + dd], lb3[dd], 1) : r_mu[i];
+        float mu;
+        if (ACTOR) {
+          float z = s_mu[e * MUP + dd];
+#pragma unroll
+          for (int part = 1; part < KS; ++part) z += s_mu[part * (E * MUP) + e * MUP + dd];
+          mu = finish_out(z, lb3[dd], 1);
+        } else {
+          mu = r_mu[i];
+        }
         const float eps = r_eps[i];
         const float a_raw = mu + d.sigma * eps;
         __builtin_nontemporal_store(a_raw, &a.act_raw[g0 + idx]);

@@ -304,12 +304,14 @@ __device__ inline void stage_net(const Net &net, float *ldsBias, u32x4 *ldsW3, i
 // Output layer with one feature tile: weights from LDS (block kb = 64 lanes x 16 B), activations from ldsH.
 // NKB > 0: straight-line code over a compile-time number of k-blocks with two accumulators (even / odd
 // k-blocks), which halves the dependent chain of matrix instructions and lets the LDS reads run ahead.
+// kb0: first k-block (NKB > 0 only), for callers that split the k range over several wavefronts.
 template <bool BF16, int NKB>
 __device__ inline void mma_out_lds(f32x16 &acc, const u32x4 *ldsW3, const unsigned char *ldsH, int hpitch, int nkb,
-                                   int bt, int lane) {
+                                   int bt, int lane, int kb0 = 0) {
   using O = Op<BF16>;
   const int brow = lane & 31, g = lane >> 5;
-  const unsigned char *xbase = ldsH + (size_t)(bt * 32 + brow) * hpitch + 16 * g;
+  const unsigned char *xbase = ldsH + (size_t)(bt * 32 + brow) * hpitch + 16 * g + (NKB > 0 ? kb0 * 32 : 0);
+  if (NKB > 0) ldsW3 += kb0 * 64;
   if (NKB > 0) {
     f32x16 acc2;
 #pragma unroll
@@ -347,8 +349,11 @@ constexpr int ring_depth(int cth) { return cth >= 8 ? 2 : 4; }
 
 // PRIMED: the caller has already called prime() for layer 1 on `ring` (to get the first weight blocks in flight
 // before the input tile is complete).  RAW_OUT: see epilogue_out.
-template <bool BF16, int NW, int CTH, bool WIDE_OUT, int NKB1, int NKB2, bool PRIMED, bool RAW_OUT, class Early,
-          class Late, class Sink>
+// KSPLIT > 1 (RAW_OUT, one output feature tile, NKB2 known): the output layer's k range is split over KSPLIT
+// wavefronts per batch tile, so that all 2 KSPLIT wavefronts share its matrix work; the sink is then called
+// as sink(row, feature, partial_sum, part) and the caller adds the KSPLIT parts.
+template <bool BF16, int NW, int CTH, bool WIDE_OUT, int NKB1, int NKB2, bool PRIMED, bool RAW_OUT, int KSPLIT = 1,
+          class Early, class Late, class Sink>
 __device__ inline void mlp_tile(const Net &net, u32x4 (&ring)[ring_depth(CTH)][CTH], const unsigned char *ldsX,
                                 int xpitch, unsigned char *ldsH, int hpitch, const float *ldsBias,
                                 const u32x4 *ldsW3, int tid, Early early, Late late, Sink sink) {
@@ -385,7 +390,18 @@ __device__ inline void mlp_tile(const Net &net, u32x4 (&ring)[ring_depth(CTH)][C
   }
   // output layer: few features.  One feature tile: wavefronts 0 and 1 take one 32-row batch tile each while
   // the others run late().  More feature tiles: split them over the wavefronts like the hidden layers.
-  if (!WIDE_OUT) {
+  if constexpr (!WIDE_OUT && KSPLIT > 1) {
+    static_assert(KSPLIT == 1 || (RAW_OUT && NKB2 > 0 && NKB2 % (KSPLIT > 0 ? KSPLIT : 1) == 0), "k split of the output layer");
+    if (w < 2 * KSPLIT) {
+      const int bt = w & 1, part = w >> 1;
+      f32x16 acc[1][1];
+      zero_acc<1, 1>(acc);
+      mma_out_lds<BF16, NKB2 / KSPLIT>(acc[0][0], ldsW3, ldsH, hpitch, net.nkb[2], bt, lane, part * (NKB2 / KSPLIT));
+      epilogue_out<1, 1, true>(acc, lb3, net.out_dim, net.out_tanh, 1, 0, bt, lane,
+                               [&](int b, int f, float z) { sink(b, f, z, part); });
+    }
+    late();
+  } else if constexpr (!WIDE_OUT) {
     if (w < 2) {
       f32x16 acc[1][1];
       zero_acc<1, 1>(acc);
