@@ -69,6 +69,13 @@ struct FusedArgs {
   uint32_t d_magic, g_magic;  // ceil(2^32 / D), ceil(2^32 / (D K / 4))
 };
 
+// Ledger input of one (env, stock) slot, written by the parallel lanes.
+struct __attribute__((aligned(16))) Slot {
+  int32_t k;   // wanted shares, signed
+  float val;   // sale proceeds (k < 0) or unit cost of a purchase (k > 0)
+  double rcp;  // 1 / unit cost in binary64 (k > 0), else 0
+};
+
 __device__ inline Row row_of(const EnvDims &d, int32_t tau, int32_t n) {
   const int32_t m = d.M == 1 ? 0 : n;
   Row r;
@@ -105,12 +112,10 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   float *s_cash = reinterpret_cast<float *>(s_row + E);
   int32_t *s_done = reinterpret_cast<int32_t *>(s_cash + E);  // episode-end flags of the step just taken
   // scratch in the hidden tile
-  int32_t *s_k = reinterpret_cast<int32_t *>(ldsH);        // wanted shares
-  float *s_val = reinterpret_cast<float *>(s_k + E * Dp);   // sale proceeds (k < 0) or unit cost (k > 0)
-  int32_t *s_q = reinterpret_cast<int32_t *>(s_val + E * Dp);  // executed shares, signed
+  Slot *s_slot = reinterpret_cast<Slot *>(ldsH);            // what the ledger needs per (env, stock), one 16-byte read
+  int32_t *s_q = reinterpret_cast<int32_t *>(s_slot + E * Dp);  // executed shares, signed
   float *s_pv = reinterpret_cast<float *>(s_q + E * Dp);    // valuation prices
   float *s_e2 = s_pv + E * Dp;                              // squared noise
-  double *s_rcp = reinterpret_cast<double *>(s_e2 + E * Dp);  // 1 / unit cost of a purchase, binary64
   // output-layer accumulators of the actor, one [E][32] plane per k part of that layer (summed in the pre-compute)
   constexpr int KS = (NKB2 > 0 && NKB2 % 4 == 0) ? 4 : 1;
   constexpr int MUP = 33;  // row pitch of a plane (lanes of one store differ in the row: 32 would hit one bank)
@@ -223,11 +228,11 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
         int32_t h = s_h[e * Dp + dd];
         if (AFTER_STEP) {
-          if (a.shares) a.shares[g0 + idx] = s_q[e * Dp + dd];
-          if (s_done[e]) {
-            h = 0;
-            s_h[e * Dp + dd] = 0;
-          }
+          // sales were booked when they were sized; purchases (q > 0) are booked here
+          const int32_t q = s_q[e * Dp + dd];
+          if (a.shares) a.shares[g0 + idx] = q;
+          h = s_done[e] ? 0 : h + max(q, 0);
+          s_h[e * Dp + dd] = h;
         }
         const float sv = (float)h * d.s_hold;
         __builtin_nontemporal_store(sv, &obs_row[(size_t)(n0 + e) * S + 1 + D + dd]);
@@ -351,9 +356,11 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
           val = p * d.one_plus_c;
           rcp = 1.0 / (double)val;
         }
-        s_k[o] = k;
-        s_val[o] = val;
-        s_rcp[o] = rcp;
+        Slot sl;
+        sl.k = k;
+        sl.val = val;
+        sl.rcp = rcp;
+        s_slot[o] = sl;
         s_q[o] = q;
         s_pv[o] = r_pv[i];
         s_e2[o] = eps * eps;
@@ -362,9 +369,11 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     if (tid_p < E)
       for (int dd = D; dd < DMAX; ++dd) {
         const int o = tid_p * Dp + dd;
-        s_k[o] = 0;
-        s_val[o] = 0.0f;
-        s_rcp[o] = 0.0;
+        Slot sl;
+        sl.k = 0;
+        sl.val = 0.0f;
+        sl.rcp = 0.0;
+        s_slot[o] = sl;
         s_q[o] = 0;
         s_pv[o] = 0.0f;
         s_e2[o] = 0.0f;
@@ -381,15 +390,11 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       constexpr int CH = 16;
 #pragma unroll
       for (int c0 = 0; c0 < DMAX; c0 += CH) {
-        int32_t kk[CH];
-        float vv[CH];
+        Slot sl[CH];
 #pragma unroll
-        for (int j = 0; j < CH; ++j) {
-          kk[j] = s_k[o0 + c0 + j];
-          vv[j] = s_val[o0 + c0 + j];
-        }
+        for (int j = 0; j < CH; ++j) sl[j] = s_slot[o0 + c0 + j];
 #pragma unroll
-        for (int j = 0; j < CH; ++j) cash = kk[j] < 0 ? cash + vv[j] : cash;
+        for (int j = 0; j < CH; ++j) cash = sl[j].k < 0 ? cash + sl[j].val : cash;
       }
       // Purchases in stock order, the rule of the reference in straight-line code:
       //   m = floor(cash / u); q = min(k, max(m, 0)); if (q u > cash) q -= 1; cash -= q u        (binary32)
@@ -401,47 +406,41 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       // (relative) away from every binary32 rounding boundary it does not hit exactly, so rounding the product
       // to binary32 gives the correctly rounded cash / u -- the same value as the division, in 3 dependent
       // operations instead of 11.
+      int32_t hn[DMAX];  // holdings after the trades (written back by the pass that emits them)
 #pragma unroll
       for (int c0 = 0; c0 < DMAX; c0 += CH) {
-        int32_t kk[CH], hh[CH], qq[CH];
-        float uu[CH];
-        double rr[CH];
+        Slot sl[CH];
+        int32_t hh[CH], qq[CH];
 #pragma unroll
         for (int j = 0; j < CH; ++j) {
-          kk[j] = s_k[o0 + c0 + j];
-          uu[j] = s_val[o0 + c0 + j];
-          rr[j] = s_rcp[o0 + c0 + j];
+          sl[j] = s_slot[o0 + c0 + j];
           hh[j] = s_h[o0 + c0 + j];
           qq[j] = s_q[o0 + c0 + j];
         }
 #pragma unroll
         for (int j = 0; j < CH; ++j) {
-          const bool buy = kk[j] > 0;
-          const int32_t k = max(kk[j], 0);  // sales and holds: k = 0 and reciprocal 0 give q = 0, outlay 0
-          const float u = uu[j];
-          const float ratio = (float)((double)cash * rr[j]);
+          const bool buy = sl[j].k > 0;
+          const int32_t k = max(sl[j].k, 0);  // sales and holds: k = 0 and reciprocal 0 give q = 0, outlay 0
+          const float u = sl[j].val;
+          const float ratio = (float)((double)cash * sl[j].rcp);
           const int32_t m = (int32_t)ratio;  // (toward zero: floor for ratio >= 0, and negatives end at 0 below)
           int32_t q = min(k, max(m, 0));
           const float out_q = (float)q * u, out_q1 = (float)(q - 1) * u;
           const bool over = buy && out_q > cash;
           q = over ? q - 1 : q;
           cash = cash - (over ? out_q1 : out_q);
-          s_h[o0 + c0 + j] = hh[j] + q;
+          hn[c0 + j] = hh[j] + q;
           s_q[o0 + c0 + j] = qq[j] + q;  // (a purchase slot held 0)
         }
       }
       double asset1 = (double)cash;
 #pragma unroll
       for (int c0 = 0; c0 < DMAX; c0 += CH) {
-        int32_t hh[CH];
         float pp[CH];
 #pragma unroll
-        for (int j = 0; j < CH; ++j) {
-          hh[j] = s_h[o0 + c0 + j];
-          pp[j] = s_pv[o0 + c0 + j];
-        }
+        for (int j = 0; j < CH; ++j) pp[j] = s_pv[o0 + c0 + j];
 #pragma unroll
-        for (int j = 0; j < CH; ++j) asset1 += (double)hh[j] * (double)pp[j];  // empty slots add +0
+        for (int j = 0; j < CH; ++j) asset1 += (double)hn[c0 + j] * (double)pp[j];  // empty slots add +0
       }
       const double r = (asset1 - asset) * (double)d.rho;
       asset = asset1;
