@@ -585,7 +585,7 @@ hipError_t launch_rollout_fused(hipStream_t st, const pr_config &c, const EnvDim
   // must mirror the carve-up at the top of the kernel
   size_t lds = (size_t)BM * a.hpitch + (size_t)BM * a.xpitch;
   if (with_actor) lds += (size_t)actor.nkb[2] * 1024 + (size_t)(actor.nct[0] + actor.nct[1] + actor.nct[2]) * 32 * 4;
-  lds += (size_t)2 * E * kDp * 4 + (size_t)E * (sizeof(Row) + sizeof(float));
+  lds += (size_t)2 * E * kDp * 4 + (size_t)E * (sizeof(Row) + sizeof(float) + sizeof(int32_t));
   if (lds > 160 * 1024) return hipErrorInvalidValue;
   const unsigned blocks = (unsigned)(d.N / E);
   const int cth = (c.hidden / 32) / NW;
