@@ -256,3 +256,28 @@ def leaderboard(n_agents: int, agent_of, ep_sum, ep_sqsum, ep_cnt):
     lib().orc_leaderboard(int(n_agents), C.c_int64(agent_of.size), _p(agent_of), _p(ep_sum), _p(ep_sqsum), _p(ep_cnt),
                           _p(mean), _p(var), _p(rank))
     return mean, var, rank
+
+
+def asset_curve(obs, done, n_stocks: int, obs_scale):
+    """Value curve of the first episode of every env, decoded from a recorded observation buffer."""
+    obs = np.ascontiguousarray(obs, dtype=np.float32)
+    done = np.ascontiguousarray(done, dtype=np.uint8)
+    T1, N, S = obs.shape
+    T = T1 - 1
+    assert done.shape == (T, N)
+    sc = np.ascontiguousarray(obs_scale, dtype=np.float32)
+    value = np.empty((T + 1, N), dtype=np.float64)
+    length = np.empty(N, dtype=np.int32)
+    lib().orc_asset_curve(int(T), C.c_int64(N), int(n_stocks), int(S), _p(obs), _p(done), _p(sc), _p(value), _p(length))
+    return value, length
+
+
+def metrics(value, length, periods_per_year: float, rf: float = 0.0):
+    """[6, N]: cumulative return, annual return, annual volatility, max drawdown, Sharpe, Calmar (Sec. 5.3)."""
+    value = np.ascontiguousarray(value, dtype=np.float64)
+    length = np.ascontiguousarray(length, dtype=np.int32)
+    T1, N = value.shape
+    out = np.empty((6, N), dtype=np.float64)
+    lib().orc_metrics(int(T1 - 1), C.c_int64(N), _p(value), _p(length), C.c_double(periods_per_year), C.c_double(rf),
+                      _p(out))
+    return out

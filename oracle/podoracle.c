@@ -30,7 +30,11 @@
  * cases, exact-rational brute force on a 1-env 2-stock 3-step grid; numpy
  * matmul + tanh for the MLP; library bf16 rounding and hand-built ties for
  * the bf16 emulation; closed forms and the O(T^2) direct sum for GAE; numpy
- * mean/var/stable argsort for the leaderboard.  The whole free-running rollout
+ * mean/var/stable argsort for the leaderboard; a hand-computed curve, geometric
+ * closed forms, numpy std / maximum.accumulate / prod and the rollout's own
+ * rewards for the trading metrics of Sec. 5.3 (whose annualisation period,
+ * risk-free rate and deviation estimator the paper leaves open: parameters and
+ * the sample estimator here).  The whole free-running rollout
  * has no printed trajectory in the paper to compare with: parity unpinned for
  * the composition, pinned stage by stage.
  */
@@ -414,4 +418,88 @@ void orc_leaderboard(int P, int64_t N, const int32_t *agent_of, const double *ep
   free(s1);
   free(s2);
   free(cnt);
+}
+
+/* ------------------------------------------------------- trading metrics -- */
+
+/* Account-value curve of each env decoded from a recorded observation buffer
+ * (state layout of Table 1: [cash, prices, holdings, indicators] times the
+ * power-of-two observation scales, which divide out exactly):
+ *   V_t = cash_t + sum_d h_{t,d} p_{t,d},  summed in stock order, binary64.
+ * The curve of env n covers the first episode in the buffer: t = 0 .. L_n with
+ * L_n = the first t whose done flag is set (obs[t+1] is then a reset
+ * observation and not part of the episode), or T when none is.
+ * obs [T+1, N, S], done [T, N]; value [T+1, N] (entries beyond L_n are 0), len [N]. */
+void orc_asset_curve(int T, int64_t N, int D, int S, const float *obs, const uint8_t *done, const float *obs_scale,
+                     double *value, int32_t *len) {
+  for (int64_t n = 0; n < N; ++n) {
+    int L = T;
+    for (int t = 0; t < T; ++t)
+      if (done[(int64_t)t * N + n]) {
+        L = t;
+        break;
+      }
+    len[n] = L;
+    for (int t = 0; t <= T; ++t) {
+      double v = 0.0;
+      if (t <= L) {
+        const float *o = obs + ((int64_t)t * N + n) * S;
+        v = (double)o[0] / (double)obs_scale[0];
+        for (int d = 0; d < D; ++d)
+          v += ((double)o[1 + D + d] / (double)obs_scale[2]) * ((double)o[1 + d] / (double)obs_scale[1]);
+      }
+      value[(int64_t)t * N + n] = v;
+    }
+  }
+}
+
+/* The five trading-performance figures of Sec. 5.3 ("Performance metrics") for one value curve V_0 .. V_L,
+ * with P periods per year and an annual risk-free rate rf; per-period simple returns r_t = V_{t+1} / V_t - 1:
+ *   out[0] cumulative return   (V_L - V_0) / V_0
+ *   out[1] annual return       (V_L / V_0)^(P / L) - 1                      (geometric average, yearly)
+ *   out[2] annual volatility   sqrt(P) * sample standard deviation of r     (0 when L < 2)
+ *   out[3] maximum drawdown    max_t (1 - V_t / max_{s <= t} V_s)           (>= 0)
+ *   out[4] Sharpe ratio        sqrt(P) * (mean(r) - rf / P) / std(r)        (0 when std(r) = 0)
+ *   out[5] Calmar ratio        annual return / maximum drawdown             (0 when the drawdown is 0)
+ * L = 0 (no step observed) gives all zeros. */
+void orc_metrics_curve(int L, const double *V, double periods_per_year, double rf, double *out) {
+  for (int i = 0; i < 6; ++i) out[i] = 0.0;
+  if (L < 1) return;
+  out[0] = (V[L] - V[0]) / V[0];
+  out[1] = pow(V[L] / V[0], periods_per_year / (double)L) - 1.0;
+  double mean = 0.0;
+  for (int t = 0; t < L; ++t) mean += V[t + 1] / V[t] - 1.0;
+  mean /= (double)L;
+  double sd = 0.0;
+  if (L >= 2) {
+    double ss = 0.0;
+    for (int t = 0; t < L; ++t) {
+      const double dv = (V[t + 1] / V[t] - 1.0) - mean;
+      ss += dv * dv;
+    }
+    sd = sqrt(ss / (double)(L - 1));
+  }
+  out[2] = sqrt(periods_per_year) * sd;
+  double peak = V[0], mdd = 0.0;
+  for (int t = 0; t <= L; ++t) {
+    if (V[t] > peak) peak = V[t];
+    const double dd = 1.0 - V[t] / peak;
+    if (dd > mdd) mdd = dd;
+  }
+  out[3] = mdd;
+  out[4] = sd > 0.0 ? sqrt(periods_per_year) * (mean - rf / periods_per_year) / sd : 0.0;
+  out[5] = mdd > 0.0 ? out[1] / mdd : 0.0;
+}
+
+/* All envs: metrics [6, N] from value [T+1, N] and len [N] (as written by orc_asset_curve). */
+void orc_metrics(int T, int64_t N, const double *value, const int32_t *len, double periods_per_year, double rf,
+                 double *metrics) {
+  double *V = (double *)malloc((size_t)(T + 1) * sizeof(double));
+  for (int64_t n = 0; n < N; ++n) {
+    for (int t = 0; t <= T; ++t) V[t] = value[(int64_t)t * N + n];
+    double out[6];
+    orc_metrics_curve(len[n], V, periods_per_year, rf, out);
+    for (int i = 0; i < 6; ++i) metrics[(int64_t)i * N + n] = out[i];
+  }
+  free(V);
 }

@@ -1,0 +1,120 @@
+"""Pins of the CPU checker's trading metrics (Sec. 5.3, "Performance metrics") and of the value curve it
+decodes from an observation record: closed forms, a hand-computed example, library routines, invariants."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2112_05923_amd import inputs
+
+P = 252.0
+
+
+def _m(V, L=None, periods=P, rf=0.0):
+    V = np.asarray(V, np.float64).reshape(-1, 1)
+    L = V.shape[0] - 1 if L is None else L
+    return oracle.metrics(V, np.array([L], np.int32), periods, rf)[:, 0]
+
+
+def test_hand_computed_example():
+    # returns +10 %, -10 %, +10 %, -10 %
+    V = [100.0, 110.0, 99.0, 108.9, 98.01]
+    cum, ar, vol, mdd, sharpe, calmar = _m(V, periods=4.0)
+    assert cum == pytest.approx(-0.0199, abs=1e-12)
+    assert ar == pytest.approx(0.9801 ** (4.0 / 4.0) - 1.0, abs=1e-12)
+    assert vol == pytest.approx(2.0 * np.sqrt(0.04 / 3.0), rel=1e-12)      # sample deviation, sqrt(P) = 2
+    assert mdd == pytest.approx(1.0 - 98.01 / 110.0, rel=1e-12)            # trough 98.01 after the peak 110
+    assert sharpe == pytest.approx(0.0, abs=1e-9)
+    assert calmar == pytest.approx(-0.0199 / (1.0 - 98.01 / 110.0), rel=1e-10)
+    # a risk-free rate of 5 % a year is 1.25 % per period here
+    assert _m(V, periods=4.0, rf=0.05)[4] == pytest.approx(2.0 * (0.0 - 0.0125) / np.sqrt(0.04 / 3.0), rel=1e-9)
+
+
+@pytest.mark.parametrize("g", [1.0007, 0.9991])
+def test_geometric_curve_closed_forms(g):
+    L = 300
+    V = 5e5 * g ** np.arange(L + 1)
+    cum, ar, vol, mdd, sharpe, calmar = _m(V)
+    assert cum == pytest.approx(g ** L - 1.0, rel=1e-9)
+    assert ar == pytest.approx(g ** P - 1.0, rel=1e-9)
+    assert vol == pytest.approx(0.0, abs=1e-9)
+    if g > 1.0:
+        assert mdd == 0.0 and calmar == 0.0
+    else:
+        assert mdd == pytest.approx(1.0 - g ** L, rel=1e-9)
+        assert calmar == pytest.approx((g ** P - 1.0) / (1.0 - g ** L), rel=1e-8)
+
+
+def test_against_library_routines_on_random_curves():
+    rng = np.random.default_rng(11)
+    T, N = 257, 9
+    r = rng.normal(2e-4, 1e-2, size=(T, N))
+    V = 1e6 * np.vstack([np.ones((1, N)), np.cumprod(1.0 + r, axis=0)])
+    L = rng.integers(2, T + 1, size=N).astype(np.int32)
+    got = oracle.metrics(V, L, P, 0.03)
+    for n in range(N):
+        v = V[: L[n] + 1, n]
+        rr = np.diff(v) / v[:-1]
+        want_mdd = float(np.max(1.0 - v / np.maximum.accumulate(v)))
+        want_ar = float(np.prod(1.0 + rr) ** (P / L[n]) - 1.0)
+        assert got[0, n] == pytest.approx(np.prod(1.0 + rr) - 1.0, rel=1e-9)
+        assert got[1, n] == pytest.approx(want_ar, rel=1e-9)
+        assert got[2, n] == pytest.approx(np.sqrt(P) * np.std(rr, ddof=1), rel=1e-9)
+        assert got[3, n] == pytest.approx(want_mdd, rel=1e-9)
+        assert got[4, n] == pytest.approx(np.sqrt(P) * (np.mean(rr) - 0.03 / P) / np.std(rr, ddof=1), rel=1e-8)
+        assert got[5, n] == pytest.approx(want_ar / want_mdd, rel=1e-8)
+
+
+def test_invariants_and_degenerate_lengths():
+    rng = np.random.default_rng(3)
+    V = 1e6 * np.cumprod(1.0 + rng.normal(0, 0.02, size=64))
+    a, b = _m(V), _m(37.5 * V)
+    np.testing.assert_allclose(a, b, rtol=1e-10, atol=1e-12)          # the unit of account does not matter
+    assert 0.0 <= a[3] < 1.0
+    # only the first L + 1 values count
+    np.testing.assert_array_equal(_m(V, L=20), _m(np.concatenate([V[:21], 1e9 * np.ones(43)]), L=20))
+    assert np.all(_m(V, L=0) == 0.0)
+    one = _m([100.0, 90.0], L=1)
+    assert one[0] == pytest.approx(-0.1) and one[2] == 0.0 and one[3] == pytest.approx(0.1) and one[4] == 0.0
+    # two returns tell the sample deviation from the population one: +10 %, -10 % -> 0.1 sqrt(2)
+    two = _m([100.0, 110.0, 99.0], periods=1.0)
+    assert two[2] == pytest.approx(0.1 * np.sqrt(2.0), rel=1e-12)
+    # a drawdown is measured from the running peak, not from the start or the global maximum that follows it
+    assert _m([100.0, 50.0, 200.0, 150.0])[3] == pytest.approx(0.5)
+
+
+def test_value_curve_decodes_the_observation_record():
+    rng = np.random.default_rng(5)
+    T, N, D, K = 6, 5, 3, 2
+    S = 1 + 2 * D + D * K
+    sc = np.array([2.0 ** -20, 2.0 ** -7, 2.0 ** -10, 1.0], np.float32)
+    cash = rng.uniform(0, 1e6, size=(T + 1, N)).astype(np.float32)
+    price = rng.uniform(10, 100, size=(T + 1, N, D)).astype(np.float32)
+    hold = rng.integers(0, 500, size=(T + 1, N, D)).astype(np.float32)
+    obs = rng.standard_normal((T + 1, N, S)).astype(np.float32)
+    obs[:, :, 0] = cash * sc[0]
+    obs[:, :, 1:1 + D] = price * sc[1]
+    obs[:, :, 1 + D:1 + 2 * D] = hold * sc[2]
+    done = np.zeros((T, N), np.uint8)
+    done[2, 1] = 1          # env 1: episode ends with step 2, obs[3] is a reset observation
+    done[4, 1] = 1          # (a later end does not matter)
+    done[T - 1, 3] = 1      # env 3: ends with the last step
+    done[0, 4] = 1          # env 4: ends at once
+    V, L = oracle.asset_curve(obs, done, D, sc)
+    assert L.tolist() == [T, 2, T, T - 1, 0]
+    want = cash.astype(np.float64) + (hold.astype(np.float64) * price.astype(np.float64)).sum(-1)
+    for n in range(N):
+        np.testing.assert_allclose(V[: L[n] + 1, n], want[: L[n] + 1, n], rtol=1e-15)
+        assert np.all(V[L[n] + 1:, n] == 0.0)
+
+
+def test_value_curve_agrees_with_the_rewards_of_the_rollout():
+    """Along an episode the recorded reward is rho times the change of the decoded value (Table 1)."""
+    w = inputs.WORKLOADS["tiny"].replace(n_envs=8, steps=24)
+    d = inputs.make_all(w)
+    cfg = oracle.cfg_from_workload(w, horizon=10)
+    out, _ = oracle.rollout(cfg, w.hidden, bool(w.mlp_dtype), w.steps, d["price"][:11], d["ind"][:11], d["noise"],
+                            actor=d["actor"], critic=d["critic"], want=("obs", "reward", "done"))
+    V, L = oracle.asset_curve(out["obs"], out["done"], w.n_stocks, w.obs_scale)
+    assert np.all(L == 9)                      # the step that reaches the horizon carries the flag
+    dv = (V[1:10] - V[:9]) * w.reward_scale
+    np.testing.assert_allclose(dv, out["reward"][:9], rtol=1e-5, atol=1e-7)
