@@ -155,6 +155,16 @@ def main():
         torch.mul(src, 1.0, out=dst)  # one vectorised elementwise kernel: reads and writes copy_calibration MiB
         torch.cuda.synchronize()
 
+    # outside the timed region: the evaluator's trading figures over the record just produced
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    pr.trading_metrics(out["obs"], out["done"], D, w.obs_scale, 252.0 * 390.0)
+    e0.record()
+    for _ in range(3):
+        pr.trading_metrics(out["obs"], out["done"], D, w.obs_scale, 252.0 * 390.0)
+    e1.record()
+    torch.cuda.synchronize()
+    t_metrics = e0.elapsed_time(e1) / 3
+
     ms = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in events) / args.steps
     t_roll, t_critic, t_gae = ms(0, 1), ms(1, 2), ms(2, 3)
     env_steps = N * T
@@ -191,6 +201,8 @@ def main():
                    "env_steps_per_step": env_steps},
         "roofline": dom,
         "stages": stages,
+        "extras": {"trading_metrics": {"ms": t_metrics, "note": "not part of value; reads 4(1+2D) of every 4S-byte row",
+                                       "GBps": (4 * (1 + 2 * D) + 1) * (T + 1) * N / t_metrics / 1e6}},
     }
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)

@@ -176,6 +176,26 @@ int rollout_set_state(pr_handle *h, const pr_state *in);
 int compute_gae(void *hip_stream, int32_t T, int32_t N, const float *reward, const float *value, const uint8_t *done,
                 float gamma, float lambda, float *adv, float *ret);
 
+/* Trading performance of a recorded rollout (Sec. 5.3 "Performance metrics"; the evaluator of Sec. 4.2 reports
+ * it next to the episodic reward), per env, over the FIRST episode in the buffer: points t = 0 .. L with L the
+ * first step whose done flag is set (the observation after it is a reset observation), else T.  The account value
+ *   V_t = cash_t + sum_d holdings_{t,d} price_{t,d}
+ * is decoded from obs (layout and scales as rollout_step_T writes them) in binary64; r_t = V_{t+1} / V_t - 1.
+ *   metrics[0][n] cumulative return  (V_L - V_0) / V_0
+ *   metrics[1][n] annual return      (V_L / V_0)^(periods_per_year / L) - 1
+ *   metrics[2][n] annual volatility  sqrt(periods_per_year) * sample standard deviation of r   (0 when L < 2)
+ *   metrics[3][n] maximum drawdown   max_t (1 - V_t / max_{s <= t} V_s)
+ *   metrics[4][n] Sharpe ratio       sqrt(periods_per_year) (mean(r) - risk_free / periods_per_year) / std(r), 0 if std = 0
+ *   metrics[5][n] Calmar ratio       annual return / maximum drawdown, 0 if the drawdown is 0
+ * (the paper names the five figures in words; periods per year, the risk-free rate and the sample estimator are
+ * this library's parameters / reading).  L = 0 gives zeros.
+ * Stateless.  Device pointers: obs [T+1, N, state_dim], done [T, N], metrics [6, N] (binary64, output),
+ * length [N] (output L, may be NULL).  obs_scale: HOST pointer to the 4 scales of pr_config (powers of two).
+ * state_dim >= 1 + 2 n_stocks.  Only enqueues on hip_stream; PR_EINVAL on bad arguments. */
+int trading_metrics(void *hip_stream, int32_t T, int32_t N, int32_t n_stocks, int32_t state_dim, const float *obs,
+                    const uint8_t *done, const float *obs_scale, double periods_per_year, double risk_free,
+                    double *metrics, int32_t *length);
+
 /* Leaderboard score of every agent (Sec. 4.1; Sec. 4.2 evaluator): mean and
  * population variance of the returns of the episodes its envs have finished
  * since the last reset, and the agents ordered best first (equal means: lower

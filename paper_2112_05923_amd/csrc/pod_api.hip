@@ -341,6 +341,20 @@ int compute_gae(void *hip_stream, int32_t T, int32_t N, const float *reward, con
   return PR_OK;
 }
 
+int trading_metrics(void *hip_stream, int32_t T, int32_t N, int32_t n_stocks, int32_t state_dim, const float *obs,
+                    const uint8_t *done, const float *obs_scale, double periods_per_year, double risk_free,
+                    double *metrics, int32_t *length) {
+  if (T < 1 || N < 1 || n_stocks < 1 || !obs || !done || !obs_scale || !metrics) return PR_EINVAL;
+  if (state_dim < 1 + 2 * n_stocks) return PR_EINVAL;
+  if (!(periods_per_year > 0.0) || !isfinite(periods_per_year) || !isfinite(risk_free)) return PR_EINVAL;
+  for (int i = 0; i < 3; ++i)
+    if (!is_pow2_float(obs_scale[i])) return PR_EINVAL;
+  if (((double)T + 1.0) * (double)N * (double)state_dim >= 9.0e18) return PR_EINVAL;
+  POD_HIP(launch_trading_metrics(static_cast<hipStream_t>(hip_stream), T, N, n_stocks, state_dim, obs, done, obs_scale,
+                                 periods_per_year, risk_free, metrics, length));
+  return PR_OK;
+}
+
 int rollout_leaderboard(pr_handle *h, double *score_mean, double *score_var, int32_t *rank) {
   if (!h || !score_mean || !score_var || !rank) return PR_EINVAL;
   POD_HIP(launch_leaderboard(h->stream, h->cfg.n_envs, h->cfg.n_agents, h->st, nullptr, score_mean, score_var, rank));

@@ -22,7 +22,7 @@ PR_NET_ACTOR, PR_NET_CRITIC = 0, 1
 
 EXPORTS = ["rollout_workspace_bytes", "rollout_init", "rollout_set_weights", "rollout_reset", "rollout_step_T",
            "rollout_step_forced", "rollout_mlp_forward", "rollout_get_state", "rollout_set_state", "compute_gae",
-           "rollout_leaderboard", "rollout_destroy", "rollout_strerror", "rollout_last_hip_error"]
+           "trading_metrics", "rollout_leaderboard", "rollout_destroy", "rollout_strerror", "rollout_last_hip_error"]
 
 
 class PrConfig(C.Structure):
@@ -84,6 +84,8 @@ def lib():
         l.rollout_set_state.argtypes = [C.c_void_p, C.POINTER(PrState)]
         l.compute_gae.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float,
                                   C.c_float, C.c_void_p, C.c_void_p]
+        l.trading_metrics.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                      C.POINTER(C.c_float), C.c_double, C.c_double, C.c_void_p, C.c_void_p]
         l.rollout_leaderboard.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         l.rollout_destroy.argtypes = [C.c_void_p]
         _lib = l
@@ -281,3 +283,22 @@ def compute_gae(reward: torch.Tensor, value: torch.Tensor, done: torch.Tensor, g
                              gamma, lam, _dev(adv, torch.float32, (T, N), "adv"),
                              _dev(ret, torch.float32, (T, N), "ret")), "compute_gae")
     return adv, ret
+
+
+METRICS = ("cumulative_return", "annual_return", "annual_volatility", "max_drawdown", "sharpe", "calmar")
+
+
+def trading_metrics(obs: torch.Tensor, done: torch.Tensor, n_stocks: int, obs_scale, periods_per_year: float,
+                    risk_free: float = 0.0):
+    """obs [T+1, N, S], done [T, N] of a recorded rollout -> (metrics [6, N] float64 in the order of METRICS,
+    length [N] int32) for the first episode of every env."""
+    T1, N, S = obs.shape
+    T = T1 - 1
+    out = torch.empty((6, N), dtype=torch.float64, device=obs.device)
+    length = torch.empty((N,), dtype=torch.int32, device=obs.device)
+    sc = (C.c_float * 4)(*[float(x) for x in obs_scale])
+    _check(lib().trading_metrics(_stream_ptr(), T, N, int(n_stocks), S, _dev(obs, torch.float32, (T1, N, S), "obs"),
+                                 _dev(done, torch.uint8, (T, N), "done"), sc, float(periods_per_year),
+                                 float(risk_free), _dev(out, torch.float64, (6, N), "metrics"),
+                                 _dev(length, torch.int32, (N,), "length")), "trading_metrics")
+    return out, length

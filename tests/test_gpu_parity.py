@@ -406,3 +406,67 @@ def test_fused_rollout_stagewise_against_checker_and_carry_across_calls():
     rec["obs"] = np.concatenate([ra["obs"], rb["obs"][1:]])
     rec["value"] = np.concatenate([ra["value"], rb["value"][1:]])
     _stagewise(w, d, ro, ocfg, T, rec)
+
+
+# ------------------------------------------------ trading metrics (evaluator)
+
+def _check_metrics(obs, done, D, scales, periods, rf):
+    got, length = pr.trading_metrics(obs, done, D, scales, periods, rf)
+    torch.cuda.synchronize()
+    V, L = oracle.asset_curve(parity.to_np(obs), parity.to_np(done), D, scales)
+    want = oracle.metrics(V, L, periods, rf)
+    got, length = parity.to_np(got), parity.to_np(length)
+    assert np.array_equal(length, L)
+    # value curve and drawdown involve no reordering; the moments are merged pairwise instead of summed in two passes
+    for i, tol in enumerate((1e-12, 1e-11, 1e-8, 1e-12, 1e-8, 1e-10)):
+        np.testing.assert_allclose(got[i], want[i], rtol=tol, atol=1e-13, err_msg=pr.METRICS[i])
+    return got, length
+
+
+@pytest.mark.parametrize("T,N,D,S", [(1000, 200, 3, 16), (5, 70, 2, 5), (130, 64, 30, 301)])
+def test_trading_metrics_on_synthetic_records(T, N, D, S):
+    rng = np.random.default_rng(T + N)
+    sc = np.array([2.0 ** -20, 2.0 ** -7, 2.0 ** -10, 1.0], np.float32)
+    obs = rng.standard_normal((T + 1, N, S)).astype(np.float32)
+    cash = rng.uniform(1e3, 1e6, size=(T + 1, N)).astype(np.float32)
+    price = (50.0 * np.exp(np.cumsum(rng.normal(0, 0.01, size=(T + 1, N, D)), axis=0))).astype(np.float32)
+    hold = rng.integers(0, 300, size=(T + 1, N, D)).astype(np.float32)
+    obs[:, :, 0] = cash * sc[0]
+    obs[:, :, 1:1 + D] = price * sc[1]
+    obs[:, :, 1 + D:1 + 2 * D] = hold * sc[2]
+    done = (rng.random((T, N)) < 2.0 / T).astype(np.uint8)
+    done[:, 0] = 0                 # one env runs through
+    done[0, 1] = 1                 # one ends at once (no return observed)
+    done[:, 2] = 0
+    done[1, 2] = 1                 # one has exactly two points ... and one return
+    done[:, 3] = 0
+    done[T - 1, 3] = 1             # one ends with the last step
+    got, length = _check_metrics(torch.from_numpy(obs).to(DEV), torch.from_numpy(done).to(DEV), D, sc, 252.0, 0.02)
+    assert length[0] == T and length[1] == 0 and length[2] == 1 and length[3] == T - 1
+    assert np.all(got[:, 1] == 0.0) and got[2, 2] == 0.0
+
+
+def test_deterministic_evaluation_rollout_and_its_metrics():
+    """The evaluator's pass (Sec. 4.2): the policy mean is the action (zero noise), one episode per env, the
+    episodic-return statistics from the leaderboard reduction and the trading figures from the record."""
+    T, H = 48, 40
+    w = inputs.WORKLOADS["large"].replace(n_envs=128, steps=T)
+    d, ro, ocfg = _make(w, horizon=H, steps=T, schedule=FUSED)
+    out = ro.alloc_buffers(T, value=False, logp=True, mu=True, shares=False)
+    ro.step_T(T, torch.zeros((T, w.n_envs, w.n_stocks), device=DEV), out)
+    torch.cuda.synchronize()
+    assert torch.equal(out["act_raw"], out["mu"])
+    got, length = _check_metrics(out["obs"], out["done"], w.n_stocks, w.obs_scale, 252.0 * 390.0, 0.0)
+    assert np.all(length == H - 1)
+    # the first episode's return, booked by the rollout, is rho times the change of value up to the terminal
+    # valuation; the record's curve ends one step earlier, so the two agree up to that last step's reward
+    mean, var, rank = ro.leaderboard()
+    st = ro.get_state()
+    torch.cuda.synchronize()
+    ep = parity.to_np(st["ep_sum"])
+    V, L = oracle.asset_curve(parity.to_np(out["obs"]), parity.to_np(out["done"]), w.n_stocks, w.obs_scale)
+    r = parity.to_np(out["reward"]).astype(np.float64)
+    want_ep = (V[H - 1] - V[0]) * w.reward_scale + r[H - 1]
+    np.testing.assert_allclose(ep, want_ep, rtol=1e-5, atol=1e-6)
+    assert float(parity.to_np(mean)[0]) == pytest.approx(float(ep.mean()), rel=1e-12)
+    assert np.all(got[3] >= 0.0) and np.all(got[3] < 1.0)
