@@ -470,3 +470,44 @@ def test_deterministic_evaluation_rollout_and_its_metrics():
     np.testing.assert_allclose(ep, want_ep, rtol=1e-5, atol=1e-6)
     assert float(parity.to_np(mean)[0]) == pytest.approx(float(ep.mean()), rel=1e-12)
     assert np.all(got[3] >= 0.0) and np.all(got[3] < 1.0)
+
+
+# ------------------------------------------ full size, as the benchmark runs it
+
+def test_full_size_large_workload_in_the_benchmarked_configuration():
+    """The `large` workload at its real size through the three calls bench.py times (persistent rollout kernel,
+    128-row value kernel over the whole buffer, GAE), checked on sampled envs that the checker replays step by
+    step, plus properties that hold for every env."""
+    w = inputs.WORKLOADS["large"]
+    T, N, D, S = w.steps, w.n_envs, w.n_stocks, w.state_dim
+    d = inputs.make_all_device(w, DEV)
+    ro = pr.Rollout(pr.make_config(w, schedule=FUSED), d["price"], d["ind"], d["actor"], d["critic"])
+    out = ro.alloc_buffers(T, value=True, logp=True, mu=True, shares=True)
+    ro.step_T(T, d["noise"], out)
+    adv, ret = pr.compute_gae(out["reward"], out["value"], out["done"], w.gamma, w.lam)
+    st = ro.get_state()
+    torch.cuda.synchronize()
+    # every env: one episode finished exactly at the last step, state reset, everything finite
+    assert int(out["done"][:-1].sum()) == 0 and int(out["done"][-1].sum()) == N
+    assert int(st["ep_count"].sum()) == N and int(st["cursor"].sum()) == 0 and float(st["cash"].min()) == w.cash0
+    for k in ("reward", "value", "logp"):
+        assert bool(torch.isfinite(out[k]).all()), k
+    assert bool(torch.isfinite(adv).all()) and bool(torch.isfinite(ret).all())
+    # sampled envs: first / last lanes of the first, a middle and the last 64-env tile, and a few random ones
+    rng = np.random.default_rng(2112)
+    idx = np.unique(np.concatenate([[0, 63, 64, 8191, 8192, N - 64, N - 1], rng.integers(0, N, 9)]))
+    ti = torch.from_numpy(idx).to(DEV)
+    take = lambda x: parity.to_np(x.index_select(1, ti))
+    rec = {k: take(out[k]) for k in ("obs", "act_raw", "reward", "done", "logp", "mu", "shares", "value")}
+    ws = w.replace(n_envs=idx.size)
+    ocfg = oracle.cfg_from_workload(ws)
+    price, ind, noise = take(d["price"]), take(d["ind"]), take(d["noise"])
+    host = {k: {kk: parity.to_np(vv) for kk, vv in d[k].items()} for k in ("actor", "critic")}
+    chk, ost = parity.check_env_record(ws, ocfg, rec, price, ind, noise, rec["mu"])
+    assert np.array_equal(parity.to_np(st["ep_sum"])[idx] != 0.0, ost.ep_sum != 0.0)
+    np.testing.assert_allclose(parity.to_np(st["ep_sum"])[idx], ost.ep_sum, rtol=1e-9, atol=1e-9)
+    ts = np.concatenate([[0, 1, T - 1], rng.integers(0, T, 21)])
+    parity.check_networks(ws, host["actor"], host["critic"], rec["obs"][ts].reshape(-1, S),
+                          rec["mu"][ts].reshape(-1, D), rec["value"][ts].reshape(-1))
+    parity.check_networks(ws, host["actor"], host["critic"], rec["obs"][T], None, rec["value"][T])
+    parity.check_gae(rec["reward"], rec["value"], rec["done"], w.gamma, w.lam, take(adv), take(ret))
