@@ -111,8 +111,11 @@ def check_env_sites(w, rec_sites):
         if sel.size == 0:
             continue
         # compact 3-row market per site: row 0 = the path's first row, row 1 = execution row, row 2 = valuation row
-        price = np.stack([rec_sites["p0"][sel], rec_sites["p_now"][sel], rec_sites["p_val"][sel]]).astype(np.float32)
-        ind = np.stack([rec_sites["i0"][sel], rec_sites["i_now"][sel], rec_sites["i_val"][sel]]).astype(np.float32)
+        # (a fourth row that the single step never reads keeps the table as long as the not-done horizon asks)
+        price = np.stack([rec_sites["p0"][sel], rec_sites["p_now"][sel], rec_sites["p_val"][sel],
+                          rec_sites["p_val"][sel]]).astype(np.float32)
+        ind = np.stack([rec_sites["i0"][sel], rec_sites["i_now"][sel], rec_sites["i_val"][sel],
+                        rec_sites["i_val"][sel]]).astype(np.float32)
         cfg = oracle.cfg_from_workload(w, horizon=2 if is_done else 3)
         st = oracle.State(cfg, sel.size)
         st.cash[:] = cash[sel]

@@ -474,14 +474,18 @@ def test_deterministic_evaluation_rollout_and_its_metrics():
 
 # ------------------------------------------ full size, as the benchmark runs it
 
-def test_full_size_large_workload_in_the_benchmarked_configuration():
-    """The `large` workload at its real size through the three calls bench.py times (persistent rollout kernel,
-    128-row value kernel over the whole buffer, GAE), checked on sampled envs that the checker replays step by
-    step, plus properties that hold for every env."""
-    w = inputs.WORKLOADS["large"]
+@pytest.mark.parametrize("name,schedule,n_sample", [("large", FUSED, 256), ("dow30", pr.PR_SCHED_STEPWISE, 64),
+                                                     ("wide", pr.PR_SCHED_STEPWISE, 24),
+                                                     ("tournament", pr.PR_SCHED_STEPWISE, 96)])
+def test_full_size_workloads(name, schedule, n_sample):
+    """Every named workload at its real size through rollout_step_T (with values) and compute_gae -- `large` in
+    the configuration bench.py times (persistent rollout kernel, 128-row value kernel over the whole buffer) --
+    checked on sampled envs that the checker replays step by step, on all envs at a few steps, and through
+    properties that hold for every env."""
+    w = inputs.WORKLOADS[name]
     T, N, D, S = w.steps, w.n_envs, w.n_stocks, w.state_dim
     d = inputs.make_all_device(w, DEV)
-    ro = pr.Rollout(pr.make_config(w, schedule=FUSED), d["price"], d["ind"], d["actor"], d["critic"])
+    ro = pr.Rollout(pr.make_config(w, schedule=schedule), d["price"], d["ind"], d["actor"], d["critic"])
     out = ro.alloc_buffers(T, value=True, logp=True, mu=True, shares=True)
     ro.step_T(T, d["noise"], out)
     adv, ret = pr.compute_gae(out["reward"], out["value"], out["done"], w.gamma, w.lam)
@@ -493,21 +497,44 @@ def test_full_size_large_workload_in_the_benchmarked_configuration():
     for k in ("reward", "value", "logp"):
         assert bool(torch.isfinite(out[k]).all()), k
     assert bool(torch.isfinite(adv).all()) and bool(torch.isfinite(ret).all())
-    # sampled envs: first / last lanes of the first, a middle and the last 64-env tile, and a few random ones
+    # sampled envs: first / last lanes of the first, a middle and the last 64-env tile, and random ones
     rng = np.random.default_rng(2112)
-    idx = np.unique(np.concatenate([[0, 63, 64, 8191, 8192, N - 64, N - 1], rng.integers(0, N, 9)]))
+    idx = np.unique(np.concatenate([[0, 63, 64, N // 2 - 1, N // 2, N - 64, N - 1], rng.integers(0, N, n_sample)]))
     ti = torch.from_numpy(idx).to(DEV)
     take = lambda x: parity.to_np(x.index_select(1, ti))
     rec = {k: take(out[k]) for k in ("obs", "act_raw", "reward", "done", "logp", "mu", "shares", "value")}
-    ws = w.replace(n_envs=idx.size)
+    ws = w.replace(n_envs=idx.size, n_agents=1)
     ocfg = oracle.cfg_from_workload(ws)
     price, ind, noise = take(d["price"]), take(d["ind"]), take(d["noise"])
     host = {k: {kk: parity.to_np(vv) for kk, vv in d[k].items()} for k in ("actor", "critic")}
     chk, ost = parity.check_env_record(ws, ocfg, rec, price, ind, noise, rec["mu"])
-    assert np.array_equal(parity.to_np(st["ep_sum"])[idx] != 0.0, ost.ep_sum != 0.0)
     np.testing.assert_allclose(parity.to_np(st["ep_sum"])[idx], ost.ep_sum, rtol=1e-9, atol=1e-9)
-    ts = np.concatenate([[0, 1, T - 1], rng.integers(0, T, 21)])
-    parity.check_networks(ws, host["actor"], host["critic"], rec["obs"][ts].reshape(-1, S),
-                          rec["mu"][ts].reshape(-1, D), rec["value"][ts].reshape(-1))
-    parity.check_networks(ws, host["actor"], host["critic"], rec["obs"][T], None, rec["value"][T])
+    ts = np.concatenate([[0, 1, T - 1], rng.integers(0, T, 9)])
+    agent = idx // (N // w.n_agents)
+    for g in np.unique(agent)[:6]:
+        sel = agent == g
+        parity.check_networks(ws, host["actor"], host["critic"], rec["obs"][ts][:, sel].reshape(-1, S),
+                              rec["mu"][ts][:, sel].reshape(-1, D), rec["value"][ts][:, sel].reshape(-1), agent=int(g))
+        parity.check_networks(ws, host["actor"], host["critic"], rec["obs"][T][sel], None, rec["value"][T][sel],
+                              agent=int(g))
     parity.check_gae(rec["reward"], rec["value"], rec["done"], w.gamma, w.lam, take(adv), take(ret))
+    # every env at a few steps: one-step replays from the state decoded out of the recorded observation
+    for t in (0, T // 2, T - 1):
+        g = lambda x, r=t: parity.to_np(x[r])
+        sites = {"obs": g(out["obs"]), "obs_next": g(out["obs"], t + 1), "mu": g(out["mu"]), "noise": g(d["noise"]),
+                 "act_raw": g(out["act_raw"]), "shares": g(out["shares"]), "reward": g(out["reward"]),
+                 "done": g(out["done"]), "tau": np.full(N, t, np.int32), "horizon": T,
+                 "p0": g(d["price"], 0), "i0": g(d["ind"], 0), "p_now": g(d["price"]), "i_now": g(d["ind"]),
+                 "p_val": g(d["price"], t + 1), "i_val": g(d["ind"], t + 1)}
+        assert parity.check_env_sites(w, sites) == N
+    if w.n_agents > 1:
+        mean, var, rank = ro.leaderboard()
+        torch.cuda.synchronize()
+        per = N // w.n_agents
+        want = oracle.leaderboard(w.n_agents, np.arange(N) // per, parity.to_np(st["ep_sum"]),
+                                  parity.to_np(st["ep_sqsum"]), parity.to_np(st["ep_count"]))
+        np.testing.assert_allclose(parity.to_np(mean), want[0], rtol=1e-12)
+        np.testing.assert_allclose(parity.to_np(var), want[1], rtol=1e-9, atol=1e-12)
+        assert np.array_equal(parity.to_np(rank), want[2])
+    del out, d, ro
+    torch.cuda.empty_cache()
