@@ -81,9 +81,16 @@ def cpu_baseline(w, n_envs: int, steps: int, threads: int):
     with cf.ThreadPoolExecutor(max_workers=threads) as ex:
         done = sum(ex.map(work, chunks))
     dt = time.perf_counter() - t0
+    # the same code on one core, on a smaller slice of the same sample
+    one = np.arange(max(1, n_envs // threads))
+    t1 = time.perf_counter()
+    work(one)
+    dt1 = time.perf_counter() - t1
     return {"value": done * steps / dt, "unit": "env-steps/s", "cores": threads, "kind": "oracle",
             "sample": f"{n_envs} envs x {steps} steps of workload '{w.name}' (free-running rollout + critic + GAE), "
-                      f"{dt:.1f} s wall"}
+                      f"{dt:.1f} s wall",
+            "one_core": {"value": one.size * steps / dt1, "unit": "env-steps/s",
+                         "sample": f"{one.size} envs x {steps} steps, {dt1:.1f} s wall"}}
 
 
 def main():
