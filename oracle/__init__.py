@@ -281,3 +281,15 @@ def metrics(value, length, periods_per_year: float, rf: float = 0.0):
     lib().orc_metrics(int(T1 - 1), C.c_int64(N), _p(value), _p(length), C.c_double(periods_per_year), C.c_double(rf),
                       _p(out))
     return out
+
+
+def population_refill(params, rank, keep: int, sigma: float, noise=None):
+    """Returns the refilled copy of params [P, count] (Sec. 4.1 generator: losers <- candidates + mutation)."""
+    out = np.array(params, dtype=np.float32, order="C", copy=True)
+    P = out.shape[0]
+    flat = out.reshape(P, -1)
+    rank = np.ascontiguousarray(rank, dtype=np.int32)
+    z = None if noise is None else np.ascontiguousarray(noise, dtype=np.float32).reshape(P, -1)
+    assert rank.shape == (P,) and 1 <= keep <= P and (z is None or z.shape == flat.shape)
+    lib().orc_population_refill(int(P), C.c_int64(flat.shape[1]), _p(rank), int(keep), C.c_float(sigma), _p(z), _p(flat))
+    return out

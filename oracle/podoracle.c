@@ -503,3 +503,28 @@ void orc_metrics(int T, int64_t N, const double *value, const int32_t *len, doub
   }
   free(V);
 }
+
+/* ------------------------------------------------- population generator -- */
+
+/* Generator / updater step on a population held in one parameter block
+ * (Sec. 4.1: the leaderboard records the candidate agents with high
+ * performance; the generator produces the training files of a new pod from a
+ * candidate and "may perform a mutation" to increase diversity).
+ * params [P, count]: one row per agent.  rank [P]: agent ids, best first.
+ * The first `keep` agents of rank are the candidates and stay as they are;
+ * agent rank[j], j >= keep, becomes candidate rank[(j - keep) % keep] plus
+ * sigma * noise[rank[j]], each operation rounded to binary32:
+ *   child = fl32(parent + fl32(sigma * z)). */
+void orc_population_refill(int P, int64_t count, const int32_t *rank, int keep, float sigma, const float *noise,
+                           float *params) {
+  for (int j = keep; j < P; ++j) {
+    const float *parent = params + (int64_t)rank[(j - keep) % keep] * count;
+    float *child = params + (int64_t)rank[j] * count;
+    const float *z = noise ? noise + (int64_t)rank[j] * count : NULL;
+    for (int64_t i = 0; i < count; ++i) {
+      volatile float step = z ? sigma * z[i] : 0.0f;
+      volatile float v = parent[i] + step;
+      child[i] = v;
+    }
+  }
+}
