@@ -172,6 +172,19 @@ def main():
     torch.cuda.synchronize()
     t_metrics = e0.elapsed_time(e1) / 3
 
+    # (also outside) the generator step on a 64-agent block of 512 x 512 weights, 16 candidates kept
+    pop = torch.randn((64, 512, 512), device=dev)
+    pop_noise = torch.randn((64, 512, 512), device=dev)
+    pop_rank = torch.randperm(64, device=dev).to(torch.int32)
+    pr.population_refill(pop, pop_rank, 16, 0.02, pop_noise)
+    e0.record()
+    for _ in range(10):
+        pr.population_refill(pop, pop_rank, 16, 0.02, pop_noise)
+    e1.record()
+    torch.cuda.synchronize()
+    t_pop = e0.elapsed_time(e1) / 10
+    del pop, pop_noise
+
     ms = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in events) / args.steps
     t_roll, t_critic, t_gae = ms(0, 1), ms(1, 2), ms(2, 3)
     env_steps = N * T
@@ -209,7 +222,10 @@ def main():
         "roofline": dom,
         "stages": stages,
         "extras": {"trading_metrics": {"ms": t_metrics, "note": "not part of value; reads 4(1+2D) of every 4S-byte row",
-                                       "GBps": (4 * (1 + 2 * D) + 1) * (T + 1) * N / t_metrics / 1e6}},
+                                       "GBps": (4 * (1 + 2 * D) + 1) * (T + 1) * N / t_metrics / 1e6},
+                   "population_refill": {"ms": t_pop, "note": "not part of value; 48 of 64 agents x 512 x 512 weights, "
+                                                              "12 B per rewritten weight",
+                                         "GBps": 48 * 512 * 512 * 12 / t_pop / 1e6}},
     }
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)

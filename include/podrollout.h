@@ -196,6 +196,20 @@ int trading_metrics(void *hip_stream, int32_t T, int32_t N, int32_t n_stocks, in
                     const uint8_t *done, const float *obs_scale, double periods_per_year, double risk_free,
                     double *metrics, int32_t *length);
 
+/* Generator / updater step on a population held on this GPU (Sec. 4.1: the leaderboard records the candidate
+ * agents with high performance, the generator produces the training files of a new pod from a candidate and may
+ * mutate them).  params [P, count]: one row per agent -- any tensor of pr_weights viewed as [P, count]; call once
+ * per tensor with the same rank.  rank [P]: agent ids, best first, a permutation of 0..P-1 (what
+ * rollout_leaderboard writes).  The first `keep` agents of rank are left as they are; agent rank[j], j >= keep,
+ * is overwritten in place with
+ *     fl32( params[rank[(j - keep) % keep]] + fl32(sigma * noise[rank[j]]) )      (element-wise, binary32).
+ * noise [P, count] (rows of kept agents are not read); may be NULL when sigma == 0 (plain copies).  The random
+ * numbers are the caller's.  Entries of rank outside 0..P-1 leave that agent untouched.
+ * Stateless; device pointers; only enqueues on hip_stream.  1 <= keep <= P <= 65535, count >= 1.
+ * Follow with rollout_set_weights to let the rollout use the new population. */
+int population_refill(void *hip_stream, int32_t P, int64_t count, const int32_t *rank, int32_t keep, float sigma,
+                      const float *noise, float *params);
+
 /* Leaderboard score of every agent (Sec. 4.1; Sec. 4.2 evaluator): mean and
  * population variance of the returns of the episodes its envs have finished
  * since the last reset, and the agents ordered best first (equal means: lower

@@ -23,7 +23,8 @@ LIB = os.path.join(HERE, "libpodrollout.so")
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
-PER_FILE = {"pod_env.hip": ["-ffp-contract=off"], "pod_fused.hip": ["-ffp-contract=off"]}
+PER_FILE = {"pod_env.hip": ["-ffp-contract=off"], "pod_fused.hip": ["-ffp-contract=off"],
+            "pod_population.hip": ["-ffp-contract=off"]}
 
 
 def sources():

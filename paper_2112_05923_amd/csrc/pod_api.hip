@@ -355,6 +355,16 @@ int trading_metrics(void *hip_stream, int32_t T, int32_t N, int32_t n_stocks, in
   return PR_OK;
 }
 
+int population_refill(void *hip_stream, int32_t P, int64_t count, const int32_t *rank, int32_t keep, float sigma,
+                      const float *noise, float *params) {
+  if (P < 1 || count < 1 || !rank || !params || keep < 1 || keep > P || P > 65535) return PR_EINVAL;
+  if (!isfinite(sigma) || (sigma != 0.0f && !noise)) return PR_EINVAL;
+  if ((double)P * (double)count >= 9.0e18) return PR_EINVAL;
+  POD_HIP(launch_population_refill(static_cast<hipStream_t>(hip_stream), P, count, rank, keep, sigma,
+                                   sigma != 0.0f ? noise : nullptr, params));
+  return PR_OK;
+}
+
 int rollout_leaderboard(pr_handle *h, double *score_mean, double *score_var, int32_t *rank) {
   if (!h || !score_mean || !score_var || !rank) return PR_EINVAL;
   POD_HIP(launch_leaderboard(h->stream, h->cfg.n_envs, h->cfg.n_agents, h->st, nullptr, score_mean, score_var, rank));

@@ -56,6 +56,8 @@ size_t env_step_lds_bytes(const EnvDims &d, int *envs_per_block);
 hipError_t launch_trading_metrics(hipStream_t st, int32_t T, int32_t N, int32_t D, int32_t S, const float *obs,
                                   const uint8_t *done, const float *obs_scale, double periods, double rf,
                                   double *metrics, int32_t *length);
+hipError_t launch_population_refill(hipStream_t st, int32_t P, int64_t count, const int32_t *rank, int32_t keep,
+                                    float sigma, const float *noise, float *params);
 hipError_t launch_gae(hipStream_t st, int32_t T, int32_t N, const float *reward, const float *value,
                       const uint8_t *done, float gamma, float lambda, float *adv, float *ret);
 

@@ -22,7 +22,7 @@ PR_NET_ACTOR, PR_NET_CRITIC = 0, 1
 
 EXPORTS = ["rollout_workspace_bytes", "rollout_init", "rollout_set_weights", "rollout_reset", "rollout_step_T",
            "rollout_step_forced", "rollout_mlp_forward", "rollout_get_state", "rollout_set_state", "compute_gae",
-           "trading_metrics", "rollout_leaderboard", "rollout_destroy", "rollout_strerror", "rollout_last_hip_error"]
+           "trading_metrics", "population_refill", "rollout_leaderboard", "rollout_destroy", "rollout_strerror", "rollout_last_hip_error"]
 
 
 class PrConfig(C.Structure):
@@ -86,6 +86,8 @@ def lib():
                                   C.c_float, C.c_void_p, C.c_void_p]
         l.trading_metrics.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                       C.POINTER(C.c_float), C.c_double, C.c_double, C.c_void_p, C.c_void_p]
+        l.population_refill.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_int32, C.c_float, C.c_void_p,
+                                        C.c_void_p]
         l.rollout_leaderboard.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         l.rollout_destroy.argtypes = [C.c_void_p]
         _lib = l
@@ -302,3 +304,16 @@ def trading_metrics(obs: torch.Tensor, done: torch.Tensor, n_stocks: int, obs_sc
                                  float(risk_free), _dev(out, torch.float64, (6, N), "metrics"),
                                  _dev(length, torch.int32, (N,), "length")), "trading_metrics")
     return out, length
+
+
+def population_refill(params: torch.Tensor, rank: torch.Tensor, keep: int, sigma: float = 0.0,
+                      noise: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """In place on params [P, ...]: agents ranked behind the first `keep` become copies of the kept ones (in turn)
+    plus sigma * noise.  rank: int32 [P], best first."""
+    P = params.shape[0]
+    count = params.numel() // P
+    shape = tuple(params.shape)
+    _check(lib().population_refill(_stream_ptr(), P, count, _dev(rank, torch.int32, (P,), "rank"), int(keep),
+                                   float(sigma), None if noise is None else _dev(noise, torch.float32, shape, "noise"),
+                                   _dev(params, torch.float32, shape, "params")), "population_refill")
+    return params

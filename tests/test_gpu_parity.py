@@ -538,3 +538,52 @@ def test_full_size_workloads(name, schedule, n_sample):
         assert np.array_equal(parity.to_np(rank), want[2])
     del out, d, ro
     torch.cuda.empty_cache()
+
+
+# ------------------------------------------------- population generator step
+
+@pytest.mark.parametrize("P,shape,keep,sigma", [(64, (301, 256), 16, 0.02), (64, (30,), 5, 0.5), (7, (1,), 1, 0.25),
+                                                (9, (3, 5), 9, 0.1), (12, (1024, 64), 4, 0.0)])
+def test_population_refill_matches_checker_bit_for_bit(P, shape, keep, sigma):
+    rng = np.random.default_rng(P * 31 + keep)
+    params = rng.standard_normal((P,) + shape).astype(np.float32)
+    noise = rng.standard_normal((P,) + shape).astype(np.float32)
+    rank = rng.permutation(P).astype(np.int32)
+    want = oracle.population_refill(params, rank, keep, sigma, noise if sigma != 0.0 else None)
+    got = pr.population_refill(torch.from_numpy(params).to(DEV), torch.from_numpy(rank).to(DEV), keep, sigma,
+                               torch.from_numpy(noise).to(DEV) if sigma != 0.0 else None)
+    torch.cuda.synchronize()
+    assert np.array_equal(parity.to_np(got).view(np.uint32), want.view(np.uint32))
+
+
+def test_population_cycle_rank_refill_and_roll_again():
+    """Leaderboard -> generator -> new weights in the rollout (Sec. 4.1 tournament loop on one GPU): after the
+    refill the replaced agents act exactly like their parents when no mutation is applied."""
+    P, T = 4, 12
+    w = inputs.WORKLOADS["tournament"].replace(n_envs=64 * P, n_agents=P, steps=T)
+    d, ro, ocfg = _make(w, horizon=T)
+    noise = torch.from_numpy(d["noise"]).to(DEV)
+    out = ro.alloc_buffers(T, value=True, logp=False, mu=True)
+    ro.step_T(T, noise, out)
+    mean, var, rank = ro.leaderboard()
+    torch.cuda.synchronize()
+    rk = parity.to_np(rank)
+    nets = {k: _dev(d[k]) for k in ("actor", "critic")}
+    for net in nets.values():
+        for v in net.values():
+            pr.population_refill(v, rank, 2, 0.0)
+    ro.set_weights(nets["actor"], nets["critic"])
+    torch.cuda.synchronize()
+    for k in ("actor", "critic"):
+        for name, v in nets[k].items():
+            want = oracle.population_refill(d[k][name], rk, 2, 0.0)
+            assert np.array_equal(parity.to_np(v), want), (k, name)
+    # the agent ranked third now carries the best agent's networks: same observations in, same means out
+    X = torch.from_numpy(np.random.default_rng(1).standard_normal((64 * P, w.state_dim)).astype(np.float32)).to(DEV)
+    mu = ro.mlp_forward(pr.PR_NET_ACTOR, X)
+    per = 64
+    Xs = X.clone()
+    Xs[rk[2] * per:(rk[2] + 1) * per] = X[rk[0] * per:(rk[0] + 1) * per]
+    mu2 = ro.mlp_forward(pr.PR_NET_ACTOR, Xs)
+    torch.cuda.synchronize()
+    assert torch.equal(mu2[rk[2] * per:(rk[2] + 1) * per], mu[rk[0] * per:(rk[0] + 1) * per])

@@ -88,6 +88,7 @@ def test_null_arguments_are_rejected_without_device_work():
     assert lib.compute_gae(None, 0, 4, None, None, None, 0.99, 0.95, None, None) == pr.PR_EINVAL
     assert lib.compute_gae(None, 4, 4, None, None, None, 0.99, 0.95, None, None) == pr.PR_EINVAL
     assert lib.trading_metrics(None, 4, 4, 3, 13, None, None, None, 252.0, 0.0, None, None) == pr.PR_EINVAL
+    assert lib.population_refill(None, 4, 16, None, 2, 0.0, None, None) == pr.PR_EINVAL
 
 
 def test_missing_library_fails_loudly(monkeypatch):
