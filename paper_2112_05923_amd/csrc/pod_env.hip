@@ -61,104 +61,128 @@ __global__ __launch_bounds__(kThreads) void observe_kernel(EnvDims d, EnvState s
 }
 
 // ----------------------------------------------------------------- env step
-// One workgroup steps E consecutive envs.  LDS holds five [E][Dp] arrays
-// (Dp odd so that the per-env serial loops of the trade pass hit distinct
-// banks): clamped action, eps^2 (later the executed shares), execution prices,
-// valuation prices, holdings.
+// One workgroup of 8 wavefronts steps E consecutive envs.  LDS holds [E][Dp]
+// arrays (Dp odd so that the per-env serial loops of the trade pass hit
+// distinct banks): wanted shares, eps^2, unit value of the trade (sale proceeds
+// or purchase cost per share), executed shares, valuation prices, holdings.
+//  1. all lanes, one wavefront per env row (no index divisions): sample and clamp the action, size the
+//     order, fetch prices; holdings come in from their [D][N] layout with lanes across envs;
+//  2. wavefront 0, one lane per env: the serial trade pass in branch-free code (a lane's branch costs all 64
+//     a round trip through the scalar unit; what bounds the pass is the dependent chain on the running cash),
+//     reward and episode bookkeeping in binary64 -- meanwhile the other wavefronts stream the market part of
+//     the next observation, 16 bytes per lane where the indicator rows allow it;
+//  3. all lanes: holdings / cash part of the next observation, executed shares, state write-back.
+constexpr int kEnvThreads = 512;
+typedef float env_f32x4 __attribute__((ext_vector_type(4)));
+
 template <int E>
-__global__ __launch_bounds__(kThreads) void env_step_kernel(EnvDims d, EnvState s, const float *__restrict__ price,
-                                                           const float *__restrict__ ind, StepIO io) {
+__global__ __launch_bounds__(kEnvThreads) void env_step_kernel(EnvDims d, EnvState s, const float *__restrict__ price,
+                                                              const float *__restrict__ ind, StepIO io) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const int D = d.D, Dp = D | 1;
-  float *s_a = reinterpret_cast<float *>(lds_raw);
-  float *s_e2 = s_a + E * Dp;
-  int32_t *s_q = reinterpret_cast<int32_t *>(s_e2);
-  float *s_p = s_e2 + E * Dp;
-  float *s_pv = s_p + E * Dp;
+  double *s_a0 = reinterpret_cast<double *>(lds_raw);  // [E] account value before the trades
+  int32_t *s_k = reinterpret_cast<int32_t *>(s_a0 + E);
+  float *s_e2 = reinterpret_cast<float *>(s_k + E * Dp);
+  float *s_val = s_e2 + E * Dp;
+  int32_t *s_q = reinterpret_cast<int32_t *>(s_val + E * Dp);
+  float *s_pv = reinterpret_cast<float *>(s_q + E * Dp);
   int32_t *s_h = reinterpret_cast<int32_t *>(s_pv + E * Dp);
   RowInfo *s_row = reinterpret_cast<RowInfo *>(s_h + E * Dp);
   float *s_cash = reinterpret_cast<float *>(s_row + E);
 
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int NWV = kEnvThreads / 64;
   const int n0 = blockIdx.x * E;
   const int ne = min(E, d.N - n0);  // live envs of this tile
 
   if (tid < ne) s_row[tid] = rows_of(d, s.tau[n0 + tid], n0 + tid);
+  for (int dd = wave; dd < D; dd += NWV)
+    for (int e = lane; e < ne; e += 64) s_h[e * Dp + dd] = s.h[(size_t)dd * d.N + n0 + e];
   __syncthreads();
 
-  // -- stage the tile: sample the action, fetch prices and holdings
-  const int tile_elems = ne * D;
-  const size_t g0 = (size_t)n0 * D;
-  for (int idx = tid; idx < tile_elems; idx += kThreads) {
-    const int e = idx / D, dd = idx - e * D;
-    const float mu = io.mu[g0 + idx];
-    const float eps = io.noise[g0 + idx];
-    const float a_raw = mu + d.sigma * eps;  // two roundings (contraction is off)
-    io.act_raw[g0 + idx] = a_raw;
-    s_a[e * Dp + dd] = fminf(1.0f, fmaxf(-1.0f, a_raw));
-    s_e2[e * Dp + dd] = eps * eps;
-    s_p[e * Dp + dd] = price[(size_t)s_row[e].row_now * D + dd];
-    s_pv[e * Dp + dd] = price[(size_t)s_row[e].row_val * D + dd];
+  // -- 1. sample, size the orders, fetch prices
+  for (int e = wave; e < ne; e += NWV) {
+    const RowInfo ri = s_row[e];
+    const size_t g0 = (size_t)(n0 + e) * D;
+    for (int dd = lane; dd < D; dd += 64) {
+      const int o = e * Dp + dd;
+      const float mu = io.mu[g0 + dd];
+      const float eps = io.noise[g0 + dd];
+      const float a_raw = mu + d.sigma * eps;  // two roundings (contraction is off)
+      io.act_raw[g0 + dd] = a_raw;
+      const float ac = fminf(1.0f, fmaxf(-1.0f, a_raw));
+      const int32_t k = (int32_t)truncf(ac * d.hmax);
+      const float p = price[(size_t)ri.row_now * D + dd];
+      const int32_t h = s_h[o];
+      int32_t q = 0;
+      float val = 1.0f;  // (holds: a harmless divisor)
+      if (k < 0) {
+        q = min(-k, h);
+        s_h[o] = h - q;
+        const float gross = p * (float)q;
+        val = gross * d.one_minus_c;
+        q = -q;
+      } else if (k > 0) {
+        val = p * d.one_plus_c;
+      }
+      s_k[o] = k;
+      s_e2[o] = eps * eps;
+      s_val[o] = val;
+      s_q[o] = q;
+      s_pv[o] = price[(size_t)ri.row_val * D + dd];
+    }
   }
-  for (int idx = tid; idx < E * D; idx += kThreads) {
-    const int dd = idx / E, e = idx - dd * E;
-    if (e < ne) s_h[e * Dp + dd] = s.h[(size_t)dd * d.N + n0 + e];
+  // account value before the trades: cash + sum h p in stock order, binary64 (lane per env, needs the prices)
+  __syncthreads();
+  if (wave == 1) {
+    for (int e = lane; e < ne; e += 64) {
+      const RowInfo ri = s_row[e];
+      double v = (double)s.cash[n0 + e];
+      for (int dd = 0; dd < D; ++dd) {
+        // holdings before the sales = holdings now + what the sale pass took
+        const int32_t k = s_k[e * Dp + dd];
+        const int32_t h0 = s_h[e * Dp + dd] + (k < 0 ? -s_q[e * Dp + dd] : 0);
+        v += (double)h0 * (double)price[(size_t)ri.row_now * D + dd];
+      }
+      s_a0[e] = v;
+    }
   }
   __syncthreads();
 
-  if (tid < E) {
-    // -- one lane per env: the serial part (Table 1 actions: sell / buy / hold)
-    if (tid < ne) {
-      const int e = tid, n = n0 + e;
-      float *a = s_a + e * Dp;
-      float *p = s_p + e * Dp;
-      float *pv = s_pv + e * Dp;
-      int32_t *h = s_h + e * Dp;
-      int32_t *q_out = s_q + e * Dp;
+  if (wave == 0) {
+    // -- 2a. one lane per env: the serial part (Table 1 actions: sell / buy / hold)
+    for (int e = lane; e < ne; e += 64) {
+      const int n = n0 + e, o0 = e * Dp;
       float cash = s.cash[n];
       float e2 = 0.0f;
-      double asset0 = (double)cash;
       for (int dd = 0; dd < D; ++dd) {
-        asset0 += (double)h[dd] * (double)p[dd];
-        e2 += s_e2[e * Dp + dd];
+        e2 += s_e2[o0 + dd];
+        const int32_t k = s_k[o0 + dd];
+        const float v = s_val[o0 + dd];
+        cash = k < 0 ? cash + v : cash;  // all sales in stock order
       }
-      // wanted shares, then all sales in stock order
+      // all purchases in stock order, each limited by the cash left:
+      //   m = floor(cash / u); q = min(k, max(m, 0)); if (q u > cash) q -= 1; cash -= q u        (binary32)
       for (int dd = 0; dd < D; ++dd) {
-        const int32_t k = (int32_t)truncf(a[dd] * d.hmax);
-        int32_t q = 0;
-        if (k < 0) {
-          q = min(-k, h[dd]);
-          h[dd] -= q;
-          const float gross = p[dd] * (float)q;
-          const float net = gross * d.one_minus_c;
-          cash = cash + net;
-          q = -q;
-        }
-        a[dd] = __int_as_float(k);
-        q_out[dd] = q;
-      }
-      // all purchases in stock order, each limited by the cash left
-      for (int dd = 0; dd < D; ++dd) {
-        const int32_t k = __float_as_int(a[dd]);
-        if (k > 0) {
-          const float u = p[dd] * d.one_plus_c;
-          const float ratio = cash / u;
-          int32_t m = (int32_t)floorf(ratio);
-          m = max(m, 0);
-          int32_t q = min(k, m);
-          float outlay = (float)q * u;
-          if (outlay > cash) {
-            q -= 1;
-            outlay = (float)q * u;
-          }
-          h[dd] += q;
-          cash = cash - outlay;
-          q_out[dd] = q;
-        }
+        const int32_t kk = s_k[o0 + dd];
+        const bool buy = kk > 0;
+        const int32_t k = max(kk, 0);
+        const float u = s_val[o0 + dd];  // unit cost of a purchase; anything non-zero otherwise (k = 0 gives q = 0)
+        const float ratio = cash / u;
+        int32_t m = (int32_t)floorf(ratio);
+        m = max(m, 0);
+        int32_t q = buy ? min(k, m) : 0;
+        const float out_q = (float)q * u, out_q1 = (float)(q - 1) * u;
+        const bool over = buy && out_q > cash;
+        q = over ? q - 1 : q;
+        const float outlay = over ? out_q1 : out_q;
+        cash = buy ? cash - outlay : cash;
+        s_h[o0 + dd] += q;
+        s_q[o0 + dd] += q;  // (a purchase slot held 0)
       }
       double asset1 = (double)cash;
-      for (int dd = 0; dd < D; ++dd) asset1 += (double)h[dd] * (double)pv[dd];
-      const double r = (asset1 - asset0) * (double)d.rho;
+      for (int dd = 0; dd < D; ++dd) asset1 += (double)s_h[o0 + dd] * (double)s_pv[o0 + dd];
+      const double r = (asset1 - s_a0[e]) * (double)d.rho;
       const RowInfo ri = s_row[e];
       double ep = s.ep_ret[n] + r;
       if (ri.done) {
@@ -167,7 +191,7 @@ __global__ __launch_bounds__(kThreads) void env_step_kernel(EnvDims d, EnvState 
         s.ep_cnt[n] += 1;
         ep = 0.0;
         cash = d.cash0;
-        for (int dd = 0; dd < D; ++dd) h[dd] = 0;
+        for (int dd = 0; dd < D; ++dd) s_h[o0 + dd] = 0;
       }
       s.ep_ret[n] = ep;
       s.cash[n] = cash;
@@ -178,41 +202,47 @@ __global__ __launch_bounds__(kThreads) void env_step_kernel(EnvDims d, EnvState 
       if (io.logp) io.logp[n] = fmaf(-0.5f, e2, d.logp_const);
     }
   } else {
-    // -- the other wavefronts stream the market part of the next observation
+    // -- 2b. the other wavefronts stream the market part of the next observation, one env row at a time
     const int DK = D * d.K;
-    const int per_row = D + DK;  // prices then indicators, both at row_obs
-    const int nthr = kThreads - E;
-    const int t2 = tid - E;
-    if (nthr > 0) {
-      for (int idx = t2; idx < ne * per_row; idx += nthr) {
-        const int e = idx / per_row, j = idx - e * per_row;
-        const size_t row = (size_t)s_row[e].row_obs;
-        float *o = io.obs_next + (size_t)(n0 + e) * d.S;
-        if (j < D)
-          o[1 + j] = price[row * D + j] * d.s_price;
-        else
-          o[1 + 2 * D + (j - D)] = ind[row * DK + (j - D)] * d.s_ind;
+    const bool vec = (DK & 3) == 0 && (reinterpret_cast<uintptr_t>(ind) & 15u) == 0;
+    for (int e = wave - 1; e < ne; e += NWV - 1) {
+      const size_t row = (size_t)s_row[e].row_obs;
+      float *o = io.obs_next + (size_t)(n0 + e) * d.S;
+      for (int j = lane; j < D; j += 64) o[1 + j] = price[row * D + j] * d.s_price;
+      const float *src = ind + row * DK;
+      float *dst = o + 1 + 2 * D;
+      if (vec) {
+        for (int j = 4 * lane; j < DK; j += 256) {
+          env_f32x4 v = *reinterpret_cast<const env_f32x4 *>(src + j);
+          v[0] *= d.s_ind;
+          v[1] *= d.s_ind;
+          v[2] *= d.s_ind;
+          v[3] *= d.s_ind;
+          *reinterpret_cast<env_f32x4 *>(dst + j) = v;  // 4-byte aligned is enough for a global store
+        }
+      } else {
+        for (int j = lane; j < DK; j += 64) dst[j] = src[j] * d.s_ind;
       }
     }
   }
   __syncthreads();
 
-  // -- write back what the trade pass produced
+  // -- 3. write back what the trade pass produced
   if (tid < ne) io.obs_next[(size_t)(n0 + tid) * d.S] = s_cash[tid] * d.s_cash;
-  for (int idx = tid; idx < tile_elems; idx += kThreads) {
-    const int e = idx / D, dd = idx - e * D;
-    io.obs_next[(size_t)(n0 + e) * d.S + 1 + D + dd] = (float)s_h[e * Dp + dd] * d.s_hold;
-    if (io.shares) io.shares[g0 + idx] = s_q[e * Dp + dd];
+  for (int e = wave; e < ne; e += NWV) {
+    const size_t g0 = (size_t)(n0 + e) * D;
+    for (int dd = lane; dd < D; dd += 64) {
+      io.obs_next[(size_t)(n0 + e) * d.S + 1 + D + dd] = (float)s_h[e * Dp + dd] * d.s_hold;
+      if (io.shares) io.shares[g0 + dd] = s_q[e * Dp + dd];
+    }
   }
-  for (int idx = tid; idx < E * D; idx += kThreads) {
-    const int dd = idx / E, e = idx - dd * E;
-    if (e < ne) s.h[(size_t)dd * d.N + n0 + e] = s_h[e * Dp + dd];
-  }
+  for (int dd = wave; dd < D; dd += NWV)
+    for (int e = lane; e < ne; e += 64) s.h[(size_t)dd * d.N + n0 + e] = s_h[e * Dp + dd];
 }
 
 size_t env_lds(int E, int D) {
   const int Dp = D | 1;
-  return (size_t)5 * E * Dp * 4 + (size_t)E * (sizeof(RowInfo) + sizeof(float));
+  return (size_t)6 * E * Dp * 4 + (size_t)E * (sizeof(RowInfo) + sizeof(float) + sizeof(double));
 }
 
 // ------------------------------------------------------------ state plumbing
@@ -338,7 +368,7 @@ hipError_t launch_env_step(hipStream_t st, const EnvDims &d, const EnvState &s, 
                            const StepIO &io) {
   int E = 0;
   const size_t lds = env_step_lds_bytes(d, &E);
-  const dim3 grid((d.N + E - 1) / E), block(kThreads);
+  const dim3 grid((d.N + E - 1) / E), block(kEnvThreads);
   switch (E) {
     case 64: hipLaunchKernelGGL(env_step_kernel<64>, grid, block, lds, st, d, s, price, ind, io); break;
     case 16: hipLaunchKernelGGL(env_step_kernel<16>, grid, block, lds, st, d, s, price, ind, io); break;
