@@ -587,3 +587,50 @@ def test_population_cycle_rank_refill_and_roll_again():
     mu2 = ro.mlp_forward(pr.PR_NET_ACTOR, Xs)
     torch.cuda.synchronize()
     assert torch.equal(mu2[rk[2] * per:(rk[2] + 1) * per], mu[rk[0] * per:(rk[0] + 1) * per])
+
+
+# ------------------------------------------------------------ graph capture
+
+@pytest.mark.parametrize("schedule", [pr.PR_SCHED_STEPWISE, FUSED])
+def test_rollout_and_gae_replay_from_a_captured_graph(schedule):
+    """The entry points only enqueue kernels on the stream the handle was created on (no allocation, no memset,
+    no host sync), so a whole rollout + GAE can be captured once and replayed: every replay must reproduce the
+    eager result."""
+    T = 16
+    w = inputs.WORKLOADS["large"].replace(n_envs=128, steps=T)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        d, ro, _ = _make(w, horizon=12, schedule=schedule)      # the handle enqueues on `side` from now on
+        noise = torch.from_numpy(d["noise"]).to(DEV)
+        out = ro.alloc_buffers(T, value=True, logp=True)
+        adv = torch.empty((T, w.n_envs), device=DEV)
+        ret = torch.empty_like(adv)
+
+        def run():
+            ro.reset()
+            ro.step_T(T, noise, out)
+            pr.compute_gae(out["reward"], out["value"], out["done"], w.gamma, w.lam, adv, ret)
+
+        run()                                     # eager: also sets the kernels' launch attributes
+        side.synchronize()
+        want = {k: v.clone() for k, v in out.items()}
+        want_adv, want_state = adv.clone(), {k: v.clone() for k, v in ro.get_state().items()}
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            run()
+        side.synchronize()
+        for rep in range(3):
+            for v in out.values():
+                v.fill_(0)                        # (eager fill kernels between the replays)
+            adv.fill_(0)
+            side.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for k in out:
+                assert torch.equal(out[k], want[k]), (rep, k)
+            assert torch.equal(adv, want_adv), rep
+            st = ro.get_state()
+            side.synchronize()
+            for k in st:
+                assert torch.equal(st[k], want_state[k]), (rep, k)
