@@ -293,3 +293,36 @@ def population_refill(params, rank, keep: int, sigma: float, noise=None):
     assert rank.shape == (P,) and 1 <= keep <= P and (z is None or z.shape == flat.shape)
     lib().orc_population_refill(int(P), C.c_int64(flat.shape[1]), _p(rank), int(keep), C.c_float(sigma), _p(z), _p(flat))
     return out
+
+
+NET_KEYS = ("W1", "b1", "W2", "b2", "W3", "b3")
+
+
+def ppo_grads(obs, act, logp_old, adv, ret, actor, critic, sigma: float, clip: float, value_coef: float):
+    """One PPO minibatch in fp64: returns (grads_actor, grads_critic, stats[4], margin[B]); nets are dicts of fp32
+    arrays without an agent axis (W [in, out])."""
+    obs, act = _f32(obs), _f32(act)
+    B, S = obs.shape
+    D = act.shape[1]
+    Hd = actor["W1"].shape[1]
+    a = {k: _f32(actor[k]) for k in NET_KEYS}
+    c = {k: _f32(critic[k]) for k in NET_KEYS}
+    assert a["W1"].shape == (S, Hd) and a["W3"].shape == (Hd, D) and c["W3"].shape == (Hd, 1)
+    ga = {k: np.zeros(a[k].shape, np.float64) for k in NET_KEYS}
+    gc = {k: np.zeros(c[k].shape, np.float64) for k in NET_KEYS}
+    stats = np.zeros(4, np.float64)
+    margin = np.zeros(B, np.float64)
+    lib().orc_ppo_grads(int(B), int(S), int(Hd), int(D), _p(obs), _p(act), _p(_f32(logp_old)), _p(_f32(adv)),
+                        _p(_f32(ret)), *[_p(a[k]) for k in NET_KEYS], *[_p(c[k]) for k in NET_KEYS],
+                        C.c_double(sigma), C.c_double(clip), C.c_double(value_coef),
+                        *[_p(ga[k]) for k in NET_KEYS], *[_p(gc[k]) for k in NET_KEYS], _p(stats), _p(margin))
+    return ga, gc, stats, margin
+
+
+def adam(theta, g, m, v, lr: float, b1: float, b2: float, eps: float, t: int):
+    """In fp64; returns new (theta, m, v)."""
+    theta, m, v = (np.array(x, dtype=np.float64, copy=True) for x in (theta, m, v))
+    g = np.ascontiguousarray(g, dtype=np.float64)
+    lib().orc_adam(C.c_int64(theta.size), _p(theta), _p(g), _p(m), _p(v), C.c_double(lr), C.c_double(b1),
+                   C.c_double(b2), C.c_double(eps), int(t))
+    return theta, m, v

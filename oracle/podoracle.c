@@ -528,3 +528,126 @@ void orc_population_refill(int P, int64_t count, const int32_t *rank, int keep, 
     }
   }
 }
+
+/* ------------------------------------------------------ PPO learner step -- */
+
+/* One minibatch of the learner (Sec. 4.2 "Learner": fetch a batch of transitions, train the networks; Sec. 5.2:
+ * PPO, batch size 1024, learning rate 1e-3).  The paper points to PPO without writing it out; this is the
+ * clipped-surrogate objective with a fixed-deviation Gaussian policy, everything in binary64:
+ *   mu = actor(obs) (tanh after every layer), V = critic(obs) (linear output)
+ *   logp = sum_d -(a_d - mu_d)^2 / (2 sigma^2) - D ln sigma - D/2 ln(2 pi),   ratio = exp(logp - logp_old)
+ *   L_pi = -(1/B) sum_b min(ratio A, clip(ratio, 1 - eps, 1 + eps) A)
+ *   L_v  = (1/B) sum_b (V - R)^2 / 2,          L = L_pi + c_v L_v
+ * A sample's surrogate passes gradient when ratio A <= clip(ratio) A (inside the clip range, or outside it on
+ * the side the minimum does not cut).
+ * Weights [in, out] row-major, fp32 inputs; gradients of L w.r.t. the 6 + 6 tensors in binary64, same layouts.
+ * stats[0..3] = L_pi, L_v, fraction of samples whose surrogate is cut, mean ratio.
+ * margin[b] (optional) = distance of ratio from the nearer clip bound, for harnesses that want to tell a flipped
+ * min() from an error. */
+static void orc_dense_fwd(int in, int out, const double *x, const float *W, const float *b, int act, double *y) {
+  for (int o = 0; o < out; ++o) {
+    double acc = (double)b[o];
+    for (int i = 0; i < in; ++i) acc += x[i] * (double)W[(size_t)i * out + o];
+    y[o] = act ? tanh(acc) : acc;
+  }
+}
+
+/* dz [out] -> accumulates gW [in,out], gb [out]; writes dx [in] (if not NULL) */
+static void orc_dense_bwd(int in, int out, const double *x, const float *W, const double *dz, double *gW, double *gb,
+                          double *dx) {
+  for (int o = 0; o < out; ++o) gb[o] += dz[o];
+  for (int i = 0; i < in; ++i) {
+    double acc = 0.0;
+    for (int o = 0; o < out; ++o) {
+      gW[(size_t)i * out + o] += x[i] * dz[o];
+      acc += dz[o] * (double)W[(size_t)i * out + o];
+    }
+    if (dx) dx[i] = acc;
+  }
+}
+
+void orc_ppo_grads(int B, int S, int Hd, int D, const float *obs, const float *act, const float *logp_old,
+                   const float *adv, const float *ret, const float *aW1, const float *ab1, const float *aW2,
+                   const float *ab2, const float *aW3, const float *ab3, const float *cW1, const float *cb1,
+                   const float *cW2, const float *cb2, const float *cW3, const float *cb3, double sigma, double clip,
+                   double value_coef, double *gaW1, double *gab1, double *gaW2, double *gab2, double *gaW3,
+                   double *gab3, double *gcW1, double *gcb1, double *gcW2, double *gcb2, double *gcW3, double *gcb3,
+                   double *stats, double *margin) {
+  double *x = (double *)malloc((size_t)S * sizeof(double));
+  double *h1 = (double *)malloc((size_t)Hd * sizeof(double)), *h2 = (double *)malloc((size_t)Hd * sizeof(double));
+  double *d1 = (double *)malloc((size_t)Hd * sizeof(double)), *d2 = (double *)malloc((size_t)Hd * sizeof(double));
+  double *mu = (double *)malloc((size_t)D * sizeof(double)), *dz = (double *)malloc((size_t)D * sizeof(double));
+  memset(gaW1, 0, sizeof(double) * (size_t)S * Hd), memset(gab1, 0, sizeof(double) * Hd);
+  memset(gaW2, 0, sizeof(double) * (size_t)Hd * Hd), memset(gab2, 0, sizeof(double) * Hd);
+  memset(gaW3, 0, sizeof(double) * (size_t)Hd * D), memset(gab3, 0, sizeof(double) * D);
+  memset(gcW1, 0, sizeof(double) * (size_t)S * Hd), memset(gcb1, 0, sizeof(double) * Hd);
+  memset(gcW2, 0, sizeof(double) * (size_t)Hd * Hd), memset(gcb2, 0, sizeof(double) * Hd);
+  memset(gcW3, 0, sizeof(double) * (size_t)Hd), memset(gcb3, 0, sizeof(double));
+  double l_pi = 0.0, l_v = 0.0, n_cut = 0.0, r_sum = 0.0;
+  const double log_norm = -(double)D * log(sigma) - 0.5 * (double)D * log(2.0 * 3.14159265358979323846);
+  for (int b = 0; b < B; ++b) {
+    for (int i = 0; i < S; ++i) x[i] = (double)obs[(size_t)b * S + i];
+    /* ---- actor */
+    orc_dense_fwd(S, Hd, x, aW1, ab1, 1, h1);
+    orc_dense_fwd(Hd, Hd, h1, aW2, ab2, 1, h2);
+    orc_dense_fwd(Hd, D, h2, aW3, ab3, 1, mu);
+    double logp = log_norm;
+    for (int d = 0; d < D; ++d) {
+      const double e = (double)act[(size_t)b * D + d] - mu[d];
+      logp -= e * e / (2.0 * sigma * sigma);
+    }
+    const double ratio = exp(logp - (double)logp_old[b]);
+    const double A = (double)adv[b];
+    const double rc = ratio < 1.0 - clip ? 1.0 - clip : (ratio > 1.0 + clip ? 1.0 + clip : ratio);
+    const double s1 = ratio * A, s2 = rc * A;
+    const int active = s1 <= s2;
+    l_pi -= (active ? s1 : s2) / (double)B;
+    n_cut += active ? 0.0 : 1.0;
+    r_sum += ratio;
+    if (margin) {
+      const double lo = fabs(ratio - (1.0 - clip)), hi = fabs(ratio - (1.0 + clip));
+      margin[b] = lo < hi ? lo : hi;
+    }
+    /* dL/dmu_d = -(1/B) active ratio A (a_d - mu_d) / sigma^2, through the output tanh */
+    for (int d = 0; d < D; ++d) {
+      const double e = (double)act[(size_t)b * D + d] - mu[d];
+      const double dmu = active ? -(ratio * A * e / (sigma * sigma)) / (double)B : 0.0;
+      dz[d] = dmu * (1.0 - mu[d] * mu[d]);
+    }
+    orc_dense_bwd(Hd, D, h2, aW3, dz, gaW3, gab3, d2);
+    for (int i = 0; i < Hd; ++i) d2[i] *= 1.0 - h2[i] * h2[i];
+    orc_dense_bwd(Hd, Hd, h1, aW2, d2, gaW2, gab2, d1);
+    for (int i = 0; i < Hd; ++i) d1[i] *= 1.0 - h1[i] * h1[i];
+    orc_dense_bwd(S, Hd, x, aW1, d1, gaW1, gab1, NULL);
+    /* ---- critic */
+    double v;
+    orc_dense_fwd(S, Hd, x, cW1, cb1, 1, h1);
+    orc_dense_fwd(Hd, Hd, h1, cW2, cb2, 1, h2);
+    orc_dense_fwd(Hd, 1, h2, cW3, cb3, 0, &v);
+    const double err = v - (double)ret[b];
+    l_v += 0.5 * err * err / (double)B;
+    double dv = value_coef * err / (double)B;
+    orc_dense_bwd(Hd, 1, h2, cW3, &dv, gcW3, gcb3, d2);
+    for (int i = 0; i < Hd; ++i) d2[i] *= 1.0 - h2[i] * h2[i];
+    orc_dense_bwd(Hd, Hd, h1, cW2, d2, gcW2, gcb2, d1);
+    for (int i = 0; i < Hd; ++i) d1[i] *= 1.0 - h1[i] * h1[i];
+    orc_dense_bwd(S, Hd, x, cW1, d1, gcW1, gcb1, NULL);
+  }
+  stats[0] = l_pi;
+  stats[1] = l_v;
+  stats[2] = n_cut / (double)B;
+  stats[3] = r_sum / (double)B;
+  free(x), free(h1), free(h2), free(d1), free(d2), free(mu), free(dz);
+}
+
+/* Adam (the optimiser of the PPO implementation the paper uses; Kingma & Ba's update with bias correction):
+ *   m = b1 m + (1 - b1) g;  v = b2 v + (1 - b2) g^2;  theta -= lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps). */
+void orc_adam(int64_t n, double *theta, const double *g, double *m, double *v, double lr, double b1, double b2,
+              double eps, int t) {
+  const double c1 = 1.0 - pow(b1, (double)t), c2 = 1.0 - pow(b2, (double)t);
+  for (int64_t i = 0; i < n; ++i) {
+    m[i] = b1 * m[i] + (1.0 - b1) * g[i];
+    v[i] = b2 * v[i] + (1.0 - b2) * g[i] * g[i];
+    theta[i] -= lr * (m[i] / c1) / (sqrt(v[i] / c2) + eps);
+  }
+}
