@@ -210,6 +210,52 @@ int trading_metrics(void *hip_stream, int32_t T, int32_t N, int32_t n_stocks, in
 int population_refill(void *hip_stream, int32_t P, int64_t count, const int32_t *rank, int32_t keep, float sigma,
                       const float *noise, float *params);
 
+/* ---- the learner's minibatch (Sec. 4.2 "Learner": fetch a batch of transitions from the buffer and train the
+ * networks; Sec. 5.2: PPO with batch size 1024 and learning rate 1e-3).  The paper names PPO and stops there; this
+ * is its clipped-surrogate objective for the fixed-deviation Gaussian policy of the rollout, one agent:
+ *   mu = actor(obs), V = critic(obs)                    (same networks as pr_weights with P = 1)
+ *   logp = sum_d -(a_d - mu_d)^2 / (2 sigma^2) - D ln sigma - D/2 ln(2 pi),    ratio = exp(logp - logp_old)
+ *   L = -(1/B) sum_b min(ratio A, clip(ratio, 1 - clip, 1 + clip) A)  +  value_coef (1/B) sum_b (V - R)^2 / 2
+ * (a sample passes policy gradient when ratio A <= clip(ratio) A).  Advantages are used as given. */
+typedef struct pr_ppo_config {
+  int32_t batch;                 /* B >= 1 rows in the minibatch                          */
+  int32_t n_stocks, n_ind, hidden;  /* D, K, Hd: S = 1 + 2 D + D K inputs, Hd % 32 == 0      */
+  float sigma, clip, value_coef;
+  float lr, beta1, beta2, adam_eps; /* Adam (used by ppo_learner_step only)                 */
+  int32_t adam_step;             /* t >= 1: number of this update, for the bias correction */
+} pr_ppo_config;
+
+/* One network's tensors, fp32, device, layouts of pr_weights without the agent axis; mutable. */
+typedef struct pr_net_params {
+  float *W1, *b1, *W2, *b2, *W3, *b3;
+} pr_net_params;
+
+/* Bytes of device scratch the two calls below need (256-byte aligned, caller-owned). */
+int ppo_workspace_bytes(const pr_ppo_config *cfg, size_t *out);
+
+/* Gradients of L for one minibatch.  obs [R, S], act_raw [R, D], logp_old, adv, ret [R]: the rollout buffers
+ * flattened over (t, n); rows [B]: which of the R rows form the minibatch (NULL: rows 0 .. B-1).
+ * actor, critic: parameters (read); grad_actor, grad_critic: outputs, same shapes.
+ * stats (device, 4 floats, may be NULL): policy loss, value loss (unweighted), fraction of samples whose
+ * surrogate is cut by the min(), mean ratio.  Only enqueues on hip_stream; no allocation. */
+int ppo_minibatch_grads(void *hip_stream, const pr_ppo_config *cfg, const float *obs, const float *act_raw,
+                        const float *logp_old, const float *adv, const float *ret, const int32_t *rows,
+                        const pr_net_params *actor, const pr_net_params *critic, const pr_net_params *grad_actor,
+                        const pr_net_params *grad_critic, void *workspace, size_t workspace_bytes, float *stats);
+
+/* Adam on one tensor of n elements:  m = b1 m + (1 - b1) g;  v = b2 v + (1 - b2) g^2;
+ *   theta -= lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps).  All device, fp32, in place. */
+int adam_update(void *hip_stream, int64_t n, float *theta, const float *grad, float *m, float *v, float lr, float beta1,
+                float beta2, float eps, int32_t t);
+
+/* ppo_minibatch_grads followed by adam_update on all twelve tensors (gradients live in the workspace).
+ * m_*, v_*: Adam moments, same shapes as the parameters, zero before the first step. */
+int ppo_learner_step(void *hip_stream, const pr_ppo_config *cfg, const float *obs, const float *act_raw,
+                     const float *logp_old, const float *adv, const float *ret, const int32_t *rows,
+                     const pr_net_params *actor, const pr_net_params *critic, const pr_net_params *m_actor,
+                     const pr_net_params *v_actor, const pr_net_params *m_critic, const pr_net_params *v_critic,
+                     void *workspace, size_t workspace_bytes, float *stats);
+
 /* Leaderboard score of every agent (Sec. 4.1; Sec. 4.2 evaluator): mean and
  * population variance of the returns of the episodes its envs have finished
  * since the last reset, and the agents ordered best first (equal means: lower

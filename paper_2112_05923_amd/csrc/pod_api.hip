@@ -365,6 +365,113 @@ int population_refill(void *hip_stream, int32_t P, int64_t count, const int32_t 
   return PR_OK;
 }
 
+namespace {
+
+bool net_ok(const pr_net_params *p) { return p && p->W1 && p->b1 && p->W2 && p->b2 && p->W3 && p->b3; }
+
+int ppo_config_ok(const pr_ppo_config *c) {
+  if (!c || c->batch < 1 || c->n_stocks < 1 || c->n_ind < 0 || c->hidden < 32 || c->hidden % 32 != 0) return PR_EINVAL;
+  if (!(c->sigma > 0.0f) || !(c->clip > 0.0f) || !(c->clip < 1.0f) || !(c->value_coef >= 0.0f)) return PR_EINVAL;
+  if (!isfinite(c->sigma) || !isfinite(c->value_coef)) return PR_EINVAL;
+  if ((double)c->batch * (double)(1 + 2 * c->n_stocks + c->n_stocks * c->n_ind) >= 2147483647.0) return PR_EINVAL;
+  return PR_OK;
+}
+
+// sizes of the six tensors of a network with O outputs
+void net_sizes(const pr_ppo_config &c, int O, int64_t n[6]) {
+  const int64_t S = 1 + 2 * c.n_stocks + c.n_stocks * c.n_ind, Hd = c.hidden;
+  n[0] = S * Hd, n[1] = Hd, n[2] = Hd * Hd, n[3] = Hd, n[4] = Hd * O, n[5] = O;
+}
+
+size_t grads_bytes(const pr_ppo_config &c) {
+  int64_t a[6], b[6];
+  net_sizes(c, c.n_stocks, a);
+  net_sizes(c, 1, b);
+  size_t t = 0;
+  for (int i = 0; i < 6; ++i) t += align_up((size_t)a[i] * 4, 256) + align_up((size_t)b[i] * 4, 256);
+  return t;
+}
+
+}  // namespace
+
+int ppo_workspace_bytes(const pr_ppo_config *cfg, size_t *out) {
+  if (!out) return PR_EINVAL;
+  const int rc = ppo_config_ok(cfg);
+  if (rc != PR_OK) return rc;
+  *out = ppo_scratch_bytes(cfg->batch, cfg->hidden, cfg->n_stocks) + grads_bytes(*cfg);
+  return PR_OK;
+}
+
+int ppo_minibatch_grads(void *hip_stream, const pr_ppo_config *cfg, const float *obs, const float *act_raw,
+                        const float *logp_old, const float *adv, const float *ret, const int32_t *rows,
+                        const pr_net_params *actor, const pr_net_params *critic, const pr_net_params *grad_actor,
+                        const pr_net_params *grad_critic, void *workspace, size_t workspace_bytes, float *stats) {
+  const int rc = ppo_config_ok(cfg);
+  if (rc != PR_OK) return rc;
+  if (!obs || !act_raw || !logp_old || !adv || !ret || !workspace) return PR_EINVAL;
+  if (!net_ok(actor) || !net_ok(critic) || !net_ok(grad_actor) || !net_ok(grad_critic)) return PR_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) ||
+      workspace_bytes < ppo_scratch_bytes(cfg->batch, cfg->hidden, cfg->n_stocks))
+    return PR_EINVAL;
+  POD_HIP(launch_ppo_grads(static_cast<hipStream_t>(hip_stream), *cfg, obs, act_raw, logp_old, adv, ret, rows, *actor,
+                           *critic, *grad_actor, *grad_critic, workspace, stats));
+  return PR_OK;
+}
+
+int adam_update(void *hip_stream, int64_t n, float *theta, const float *grad, float *m, float *v, float lr, float beta1,
+                float beta2, float eps, int32_t t) {
+  if (n < 1 || !theta || !grad || !m || !v || t < 1) return PR_EINVAL;
+  if (!(beta1 >= 0.0f) || !(beta1 < 1.0f) || !(beta2 >= 0.0f) || !(beta2 < 1.0f) || !(eps > 0.0f) || !isfinite(lr))
+    return PR_EINVAL;
+  POD_HIP(launch_adam(static_cast<hipStream_t>(hip_stream), n, theta, grad, m, v, lr, beta1, beta2, eps, t));
+  return PR_OK;
+}
+
+int ppo_learner_step(void *hip_stream, const pr_ppo_config *cfg, const float *obs, const float *act_raw,
+                     const float *logp_old, const float *adv, const float *ret, const int32_t *rows,
+                     const pr_net_params *actor, const pr_net_params *critic, const pr_net_params *m_actor,
+                     const pr_net_params *v_actor, const pr_net_params *m_critic, const pr_net_params *v_critic,
+                     void *workspace, size_t workspace_bytes, float *stats) {
+  const int rc = ppo_config_ok(cfg);
+  if (rc != PR_OK) return rc;
+  if (!net_ok(m_actor) || !net_ok(v_actor) || !net_ok(m_critic) || !net_ok(v_critic) || !net_ok(actor) ||
+      !net_ok(critic) || !workspace)
+    return PR_EINVAL;
+  if (cfg->adam_step < 1 || !(cfg->beta1 >= 0.0f) || !(cfg->beta1 < 1.0f) || !(cfg->beta2 >= 0.0f) ||
+      !(cfg->beta2 < 1.0f) || !(cfg->adam_eps > 0.0f) || !isfinite(cfg->lr))
+    return PR_EINVAL;
+  const size_t scratch = ppo_scratch_bytes(cfg->batch, cfg->hidden, cfg->n_stocks);
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < scratch + grads_bytes(*cfg)) return PR_EINVAL;
+  // gradients behind the scratch, tensor by tensor
+  unsigned char *p = static_cast<unsigned char *>(workspace) + scratch;
+  int64_t na[6], nc[6];
+  net_sizes(*cfg, cfg->n_stocks, na);
+  net_sizes(*cfg, 1, nc);
+  float *ga[6], *gc[6];
+  for (int i = 0; i < 6; ++i) {
+    ga[i] = reinterpret_cast<float *>(p);
+    p += align_up((size_t)na[i] * 4, 256);
+  }
+  for (int i = 0; i < 6; ++i) {
+    gc[i] = reinterpret_cast<float *>(p);
+    p += align_up((size_t)nc[i] * 4, 256);
+  }
+  const pr_net_params gpa = {ga[0], ga[1], ga[2], ga[3], ga[4], ga[5]}, gpc = {gc[0], gc[1], gc[2], gc[3], gc[4], gc[5]};
+  int r2 = ppo_minibatch_grads(hip_stream, cfg, obs, act_raw, logp_old, adv, ret, rows, actor, critic, &gpa, &gpc,
+                               workspace, workspace_bytes, stats);
+  if (r2 != PR_OK) return r2;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  float *const *ta = &actor->W1, *const *tc = &critic->W1;
+  float *const *ma = &m_actor->W1, *const *va = &v_actor->W1, *const *mc = &m_critic->W1, *const *vc = &v_critic->W1;
+  for (int i = 0; i < 6; ++i) {
+    POD_HIP(launch_adam(st, na[i], ta[i], ga[i], ma[i], va[i], cfg->lr, cfg->beta1, cfg->beta2, cfg->adam_eps,
+                        cfg->adam_step));
+    POD_HIP(launch_adam(st, nc[i], tc[i], gc[i], mc[i], vc[i], cfg->lr, cfg->beta1, cfg->beta2, cfg->adam_eps,
+                        cfg->adam_step));
+  }
+  return PR_OK;
+}
+
 int rollout_leaderboard(pr_handle *h, double *score_mean, double *score_var, int32_t *rank) {
   if (!h || !score_mean || !score_var || !rank) return PR_EINVAL;
   POD_HIP(launch_leaderboard(h->stream, h->cfg.n_envs, h->cfg.n_agents, h->st, nullptr, score_mean, score_var, rank));

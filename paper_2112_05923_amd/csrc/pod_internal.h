@@ -58,6 +58,13 @@ hipError_t launch_trading_metrics(hipStream_t st, int32_t T, int32_t N, int32_t 
                                   double *metrics, int32_t *length);
 hipError_t launch_population_refill(hipStream_t st, int32_t P, int64_t count, const int32_t *rank, int32_t keep,
                                     float sigma, const float *noise, float *params);
+size_t ppo_scratch_bytes(int B, int Hd, int D);
+hipError_t launch_ppo_grads(hipStream_t st, const pr_ppo_config &c, const float *obs, const float *act,
+                            const float *logp_old, const float *adv, const float *ret, const int32_t *rows,
+                            const pr_net_params &actor, const pr_net_params &critic, const pr_net_params &ga,
+                            const pr_net_params &gc, void *scratch, float *stats);
+hipError_t launch_adam(hipStream_t st, int64_t n, float *theta, const float *g, float *m, float *v, float lr, float b1,
+                       float b2, float eps, int32_t t);
 hipError_t launch_gae(hipStream_t st, int32_t T, int32_t N, const float *reward, const float *value,
                       const uint8_t *done, float gamma, float lambda, float *adv, float *ret);
 

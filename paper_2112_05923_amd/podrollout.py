@@ -22,7 +22,18 @@ PR_NET_ACTOR, PR_NET_CRITIC = 0, 1
 
 EXPORTS = ["rollout_workspace_bytes", "rollout_init", "rollout_set_weights", "rollout_reset", "rollout_step_T",
            "rollout_step_forced", "rollout_mlp_forward", "rollout_get_state", "rollout_set_state", "compute_gae",
-           "trading_metrics", "population_refill", "rollout_leaderboard", "rollout_destroy", "rollout_strerror", "rollout_last_hip_error"]
+           "trading_metrics", "population_refill", "ppo_workspace_bytes",
+           "ppo_minibatch_grads", "adam_update", "ppo_learner_step", "rollout_leaderboard", "rollout_destroy", "rollout_strerror", "rollout_last_hip_error"]
+
+
+class PrPpoConfig(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_stocks", C.c_int32), ("n_ind", C.c_int32), ("hidden", C.c_int32),
+                ("sigma", C.c_float), ("clip", C.c_float), ("value_coef", C.c_float), ("lr", C.c_float),
+                ("beta1", C.c_float), ("beta2", C.c_float), ("adam_eps", C.c_float), ("adam_step", C.c_int32)]
+
+
+class PrNetParams(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in ("W1", "b1", "W2", "b2", "W3", "b3")]
 
 
 class PrConfig(C.Structure):
@@ -88,6 +99,14 @@ def lib():
                                       C.POINTER(C.c_float), C.c_double, C.c_double, C.c_void_p, C.c_void_p]
         l.population_refill.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_int32, C.c_float, C.c_void_p,
                                         C.c_void_p]
+        NP = C.POINTER(PrNetParams)
+        l.ppo_workspace_bytes.argtypes = [C.POINTER(PrPpoConfig), C.POINTER(C.c_size_t)]
+        l.ppo_minibatch_grads.argtypes = [C.c_void_p, C.POINTER(PrPpoConfig)] + [C.c_void_p] * 6 + [NP] * 4 + [
+            C.c_void_p, C.c_size_t, C.c_void_p]
+        l.adam_update.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float,
+                                  C.c_float, C.c_float, C.c_float, C.c_int32]
+        l.ppo_learner_step.argtypes = [C.c_void_p, C.POINTER(PrPpoConfig)] + [C.c_void_p] * 6 + [NP] * 6 + [
+            C.c_void_p, C.c_size_t, C.c_void_p]
         l.rollout_leaderboard.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         l.rollout_destroy.argtypes = [C.c_void_p]
         _lib = l
@@ -317,3 +336,84 @@ def population_refill(params: torch.Tensor, rank: torch.Tensor, keep: int, sigma
                                    float(sigma), None if noise is None else _dev(noise, torch.float32, shape, "noise"),
                                    _dev(params, torch.float32, shape, "params")), "population_refill")
     return params
+
+
+# ------------------------------------------------------------------ learner
+
+NET_KEYS = ("W1", "b1", "W2", "b2", "W3", "b3")
+
+
+def make_ppo_config(w, batch: int = 1024, clip: float = 0.2, value_coef: float = 0.5, lr: float = 1e-3,
+                    beta1: float = 0.9, beta2: float = 0.999, adam_eps: float = 1e-8, adam_step: int = 1) -> PrPpoConfig:
+    """Batch size and learning rate default to the paper's (Sec. 5.2)."""
+    return PrPpoConfig(batch, w.n_stocks, w.n_ind, w.hidden, w.sigma, clip, value_coef, lr, beta1, beta2, adam_eps,
+                       adam_step)
+
+
+def _net_shapes(cfg: PrPpoConfig, out_dim: int):
+    S, Hd = 1 + 2 * cfg.n_stocks + cfg.n_stocks * cfg.n_ind, cfg.hidden
+    return {"W1": (S, Hd), "b1": (Hd,), "W2": (Hd, Hd), "b2": (Hd,), "W3": (Hd, out_dim), "b3": (out_dim,)}
+
+
+def _net_struct(net: Dict[str, torch.Tensor], cfg: PrPpoConfig, out_dim: int, what: str) -> PrNetParams:
+    shp = _net_shapes(cfg, out_dim)
+    return PrNetParams(*[_dev(net[k], torch.float32, shp[k], f"{what}.{k}") for k in NET_KEYS])
+
+
+def ppo_workspace(cfg: PrPpoConfig, device) -> torch.Tensor:
+    n = C.c_size_t(0)
+    _check(lib().ppo_workspace_bytes(C.byref(cfg), C.byref(n)), "ppo_workspace_bytes")
+    return torch.empty(n.value + 256, dtype=torch.uint8, device=device)
+
+
+def _aligned_ptr(ws: torch.Tensor):
+    p = (ws.data_ptr() + 255) // 256 * 256
+    return p, ws.numel() - (p - ws.data_ptr())
+
+
+def _batch_args(cfg, obs, act_raw, logp_old, adv, ret, rows):
+    R = obs.shape[0]
+    S, D = 1 + 2 * cfg.n_stocks + cfg.n_stocks * cfg.n_ind, cfg.n_stocks
+    return [_dev(obs, torch.float32, (R, S), "obs"), _dev(act_raw, torch.float32, (R, D), "act_raw"),
+            _dev(logp_old, torch.float32, (R,), "logp_old"), _dev(adv, torch.float32, (R,), "adv"),
+            _dev(ret, torch.float32, (R,), "ret"),
+            None if rows is None else _dev(rows, torch.int32, (cfg.batch,), "rows")]
+
+
+def ppo_minibatch_grads(cfg: PrPpoConfig, obs, act_raw, logp_old, adv, ret, rows, actor, critic, workspace=None):
+    """Gradients of the PPO objective for one minibatch: (grads_actor, grads_critic, stats[4]) as device tensors."""
+    dev = obs.device
+    ws = ppo_workspace(cfg, dev) if workspace is None else workspace
+    ptr, nbytes = _aligned_ptr(ws)
+    ga = {k: torch.empty(v, dtype=torch.float32, device=dev) for k, v in _net_shapes(cfg, cfg.n_stocks).items()}
+    gc = {k: torch.empty(v, dtype=torch.float32, device=dev) for k, v in _net_shapes(cfg, 1).items()}
+    stats = torch.empty(4, dtype=torch.float32, device=dev)
+    sa, sc = _net_struct(actor, cfg, cfg.n_stocks, "actor"), _net_struct(critic, cfg, 1, "critic")
+    sga, sgc = _net_struct(ga, cfg, cfg.n_stocks, "grad_actor"), _net_struct(gc, cfg, 1, "grad_critic")
+    _check(lib().ppo_minibatch_grads(_stream_ptr(), C.byref(cfg), *_batch_args(cfg, obs, act_raw, logp_old, adv, ret, rows),
+                                     C.byref(sa), C.byref(sc), C.byref(sga), C.byref(sgc), ptr, nbytes,
+                                     stats.data_ptr()), "ppo_minibatch_grads")
+    return ga, gc, stats
+
+
+def adam_update(theta, grad, m, v, lr, beta1, beta2, eps, t):
+    n = theta.numel()
+    shp = tuple(theta.shape)
+    _check(lib().adam_update(_stream_ptr(), n, _dev(theta, torch.float32, shp, "theta"),
+                             _dev(grad, torch.float32, shp, "grad"), _dev(m, torch.float32, shp, "m"),
+                             _dev(v, torch.float32, shp, "v"), lr, beta1, beta2, eps, int(t)), "adam_update")
+    return theta
+
+
+def ppo_learner_step(cfg: PrPpoConfig, obs, act_raw, logp_old, adv, ret, rows, actor, critic, m_actor, v_actor,
+                     m_critic, v_critic, workspace):
+    """One optimiser step in place on actor / critic and their Adam moments; returns stats[4] (device)."""
+    ptr, nbytes = _aligned_ptr(workspace)
+    stats = torch.empty(4, dtype=torch.float32, device=obs.device)
+    D = cfg.n_stocks
+    st = [_net_struct(actor, cfg, D, "actor"), _net_struct(critic, cfg, 1, "critic"),
+          _net_struct(m_actor, cfg, D, "m_actor"), _net_struct(v_actor, cfg, D, "v_actor"),
+          _net_struct(m_critic, cfg, 1, "m_critic"), _net_struct(v_critic, cfg, 1, "v_critic")]
+    _check(lib().ppo_learner_step(_stream_ptr(), C.byref(cfg), *_batch_args(cfg, obs, act_raw, logp_old, adv, ret, rows),
+                                  *[C.byref(x) for x in st], ptr, nbytes, stats.data_ptr()), "ppo_learner_step")
+    return stats

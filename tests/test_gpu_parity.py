@@ -634,3 +634,102 @@ def test_rollout_and_gae_replay_from_a_captured_graph(schedule):
             side.synchronize()
             for k in st:
                 assert torch.equal(st[k], want_state[k]), (rep, k)
+
+
+# ------------------------------------------------------------------ learner
+
+def _ppo_case(w, B, R, seed):
+    """A minibatch drawn from a synthetic buffer of R transitions with the workload's network shapes; the old
+    log-probs are scattered around the new ones so that both branches of the clipped surrogate are live."""
+    rng = np.random.default_rng(seed)
+    S, D = w.state_dim, w.n_stocks
+    nets = {k: {kk: vv[0] for kk, vv in inputs.make_weights(w, critic=(k == "critic")).items()} for k in ("actor", "critic")}
+    obs = rng.standard_normal((R, S)).astype(np.float32)
+    obs[:, 0] *= 0.5
+    mu = oracle.mlp(obs, *[nets["actor"][k] for k in oracle.NET_KEYS], True, False)
+    act = (mu + w.sigma * rng.standard_normal((R, D))).astype(np.float32)
+    logp = (-(act - mu) ** 2 / (2 * w.sigma ** 2)).sum(1) - D * np.log(w.sigma) - 0.5 * D * np.log(2 * np.pi)
+    logp_old = (logp + rng.normal(0, 0.25, R)).astype(np.float32)
+    adv = rng.standard_normal(R).astype(np.float32)
+    ret = rng.standard_normal(R).astype(np.float32)
+    rows = rng.permutation(R)[:B].astype(np.int32)
+    return nets, obs, act, logp_old, adv, ret, rows
+
+
+def _rel(got, want):
+    return float(np.abs(got.astype(np.float64) - want).max() / max(np.abs(want).max(), 1e-30))
+
+
+@pytest.mark.parametrize("name,B,R,use_rows", [("tiny", 96, 200, True), ("dow30", 1024, 1500, True),
+                                               ("large", 1024, 1024, False), ("tiny", 1, 3, True)])
+def test_ppo_minibatch_gradients_match_checker(name, B, R, use_rows):
+    w = inputs.WORKLOADS[name]
+    nets, obs, act, logp_old, adv, ret, rows = _ppo_case(w, B, R, seed=B + R)
+    sel = rows if use_rows else np.arange(B)
+    ga, gc, stats, margin = oracle.ppo_grads(obs[sel], act[sel], logp_old[sel], adv[sel], ret[sel], nets["actor"],
+                                             nets["critic"], w.sigma, 0.2, 0.5)
+    # samples whose ratio sits on a clip bound may take the other branch of min() in fp32: none here
+    assert margin.min() > 2e-5
+    cfg = pr.make_ppo_config(w, batch=B)
+    t = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
+    dga, dgc, dstats = pr.ppo_minibatch_grads(cfg, t(obs), t(act), t(logp_old), t(adv), t(ret),
+                                              t(rows) if use_rows else None, _dev(nets["actor"]), _dev(nets["critic"]))
+    torch.cuda.synchronize()
+    # fp32 products and sums against fp64: tensor-wise, relative to the largest entry (entries cancel to zero)
+    for k in oracle.NET_KEYS:
+        assert _rel(parity.to_np(dga[k]), ga[k]) <= parity.TOL_F32, ("actor", k)
+        assert _rel(parity.to_np(dgc[k]), gc[k]) <= parity.TOL_F32, ("critic", k)
+    np.testing.assert_allclose(parity.to_np(dstats), stats, rtol=2e-4, atol=1e-6)
+    if B >= 96:
+        assert 0.05 < stats[2] < 0.95
+
+
+def test_adam_update_matches_checker_over_three_steps():
+    rng = np.random.default_rng(8)
+    n = 70001
+    th = rng.standard_normal(n).astype(np.float32)
+    d_th, d_m, d_v = torch.from_numpy(th.copy()).to(DEV), torch.zeros(n, device=DEV), torch.zeros(n, device=DEV)
+    o_th, o_m, o_v = th.astype(np.float64), np.zeros(n), np.zeros(n)
+    gmax = np.zeros(n)
+    for step in (1, 2, 3):
+        g = (rng.standard_normal(n) * 10.0 ** rng.uniform(-4, 1, n)).astype(np.float32)
+        gmax = np.maximum(gmax, np.abs(g))
+        pr.adam_update(d_th, torch.from_numpy(g).to(DEV), d_m, d_v, 1e-3, 0.9, 0.999, 1e-8, step)
+        o_th, o_m, o_v = oracle.adam(o_th, g, o_m, o_v, 1e-3, 0.9, 0.999, 1e-8, step)
+    torch.cuda.synchronize()
+    # the moments are short sums of terms of either sign: errors scale with the terms, not with the result
+    assert np.all(np.abs(parity.to_np(d_m) - o_m) <= 1e-6 * gmax)
+    assert np.all(np.abs(parity.to_np(d_v) - o_v) <= 1e-6 * gmax ** 2)
+    # three steps of size <= lr each: compare the movement, not the (much larger) parameter
+    # (each step also rounds the fp32 parameter itself: up to half a spacing of theta per step)
+    moved, want = parity.to_np(d_th).astype(np.float64) - th, o_th - th
+    assert np.all(np.abs(moved - want) <= 1e-3 * np.abs(want) + 2.0 * np.spacing(np.abs(th) + 1e-2))
+
+
+def test_ppo_learner_step_updates_both_networks_like_the_checker():
+    w = inputs.WORKLOADS["dow30"]
+    B, R = 512, 700
+    nets, obs, act, logp_old, adv, ret, rows = _ppo_case(w, B, R, seed=77)
+    cfg = pr.make_ppo_config(w, batch=B, adam_step=1)
+    t = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
+    dn = {k: _dev(nets[k]) for k in nets}
+    zeros = lambda net: {k: torch.zeros_like(v) for k, v in net.items()}
+    mom = {k: (zeros(dn[k]), zeros(dn[k])) for k in dn}
+    ws = pr.ppo_workspace(cfg, DEV)
+    data = (t(obs), t(act), t(logp_old), t(adv), t(ret), t(rows))
+    pr.ppo_learner_step(cfg, *data, dn["actor"], dn["critic"], mom["actor"][0], mom["actor"][1], mom["critic"][0],
+                        mom["critic"][1], ws)
+    torch.cuda.synchronize()
+    ga, gc, _, _ = oracle.ppo_grads(obs[rows], act[rows], logp_old[rows], adv[rows], ret[rows], nets["actor"],
+                                    nets["critic"], w.sigma, cfg.clip, cfg.value_coef)
+    for which, g in (("actor", ga), ("critic", gc)):
+        for k in oracle.NET_KEYS:
+            th, m, v = oracle.adam(nets[which][k].astype(np.float64), g[k], np.zeros_like(g[k]), np.zeros_like(g[k]),
+                                   cfg.lr, cfg.beta1, cfg.beta2, cfg.adam_eps, 1)
+            moved = parity.to_np(dn[which][k]).astype(np.float64) - nets[which][k]
+            want = th - nets[which][k]
+            # the first Adam step is lr * g / (|g| + eps): entries whose gradient is far above eps move by lr
+            big = np.abs(g[k]) > 1e-4 * np.abs(g[k]).max()
+            assert np.all(np.abs(moved[big] - want[big]) <= 2e-3 * np.abs(want[big]) +
+                          np.spacing(np.abs(nets[which][k][big]) + np.float32(1e-2))), (which, k)
+            assert _rel(parity.to_np(mom[which][0][k]), m) <= parity.TOL_F32, (which, k)

@@ -89,6 +89,13 @@ def test_null_arguments_are_rejected_without_device_work():
     assert lib.compute_gae(None, 4, 4, None, None, None, 0.99, 0.95, None, None) == pr.PR_EINVAL
     assert lib.trading_metrics(None, 4, 4, 3, 13, None, None, None, 252.0, 0.0, None, None) == pr.PR_EINVAL
     assert lib.population_refill(None, 4, 16, None, 2, 0.0, None, None) == pr.PR_EINVAL
+    cfg = pr.PrPpoConfig(1024, 30, 8, 512, 0.5, 0.2, 0.5, 1e-3, 0.9, 0.999, 1e-8, 1)
+    n = C.c_size_t(0)
+    assert lib.ppo_workspace_bytes(C.byref(cfg), C.byref(n)) == pr.PR_OK and n.value > 4 * 1024 * 512 * 4
+    bad = pr.PrPpoConfig(1024, 30, 8, 500, 0.5, 0.2, 0.5, 1e-3, 0.9, 0.999, 1e-8, 1)
+    assert lib.ppo_workspace_bytes(C.byref(bad), C.byref(n)) == pr.PR_EINVAL
+    assert lib.adam_update(None, 0, None, None, None, None, 1e-3, 0.9, 0.999, 1e-8, 1) == pr.PR_EINVAL
+    assert lib.ppo_minibatch_grads(None, C.byref(cfg), *([None] * 6), *([None] * 4), None, 0, None) == pr.PR_EINVAL
 
 
 def test_missing_library_fails_loudly(monkeypatch):
