@@ -460,15 +460,17 @@ int ppo_learner_step(void *hip_stream, const pr_ppo_config *cfg, const float *ob
   int r2 = ppo_minibatch_grads(hip_stream, cfg, obs, act_raw, logp_old, adv, ret, rows, actor, critic, &gpa, &gpc,
                                workspace, workspace_bytes, stats);
   if (r2 != PR_OK) return r2;
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  // one launch for the twelve tensors
+  int64_t n12[12];
+  float *th[12], *gg[12], *mm[12], *vv[12];
   float *const *ta = &actor->W1, *const *tc = &critic->W1;
   float *const *ma = &m_actor->W1, *const *va = &v_actor->W1, *const *mc = &m_critic->W1, *const *vc = &v_critic->W1;
   for (int i = 0; i < 6; ++i) {
-    POD_HIP(launch_adam(st, na[i], ta[i], ga[i], ma[i], va[i], cfg->lr, cfg->beta1, cfg->beta2, cfg->adam_eps,
-                        cfg->adam_step));
-    POD_HIP(launch_adam(st, nc[i], tc[i], gc[i], mc[i], vc[i], cfg->lr, cfg->beta1, cfg->beta2, cfg->adam_eps,
-                        cfg->adam_step));
+    n12[i] = na[i], th[i] = ta[i], gg[i] = ga[i], mm[i] = ma[i], vv[i] = va[i];
+    n12[6 + i] = nc[i], th[6 + i] = tc[i], gg[6 + i] = gc[i], mm[6 + i] = mc[i], vv[6 + i] = vc[i];
   }
+  POD_HIP(launch_adam12(static_cast<hipStream_t>(hip_stream), n12, th, gg, mm, vv, cfg->lr, cfg->beta1, cfg->beta2,
+                        cfg->adam_eps, cfg->adam_step));
   return PR_OK;
 }
 
