@@ -40,7 +40,8 @@ class Cfg(C.Structure):
 
 class _State(C.Structure):
     _fields_ = [("cash", C.c_void_p), ("h", C.c_void_p), ("tau", C.c_void_p), ("asset", C.c_void_p),
-                ("ep_ret", C.c_void_p), ("ep_sum", C.c_void_p), ("ep_sqsum", C.c_void_p), ("ep_cnt", C.c_void_p)]
+                ("ep_ret", C.c_void_p), ("ep_sum", C.c_void_p), ("ep_sqsum", C.c_void_p), ("ep_cnt", C.c_void_p),
+                ("start", C.c_void_p)]
 
 
 _lib = None
@@ -144,9 +145,12 @@ def asset(cash: float, h, p) -> float:
 class State:
     """Persistent per-env state (cash, holdings, cursor, asset, episode sums)."""
 
-    def __init__(self, cfg: Cfg, n_envs: int):
+    def __init__(self, cfg: Cfg, n_envs: int, start=None):
+        """start: per-env table row where every episode of the env begins (None = row 0)."""
         D = cfg.n_stocks
         self.n_envs = n_envs
+        self.start = np.zeros(n_envs, dtype=np.int32) if start is None else np.array(start, dtype=np.int32)
+        assert self.start.shape == (n_envs,) and (self.start >= 0).all()
         self.cash = np.empty(n_envs, dtype=np.float32)
         self.h = np.empty((n_envs, D), dtype=np.int32)
         self.tau = np.empty(n_envs, dtype=np.int32)
@@ -198,9 +202,10 @@ def rollout(cfg: Cfg, hidden: int, bf16: bool, T: int, price, ind, noise, actor=
     N, D = noise.shape[1], cfg.n_stocks
     M = price.shape[1]
     S = 1 + 2 * D + D * cfg.n_ind
-    assert noise.shape == (T, N, D) and price.shape[0] >= cfg.horizon + 1 and ind.shape[:2] == price.shape[:2]
+    assert noise.shape == (T, N, D) and ind.shape[:2] == price.shape[:2]
     if state is None:
         state = State(cfg, N)
+    assert price.shape[0] >= int(state.start.max()) + cfg.horizon + 1
     agent_of = np.zeros(N, dtype=np.int32) if agent_of is None else np.ascontiguousarray(agent_of, dtype=np.int32)
     if market_of is None:
         market_of = np.arange(N, dtype=np.int32) % M

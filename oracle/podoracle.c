@@ -48,7 +48,7 @@
 typedef struct orc_cfg {
   int32_t n_stocks;     /* D */
   int32_t n_ind;        /* K indicators per stock */
-  int32_t horizon;      /* H: an episode ends when the cursor reaches H */
+  int32_t horizon;      /* H: an episode ends H steps after its start row */
   float cash0;          /* initial capital */
   float hmax;           /* largest trade per stock and step, in shares */
   float cost;           /* proportional transaction cost c */
@@ -237,12 +237,15 @@ typedef struct orc_state {
   double *asset;
   double *ep_ret, *ep_sum, *ep_sqsum;
   int32_t *ep_cnt;
+  int32_t *start; /* table row every episode of the env begins at (replay of one historical table from per-env
+                     offsets, Sec. 5.3 data; 0 everywhere is the plain case).  Set by the caller before
+                     orc_reset_state and kept by it. */
 } orc_state;
 
 void orc_reset_state(const orc_cfg *c, int64_t N, orc_state *s) {
   for (int64_t n = 0; n < N; ++n) {
     s->cash[n] = c->cash0;
-    s->tau[n] = 0;
+    s->tau[n] = s->start[n];
     s->asset[n] = (double)c->cash0;
     s->ep_ret[n] = s->ep_sum[n] = s->ep_sqsum[n] = 0.0;
     s->ep_cnt[n] = 0;
@@ -252,9 +255,9 @@ void orc_reset_state(const orc_cfg *c, int64_t N, orc_state *s) {
 
 /* One transition of env n given its raw action: trade at the prices of the
  * current cursor, advance the cursor, value the portfolio at the new prices,
- * reward = rho * (change of account value) (Table 1), episode end when the
- * cursor reaches H, then bookkeeping of the finished episode's return and
- * reset to the initial capital with no shares.  p_now / p_next are the market
+ * reward = rho * (change of account value) (Table 1), episode end after H
+ * steps from the env's start row, then bookkeeping of the finished episode's
+ * return and reset to the initial capital with no shares at the start row.  p_now / p_next are the market
  * rows at the cursor before / after the advance.  Returns the reward. */
 double orc_env_step(const orc_cfg *c, int64_t n, orc_state *s, const float *a_raw, const float *p_now,
                     const float *p_next, int32_t *shares, uint8_t *flags, uint8_t *done_out) {
@@ -266,7 +269,7 @@ double orc_env_step(const orc_cfg *c, int64_t n, orc_state *s, const float *a_ra
   double r = (asset_new - s->asset[n]) * (double)c->reward_scale;
   s->asset[n] = asset_new;
   s->ep_ret[n] += r;
-  uint8_t done = (uint8_t)(s->tau[n] == c->horizon);
+  uint8_t done = (uint8_t)(s->tau[n] - s->start[n] == c->horizon);
   if (done) {
     s->ep_sum[n] += s->ep_ret[n];
     s->ep_sqsum[n] += s->ep_ret[n] * s->ep_ret[n];
@@ -274,7 +277,7 @@ double orc_env_step(const orc_cfg *c, int64_t n, orc_state *s, const float *a_ra
     s->ep_ret[n] = 0.0;
     s->cash[n] = c->cash0;
     for (int d = 0; d < D; ++d) h[d] = 0;
-    s->tau[n] = 0;
+    s->tau[n] = s->start[n];
     s->asset[n] = (double)c->cash0;
   }
   *done_out = done;

@@ -374,3 +374,81 @@ def test_rounded_quotient_never_overspends():
             assert shares.tolist() == [m] and not flags[0] & oracle.FLAG_GUARD, (p, m, cash)
             assert cash2 == np.float32(cash - outlay_m)
     assert hits > 50 and guards > 10, (hits, guards)
+
+
+# ------------------------------------------- replay of one table from per-env start rows (Sec. 5.3 data set-up)
+
+
+def _replay_case(H=6, T=20, N=5, D=3, K=2, rows=40, seed=5):
+    rng = np.random.default_rng(seed)
+    price = rng.uniform(10.0, 100.0, (rows, 1, D)).astype(np.float32)
+    ind = rng.standard_normal((rows, 1, D * K)).astype(np.float32)
+    start = rng.integers(0, rows - H, N).astype(np.int32)
+    start[0], start[1] = 0, rows - H - 1      # both ends of the admissible range
+    return price, ind, start
+
+
+def test_replay_cursor_rows_and_episode_ends_follow_the_start_rows():
+    """No trading (means and noise zero): the observation's price block must be the table row start + (t mod H),
+    read here straight from the table; episodes end every H steps whatever the start row; rewards vanish."""
+    H, T, N, D, K = 6, 20, 5, 3, 2
+    price, ind, start = _replay_case(H, T, N, D, K)
+    cfg = cfg2(D=D, K=K, H=H)
+    st = oracle.State(cfg, N, start=start)
+    z = np.zeros((T, N, D), np.float32)
+    out, st = oracle.rollout(cfg, 8, False, T, price, ind, z, mu_forced=z, state=st)
+    s_price, s_ind = cfg.obs_scale[1], cfg.obs_scale[3]
+    for t in range(T + 1):
+        row = start + t % H
+        assert np.array_equal(out["obs"][t][:, 1:1 + D], price[row, 0] * np.float32(s_price))
+        assert np.array_equal(out["obs"][t][:, 1 + 2 * D:], ind[row, 0] * np.float32(s_ind))
+    want_done = np.array([(t + 1) % H == 0 for t in range(T)], np.uint8)
+    assert np.array_equal(out["done"], np.repeat(want_done[:, None], N, 1))
+    assert (out["reward"] == 0).all()
+    assert np.array_equal(st.tau, start + T % H) and (st.ep_cnt == T // H).all()
+
+
+def test_replay_buy_and_hold_return_closed_form():
+    """Buy 100 shares of stock 0 on the first step of every episode, then hold: the episode's return is
+    rho (100 p[start + H] - 100 p[start] (1 + c)), from the table alone; identical in every episode."""
+    H, T, N, D, K = 6, 18, 5, 3, 2
+    price, ind, start = _replay_case(H, T, N, D, K)
+    c, rho = 2.0 ** -9, 2.0 ** -4
+    cfg = cfg2(D=D, K=K, H=H, cost=c, reward_scale=rho, hmax=100.0)
+    mu = np.zeros((T, N, D), np.float32)
+    mu[0::H, :, 0] = 1.0
+    st = oracle.State(cfg, N, start=start)
+    out, st = oracle.rollout(cfg, 8, False, T, price, ind, np.zeros_like(mu), mu_forced=mu, state=st)
+    p = price[:, 0, 0].astype(np.float64)
+    want = rho * (100.0 * p[start + H] - 100.0 * p[start] * (1.0 + c))
+    ep = out["reward"].reshape(T // H, H, N).sum(1)
+    # cash is binary32: near 1e6 its spacing is 1/16, so the purchase books at most 1/16 off the exact outlay
+    tol = rho * 0.0625
+    np.testing.assert_allclose(ep, np.repeat(want[None], T // H, 0), rtol=0, atol=tol)
+    np.testing.assert_allclose(st.ep_sum, want * (T // H), rtol=0, atol=tol * (T // H))
+    # per-step rewards after the purchase: rho * 100 * price change along the env's own rows
+    for t in range(1, H):
+        np.testing.assert_allclose(out["reward"][t], rho * 100.0 * (p[start + t + 1] - p[start + t]), rtol=0, atol=1e-9)
+
+
+def test_replay_equals_plain_rollout_on_the_sliced_table():
+    """Definition of the replay: env n started at row s_n on the shared table behaves exactly like an env with a
+    private market made of rows s_n .. s_n + H of that table (the plain case pinned above)."""
+    w = inputs.WORKLOADS["tiny"]
+    H, T, N = 8, 30, w.n_envs
+    d = inputs.make_all(w, horizon=47, n_market=1, steps=T)
+    rng = np.random.default_rng(11)
+    start = rng.integers(0, 47 - H + 1, N).astype(np.int32)
+    cfg = oracle.cfg_from_workload(w, horizon=H)
+    st = oracle.State(cfg, N, start=start)
+    a, st = oracle.rollout(cfg, w.hidden, False, T, d["price"], d["ind"], d["noise"], actor=d["actor"],
+                           critic=d["critic"], state=st)
+    rows = start[None, :] + np.arange(H + 1)[:, None]                     # [H+1, N]
+    price_n = np.ascontiguousarray(d["price"][rows, 0])                  # [H+1, N, D]
+    ind_n = np.ascontiguousarray(d["ind"][rows, 0])
+    b, st_b = oracle.rollout(cfg, w.hidden, False, T, price_n, ind_n, d["noise"], actor=d["actor"], critic=d["critic"])
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    assert np.array_equal(st.tau - start, st_b.tau) and np.array_equal(st.cash, st_b.cash)
+    assert np.array_equal(st.ep_sum, st_b.ep_sum) and np.array_equal(st.h, st_b.h)
+    assert a["done"].sum() == N * (T // H) and np.abs(a["shares"]).sum() > 0
