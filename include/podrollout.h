@@ -109,7 +109,8 @@ typedef struct pr_buffers {
 typedef struct pr_state {
   float *cash;       /* [N]    */
   int32_t *holdings; /* [N, D] */
-  int32_t *cursor;   /* [N]    market row of the current observation, 0 <= tau < H */
+  int32_t *cursor;   /* [N]    market row of the current observation, start_n <= tau < start_n + H
+                                (start_n = 0 unless rollout_set_replay gave start rows)      */
   double *ep_return; /* [N]    return accumulated in the running episode           */
   double *ep_sum;    /* [N]    sum of the returns of finished episodes             */
   double *ep_sqsum;  /* [N]    sum of their squares                                */
@@ -137,8 +138,20 @@ int rollout_init(const pr_config *cfg, const pr_market *market, const pr_weights
 /* Replace both networks (a new policy for the same envs); env state is kept. */
 int rollout_set_weights(pr_handle *h, const pr_weights *actor, const pr_weights *critic);
 
-/* All envs back to cash0, no shares, cursor 0; episode statistics cleared. */
+/* All envs back to cash0, no shares, cursor at their start row (0 unless
+ * rollout_set_replay gave others); episode statistics cleared. */
 int rollout_reset(pr_handle *h);
+
+/* Replay of one long historical table from per-env start rows (Sec. 5.3: every
+ * env trades the same minute-level data set; Sec. 4.2 vectorised sub-environments).
+ * table: price [table_rows, M, D], ind [table_rows, M, D*K] (device; same M, D, K as
+ * the config; M = 1 is the shared-table case).  start: device [N], copied.  From now
+ * on env n's episodes run over rows start_n .. start_n + H: done after H steps, then
+ * back to cash0, no shares, cursor start_n.  Requires table_rows >= H + 1 and
+ * 0 <= start_n <= table_rows - 1 - H for every env (checked on the device; the call
+ * synchronises the stream), else PR_EINVAL and nothing changes.  Resets all envs
+ * like rollout_reset.  Do not call during stream capture. */
+int rollout_set_replay(pr_handle *h, const pr_market *table, int32_t table_rows, const int32_t *start);
 
 /* T steps of agent-environment interaction for all N envs (Sec. 4.2 worker;
  * Table 1 stock trading):

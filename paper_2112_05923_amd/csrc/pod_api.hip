@@ -21,6 +21,7 @@ struct pr_handle {
   void *w_packed[2][3];   // device, per net and layer
   float *b_packed[2][3];
   float *mu_scratch;      // [N, D]
+  int32_t *start;         // [N] episode start rows (zeros unless a replay table is set)
   int32_t S;
 };
 
@@ -50,7 +51,7 @@ bool is_pow2_float(float x) {
 struct Layout {
   size_t w[2][3], b[2][3];
   size_t w1_fused;
-  size_t cash, tau, h, ep_ret, ep_sum, ep_sqsum, ep_cnt, mu;
+  size_t cash, tau, h, ep_ret, ep_sum, ep_sqsum, ep_cnt, mu, start;
   size_t total;
 };
 
@@ -108,6 +109,7 @@ Layout make_layout(const pr_config &c) {
   L.ep_sqsum = take(N * 8);
   L.ep_cnt = take(N * 4);
   L.mu = take(N * D * 4);
+  L.start = take(N * 4);
   L.total = off;
   return L;
 }
@@ -221,6 +223,8 @@ int rollout_init(const pr_config *cfg, const pr_market *market, const pr_weights
   h->st.ep_sqsum = reinterpret_cast<double *>(ws + L.ep_sqsum);
   h->st.ep_cnt = reinterpret_cast<int32_t *>(ws + L.ep_cnt);
   h->mu_scratch = reinterpret_cast<float *>(ws + L.mu);
+  h->start = reinterpret_cast<int32_t *>(ws + L.start);
+  h->st.start = h->start;
 
   EnvDims &d = h->dims;
   d.N = cfg->n_envs;
@@ -248,7 +252,8 @@ int rollout_init(const pr_config *cfg, const pr_market *market, const pr_weights
   fill_net(h->critic, h, 1);
   int prc = pack_nets(h, actor, critic);
   if (prc == PR_OK) {
-    hipError_t e = launch_state_reset(h->stream, h->dims, h->st);
+    hipError_t e = hipMemsetAsync(h->start, 0, (size_t)cfg->n_envs * 4, h->stream);
+    if (e == hipSuccess) e = launch_state_reset(h->stream, h->dims, h->st);
     if (e != hipSuccess) prc = hip_fail(e);
   }
   if (prc != PR_OK) {
@@ -266,6 +271,22 @@ int rollout_set_weights(pr_handle *h, const pr_weights *actor, const pr_weights 
 
 int rollout_reset(pr_handle *h) {
   if (!h) return PR_EINVAL;
+  POD_HIP(launch_state_reset(h->stream, h->dims, h->st));
+  return PR_OK;
+}
+
+int rollout_set_replay(pr_handle *h, const pr_market *table, int32_t table_rows, const int32_t *start) {
+  if (!h || !table || !table->price || (h->cfg.n_ind > 0 && !table->ind) || !start) return PR_EINVAL;
+  if (table_rows < h->cfg.horizon + 1 || (double)table_rows * h->cfg.n_market >= 2147483647.0) return PR_EINVAL;
+  if (h->cfg.schedule == PR_SCHED_FUSED && (reinterpret_cast<uintptr_t>(table->ind) & 15u)) return PR_EINVAL;
+  // every episode must stay inside the table: checked on the device, read back here (this call synchronises)
+  int32_t *flag = reinterpret_cast<int32_t *>(h->mu_scratch), bad = 1;
+  POD_HIP(launch_check_starts(h->stream, h->cfg.n_envs, h->cfg.horizon, table_rows, start, flag));
+  POD_HIP(hipMemcpyAsync(&bad, flag, sizeof(bad), hipMemcpyDeviceToHost, h->stream));
+  POD_HIP(hipStreamSynchronize(h->stream));
+  if (bad) return PR_EINVAL;
+  POD_HIP(hipMemcpyAsync(h->start, start, (size_t)h->cfg.n_envs * 4, hipMemcpyDeviceToDevice, h->stream));
+  h->market = *table;
   POD_HIP(launch_state_reset(h->stream, h->dims, h->st));
   return PR_OK;
 }

@@ -22,13 +22,13 @@ struct RowInfo {
   int32_t done;
 };
 
-__device__ inline RowInfo rows_of(const EnvDims &d, int32_t tau, int32_t n) {
+__device__ inline RowInfo rows_of(const EnvDims &d, int32_t tau, int32_t start, int32_t n) {
   const int32_t m = d.M == 1 ? 0 : n;
   RowInfo r;
   r.row_now = tau * d.M + m;
   r.row_val = (tau + 1) * d.M + m;
-  r.done = (tau + 1 == d.H);
-  r.row_obs = r.done ? m : r.row_val;
+  r.done = (tau + 1 - start == d.H);
+  r.row_obs = r.done ? start * d.M + m : r.row_val;
   return r;
 }
 
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kEnvThreads) void env_step_kernel(EnvDims d, EnvSta
   const int n0 = blockIdx.x * E;
   const int ne = min(E, d.N - n0);  // live envs of this tile
 
-  if (tid < ne) s_row[tid] = rows_of(d, s.tau[n0 + tid], n0 + tid);
+  if (tid < ne) s_row[tid] = rows_of(d, s.tau[n0 + tid], s.start[n0 + tid], n0 + tid);
   for (int dd = wave; dd < D; dd += NWV)
     for (int e = lane; e < ne; e += 64) s_h[e * Dp + dd] = s.h[(size_t)dd * d.N + n0 + e];
   __syncthreads();
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(kEnvThreads) void env_step_kernel(EnvDims d, EnvSta
       }
       s.ep_ret[n] = ep;
       s.cash[n] = cash;
-      s.tau[n] = ri.done ? 0 : s.tau[n] + 1;
+      s.tau[n] = ri.done ? s.start[n] : s.tau[n] + 1;
       s_cash[e] = cash;
       io.reward[n] = (float)r;
       io.done[n] = (uint8_t)ri.done;
@@ -246,11 +246,23 @@ size_t env_lds(int E, int D) {
 }
 
 // ------------------------------------------------------------ state plumbing
+// *bad = 1 unless every env's episode rows start .. start + H lie inside a table of `rows` rows.
+__global__ __launch_bounds__(256) void check_starts_kernel(int32_t N, int32_t H, int32_t rows,
+                                                           const int32_t *__restrict__ start, int32_t *bad) {
+  int flag = 0;
+  for (int i = threadIdx.x; i < N; i += 256) {
+    const int32_t s = start[i];
+    flag |= (s < 0 || s > rows - 1 - H);
+  }
+  flag = __syncthreads_or(flag);
+  if (threadIdx.x == 0) *bad = flag;
+}
+
 __global__ void state_reset_kernel(EnvDims d, EnvState s) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < (size_t)d.N) {
     s.cash[i] = d.cash0;
-    s.tau[i] = 0;
+    s.tau[i] = s.start[i];
     s.ep_ret[i] = 0.0;
     s.ep_sum[i] = 0.0;
     s.ep_sqsum[i] = 0.0;
@@ -375,6 +387,11 @@ hipError_t launch_env_step(hipStream_t st, const EnvDims &d, const EnvState &s, 
     case 4: hipLaunchKernelGGL(env_step_kernel<4>, grid, block, lds, st, d, s, price, ind, io); break;
     default: hipLaunchKernelGGL(env_step_kernel<1>, grid, block, lds, st, d, s, price, ind, io); break;
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_check_starts(hipStream_t st, int32_t N, int32_t H, int32_t rows, const int32_t *start, int32_t *bad) {
+  hipLaunchKernelGGL(check_starts_kernel, dim3(1), dim3(256), 0, st, N, H, rows, start, bad);
   return hipGetLastError();
 }
 

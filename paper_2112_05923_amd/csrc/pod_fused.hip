@@ -76,12 +76,12 @@ struct __attribute__((aligned(16))) Slot {
   double rcp;  // 1 / unit cost in binary64 (k > 0), else 0
 };
 
-__device__ inline Row row_of(const EnvDims &d, int32_t tau, int32_t n) {
+__device__ inline Row row_of(const EnvDims &d, int32_t tau, int32_t start, int32_t n) {
   const int32_t m = d.M == 1 ? 0 : n;
   Row r;
   r.row_val = (tau + 1) * d.M + m;
-  r.done = (tau + 1 == d.H);
-  r.row_obs = r.done ? m : r.row_val;
+  r.done = (tau + 1 - start == d.H);
+  r.row_obs = r.done ? start * d.M + m : r.row_val;
   r.pad = 0;
   return r;
 }
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
 
   // ---- ledger lanes (wavefront 0): per-env scalars in registers for the whole rollout
   float cash = 0.0f;
-  int32_t tau = 0, ep_cnt = 0;
+  int32_t tau = 0, start = 0, ep_cnt = 0;
   double asset = 0.0, ep_ret = 0.0, ep_sum = 0.0, ep_sqsum = 0.0;
 
   Net net;
@@ -140,6 +140,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     const int n = n0 + lane;
     cash = a.st.cash[n];
     tau = a.st.tau[n];
+    start = a.st.start[n];
     ep_ret = a.st.ep_ret[n];
     ep_sum = a.st.ep_sum[n];
     ep_sqsum = a.st.ep_sqsum[n];
@@ -288,7 +289,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     double v = (double)cash;
     for (int dd = 0; dd < D; ++dd) v += (double)s_h[e * Dp + dd] * (double)s_p[e * Dp + dd];
     asset = v;
-    s_row[e] = row_of(d, tau, n0 + e);
+    s_row[e] = row_of(d, tau, start, n0 + e);
   }
 
   // Weight ring of the actor.  Layer 1's first blocks are requested a phase early (here, and after each step's
@@ -456,13 +457,13 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         ep_ret = 0.0;
         cash = d.cash0;
         asset = (double)d.cash0;
-        tau = 0;
+        tau = start;
       } else {
         tau += 1;
       }
       s_cash[e] = cash;
       s_done[e] = dn;
-      s_row[e] = row_of(d, tau, n);  // cursor rows of step t + 1 (nobody reads the old ones any more)
+      s_row[e] = row_of(d, tau, start, n);  // cursor rows of step t + 1 (nobody reads the old ones any more)
     } else if (wave == 1 && a.logp) {
       // ---- log-probability of the sampled action: squared noise summed in stock order, one lane per env
       int e = lane;

@@ -21,6 +21,7 @@ struct EnvState {
   double *ep_sum;    // [N]
   double *ep_sqsum;  // [N]
   int32_t *ep_cnt;   // [N]
+  const int32_t *start;  // [N] table row every episode of the env begins at (0 unless a replay table is set)
 };
 
 struct EnvDims {
@@ -46,6 +47,7 @@ hipError_t launch_observe(hipStream_t st, const EnvDims &d, const EnvState &s, c
 hipError_t launch_env_step(hipStream_t st, const EnvDims &d, const EnvState &s, const float *price, const float *ind,
                            const StepIO &io);
 hipError_t launch_state_reset(hipStream_t st, const EnvDims &d, const EnvState &s);
+hipError_t launch_check_starts(hipStream_t st, int32_t N, int32_t H, int32_t rows, const int32_t *start, int32_t *bad);
 hipError_t launch_state_copy(hipStream_t st, const EnvDims &d, const EnvState &s, const pr_state &user, bool to_user);
 hipError_t launch_leaderboard(hipStream_t st, int32_t N, int32_t P, const EnvState &s, double *scratch_mean,
                               double *score_mean, double *score_var, int32_t *rank);

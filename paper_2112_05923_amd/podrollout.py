@@ -20,7 +20,8 @@ PR_MLP_F32, PR_MLP_BF16 = 0, 1
 PR_SCHED_STEPWISE, PR_SCHED_FUSED = 0, 1
 PR_NET_ACTOR, PR_NET_CRITIC = 0, 1
 
-EXPORTS = ["rollout_workspace_bytes", "rollout_init", "rollout_set_weights", "rollout_reset", "rollout_step_T",
+EXPORTS = ["rollout_workspace_bytes", "rollout_init", "rollout_set_weights", "rollout_reset", "rollout_set_replay",
+           "rollout_step_T",
            "rollout_step_forced", "rollout_mlp_forward", "rollout_get_state", "rollout_set_state", "compute_gae",
            "trading_metrics", "population_refill", "ppo_workspace_bytes",
            "ppo_minibatch_grads", "adam_update", "ppo_learner_step", "rollout_leaderboard", "rollout_destroy", "rollout_strerror", "rollout_last_hip_error"]
@@ -88,6 +89,7 @@ def lib():
                                    C.POINTER(PrWeights), C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]
         l.rollout_set_weights.argtypes = [C.c_void_p, C.POINTER(PrWeights), C.POINTER(PrWeights)]
         l.rollout_reset.argtypes = [C.c_void_p]
+        l.rollout_set_replay.argtypes = [C.c_void_p, C.POINTER(PrMarket), C.c_int32, C.c_void_p]
         l.rollout_step_T.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(PrBuffers)]
         l.rollout_step_forced.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(PrBuffers)]
         l.rollout_mlp_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
@@ -203,6 +205,16 @@ class Rollout:
 
     def reset(self):
         _check(lib().rollout_reset(self._h), "rollout_reset")
+
+    def set_replay(self, price: torch.Tensor, ind: Optional[torch.Tensor], start: torch.Tensor):
+        """Episodes of env n run over rows start[n] .. start[n] + H of the table price [rows, M, D], ind [rows, M, D*K]."""
+        rows = int(price.shape[0])
+        m = PrMarket()
+        m.price = _dev(price, torch.float32, (rows, self.cfg.n_market, self.D), "price")
+        m.ind = _dev(ind, torch.float32, (rows, self.cfg.n_market, self.D * self.K), "ind") if self.K > 0 else None
+        s = _dev(start, torch.int32, (self.N,), "start")
+        _check(lib().rollout_set_replay(self._h, C.byref(m), rows, s), "rollout_set_replay")
+        self._keep = (price, ind) + self._keep[2:]
 
     def alloc_buffers(self, T: int, value=True, logp=True, mu=False, shares=False) -> Dict[str, torch.Tensor]:
         N, D, S, dev = self.N, self.D, self.S, self.device

@@ -589,6 +589,61 @@ def test_population_cycle_rank_refill_and_roll_again():
     assert torch.equal(mu2[rk[2] * per:(rk[2] + 1) * per], mu[rk[0] * per:(rk[0] + 1) * per])
 
 
+# ------------------------------- one shared table replayed from per-env start rows
+
+REPLAY_CASES = [
+    # name, base workload, overrides, table rows, H, T, schedule
+    ("tiny_stepwise", "tiny", dict(n_envs=70), 97, 24, 64, pr.PR_SCHED_STEPWISE),
+    ("dow30_fused", "large", dict(n_envs=192, hidden=256, cost=2.0e-3), 301, 40, 100, 1),
+    ("hundred_stocks_stepwise", "large", dict(n_envs=200, n_stocks=100, hidden=256, cost=2.0e-3), 211, 40, 90,
+     pr.PR_SCHED_STEPWISE),
+]
+
+
+@pytest.mark.parametrize("name,base,over,rows,H,T,schedule", REPLAY_CASES, ids=[c[0] for c in REPLAY_CASES])
+def test_replay_of_a_shared_table_from_per_env_start_rows(name, base, over, rows, H, T, schedule):
+    """rollout_set_replay: one table (M = 1), every env on its own window of H + 1 rows; episodes end and restart
+    inside the rollout.  Environment stage teacher-forced on the recorded means, networks on sampled rows, the
+    final state, and a second call that continues the episodes."""
+    w = inputs.WORKLOADS[base].replace(steps=T, **over)
+    N, D, S = w.n_envs, w.n_stocks, w.state_dim
+    d = inputs.make_all(w, horizon=rows - 1, n_market=1, steps=2 * T)
+    rng = np.random.default_rng(len(name))
+    start = rng.integers(0, rows - H, N).astype(np.int32)
+    start[0], start[N - 1] = 0, rows - 1 - H
+    price, ind = torch.from_numpy(d["price"]).to(DEV), torch.from_numpy(d["ind"]).to(DEV)
+    cfg = pr.make_config(w, horizon=H, n_market=1, schedule=schedule)
+    ro = pr.Rollout(cfg, price[:H + 1], ind[:H + 1], _dev(d["actor"]), _dev(d["critic"]))
+    ro.set_replay(price, ind, torch.from_numpy(start).to(DEV))
+    ocfg = oracle.cfg_from_workload(w, horizon=H)
+    ost = oracle.State(ocfg, N, start=start)
+    noise = torch.from_numpy(d["noise"]).to(DEV)
+    for call in range(2):
+        out = ro.alloc_buffers(T, value=True, logp=True, mu=True, shares=True)
+        ro.step_T(T, noise[call * T:(call + 1) * T], out)
+        torch.cuda.synchronize()
+        rec = _rec(out)
+        chk, ost = parity.check_env_record(w, ocfg, rec, d["price"], d["ind"], d["noise"][call * T:(call + 1) * T],
+                                           rec["mu"], state0=ost)
+        gst = {k: parity.to_np(v) for k, v in ro.get_state().items()}
+        assert np.array_equal(gst["cursor"], ost.tau) and np.array_equal(gst["ep_count"], ost.ep_cnt)
+        assert np.array_equal(gst["cash"], ost.cash) and np.array_equal(gst["holdings"], ost.h)
+        np.testing.assert_allclose(gst["ep_sum"], ost.ep_sum, rtol=1e-9, atol=1e-9)
+        ts = [0, H - 1, H, T - 1]
+        parity.check_networks(w, d["actor"], d["critic"], rec["obs"][ts].reshape(-1, S), rec["mu"][ts].reshape(-1, D),
+                              rec["value"][ts].reshape(-1))
+    assert int(gst["ep_count"].min()) == (2 * T) // H and rec["done"].sum() > 0
+    # a start row that would run past the table is refused and leaves the handle as it was
+    bad = torch.from_numpy(start).to(DEV).clone()
+    bad[N // 2] = rows - H
+    with pytest.raises(RuntimeError):
+        ro.set_replay(price, ind, bad)
+    assert np.array_equal(parity.to_np(ro.get_state()["cursor"]), ost.tau)
+    ro.reset()
+    torch.cuda.synchronize()
+    assert np.array_equal(parity.to_np(ro.get_state()["cursor"]), start)
+
+
 # ------------------------------------------------------------ graph capture
 
 @pytest.mark.parametrize("schedule", [pr.PR_SCHED_STEPWISE, FUSED])

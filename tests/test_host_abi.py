@@ -83,6 +83,7 @@ def test_null_arguments_are_rejected_without_device_work():
     assert lib.rollout_step_forced(None, 4, None, None, None) == pr.PR_EINVAL
     assert lib.rollout_mlp_forward(None, 0, 1, None, 1, None) == pr.PR_EINVAL
     assert lib.rollout_reset(None) == pr.PR_EINVAL
+    assert lib.rollout_set_replay(None, None, 0, None) == pr.PR_EINVAL
     assert lib.rollout_destroy(None) == pr.PR_EINVAL
     assert lib.rollout_leaderboard(None, None, None, None) == pr.PR_EINVAL
     assert lib.compute_gae(None, 0, 4, None, None, None, 0.99, 0.95, None, None) == pr.PR_EINVAL
