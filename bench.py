@@ -185,6 +185,58 @@ def main():
     t_pop = e0.elapsed_time(e1) / 10
     del pop, pop_noise
 
+    # (also outside) one PPO minibatch step of the learner (Sec. 5.2: batch 1024) on rows drawn from this buffer
+    t_learn = None
+    if w.n_agents == 1:
+        lcfg = pr.make_ppo_config(w, batch=1024)
+        host_nets = {k: inputs.make_weights(w, critic=(k == "critic")) for k in ("actor", "critic")}
+        nets = {k: {kk: torch.from_numpy(vv[0]).to(dev) for kk, vv in n.items()} for k, n in host_nets.items()}
+        zeros = lambda n: {k: torch.zeros_like(v) for k, v in n.items()}
+        mom = [zeros(nets["actor"]), zeros(nets["actor"]), zeros(nets["critic"]), zeros(nets["critic"])]
+        lws = pr.ppo_workspace(lcfg, dev)
+        g = torch.Generator(device=dev)
+        g.manual_seed(inputs.BASE_SEED)
+        rows = torch.randint(0, T * N, (1024,), generator=g, device=dev, dtype=torch.int32)
+        learn = lambda: pr.ppo_learner_step(lcfg, obs2d[:T * N], out["act_raw"].view(T * N, D), out["logp"].view(-1),
+                                            adv.view(-1), ret.view(-1), rows, nets["actor"], nets["critic"], *mom, lws)
+        learn()
+        e0.record()
+        for _ in range(10):
+            learn()
+        e1.record()
+        torch.cuda.synchronize()
+        t_learn = e0.elapsed_time(e1) / 10
+
+    # (also outside) the same step on one shared market table of 2^17 rows replayed from random per-env start rows,
+    # cost 0.2 % (Sec. 5.3 set-up: every env trades the same minute-level data set)
+    t_replay = None
+    if w.n_agents == 1:
+        R = 1 << 17
+        wr = w.replace(cost=2.0e-3)
+        tab = inputs.make_all_device(wr, dev, horizon=R - 1, n_market=1, steps=1)
+        ro2 = pr.Rollout(pr.make_config(wr, horizon=T, n_market=1, schedule=sched), tab["price"][:T + 1],
+                         tab["ind"][:T + 1], d["actor"], d["critic"])
+        g = torch.Generator(device=dev)
+        g.manual_seed(inputs.BASE_SEED + 1)
+        ro2.set_replay(tab["price"], tab["ind"],
+                       torch.randint(0, R - T, (N,), generator=g, device=dev, dtype=torch.int32))
+
+        def replay_step():
+            ro2.reset()
+            ro2.step_T(T, d["noise"], roll)
+            ro2.mlp_forward(pr.PR_NET_CRITIC, obs2d, val2d)
+            pr.compute_gae(out["reward"], out["value"], out["done"], w.gamma, w.lam, adv, ret)
+
+        replay_step()
+        e0.record()
+        for _ in range(3):
+            replay_step()
+        e1.record()
+        torch.cuda.synchronize()
+        t_replay = e0.elapsed_time(e1) / 3
+        ro2.close()
+        del tab
+
     ms = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in events) / args.steps
     t_roll, t_critic, t_gae = ms(0, 1), ms(1, 2), ms(2, 3)
     env_steps = N * T
@@ -227,6 +279,14 @@ def main():
                                                               "12 B per rewritten weight",
                                          "GBps": 48 * 512 * 512 * 12 / t_pop / 1e6}},
     }
+    if t_learn is not None:
+        res["extras"]["ppo_learner_step"] = {"ms": t_learn, "samples_per_s": 1024 / t_learn * 1e3,
+                                             "note": "not part of value; minibatch 1024 gathered from this buffer, "
+                                                     "both networks forward + backward + Adam, fp32"}
+    if t_replay is not None:
+        res["extras"]["replay_shared_table"] = {"ms": t_replay, "env_steps_per_s": env_steps / t_replay * 1e3,
+                                                "note": "not part of value; the same step with M = 1, a table of "
+                                                        "131072 rows, random per-env start rows, cost 0.2 %"}
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)
         res["cpu_baseline"] = cpu_baseline(w, args.cpu_envs, min(args.cpu_steps, T), threads)
