@@ -419,7 +419,7 @@ int ppo_workspace_bytes(const pr_ppo_config *cfg, size_t *out) {
   if (!out) return PR_EINVAL;
   const int rc = ppo_config_ok(cfg);
   if (rc != PR_OK) return rc;
-  *out = ppo_scratch_bytes(cfg->batch, cfg->hidden, cfg->n_stocks) + grads_bytes(*cfg);
+  *out = ppo_scratch_bytes(cfg->batch, cfg->hidden, cfg->n_stocks, 1 + cfg->n_stocks * (2 + cfg->n_ind)) + grads_bytes(*cfg);
   return PR_OK;
 }
 
@@ -432,7 +432,7 @@ int ppo_minibatch_grads(void *hip_stream, const pr_ppo_config *cfg, const float 
   if (!obs || !act_raw || !logp_old || !adv || !ret || !workspace) return PR_EINVAL;
   if (!net_ok(actor) || !net_ok(critic) || !net_ok(grad_actor) || !net_ok(grad_critic)) return PR_EINVAL;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) ||
-      workspace_bytes < ppo_scratch_bytes(cfg->batch, cfg->hidden, cfg->n_stocks))
+      workspace_bytes < ppo_scratch_bytes(cfg->batch, cfg->hidden, cfg->n_stocks, 1 + cfg->n_stocks * (2 + cfg->n_ind)))
     return PR_EINVAL;
   POD_HIP(launch_ppo_grads(static_cast<hipStream_t>(hip_stream), *cfg, obs, act_raw, logp_old, adv, ret, rows, *actor,
                            *critic, *grad_actor, *grad_critic, workspace, stats));
@@ -461,7 +461,7 @@ int ppo_learner_step(void *hip_stream, const pr_ppo_config *cfg, const float *ob
   if (cfg->adam_step < 1 || !(cfg->beta1 >= 0.0f) || !(cfg->beta1 < 1.0f) || !(cfg->beta2 >= 0.0f) ||
       !(cfg->beta2 < 1.0f) || !(cfg->adam_eps > 0.0f) || !isfinite(cfg->lr))
     return PR_EINVAL;
-  const size_t scratch = ppo_scratch_bytes(cfg->batch, cfg->hidden, cfg->n_stocks);
+  const size_t scratch = ppo_scratch_bytes(cfg->batch, cfg->hidden, cfg->n_stocks, 1 + cfg->n_stocks * (2 + cfg->n_ind));
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < scratch + grads_bytes(*cfg)) return PR_EINVAL;
   // gradients behind the scratch, tensor by tensor
   unsigned char *p = static_cast<unsigned char *>(workspace) + scratch;

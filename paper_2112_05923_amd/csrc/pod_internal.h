@@ -60,7 +60,7 @@ hipError_t launch_trading_metrics(hipStream_t st, int32_t T, int32_t N, int32_t 
                                   double *metrics, int32_t *length);
 hipError_t launch_population_refill(hipStream_t st, int32_t P, int64_t count, const int32_t *rank, int32_t keep,
                                     float sigma, const float *noise, float *params);
-size_t ppo_scratch_bytes(int B, int Hd, int D);
+size_t ppo_scratch_bytes(int B, int Hd, int D, int S);
 hipError_t launch_ppo_grads(hipStream_t st, const pr_ppo_config &c, const float *obs, const float *act,
                             const float *logp_old, const float *adv, const float *ret, const int32_t *rows,
                             const pr_net_params &actor, const pr_net_params &critic, const pr_net_params &ga,

@@ -788,3 +788,47 @@ def test_ppo_learner_step_updates_both_networks_like_the_checker():
             assert np.all(np.abs(moved[big] - want[big]) <= 2e-3 * np.abs(want[big]) +
                           np.spacing(np.abs(nets[which][k][big]) + np.float32(1e-2))), (which, k)
             assert _rel(parity.to_np(mom[which][0][k]), m) <= parity.TOL_F32, (which, k)
+
+
+def test_learner_step_replays_from_a_captured_graph():
+    """ppo_learner_step allocates nothing and only enqueues kernels, so it can be captured: three replays must
+    walk the parameters and moments exactly as three eager calls do (the step counter is baked in at capture, so
+    the eager calls use the same one)."""
+    w = inputs.WORKLOADS["dow30"]
+    B = 1024
+    nets, obs, act, logp_old, adv, ret, rows = _ppo_case(w, B, 1300, seed=77)
+    cfg = pr.make_ppo_config(w, batch=B)
+    t = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        batch = [t(obs), t(act), t(logp_old), t(adv), t(ret), t(rows)]
+        ws = pr.ppo_workspace(cfg, DEV)
+
+        def fresh():
+            p = [_dev(nets["actor"]), _dev(nets["critic"])]
+            return p + [{k: torch.zeros_like(v) for k, v in p[i % 2].items()} for i in range(4)]
+
+        eager = fresh()
+        eager = [eager[0], eager[1], eager[2], eager[4], eager[3], eager[5]]     # actor, critic, m_a, v_a, m_c, v_c
+        for _ in range(3):
+            pr.ppo_learner_step(cfg, *batch, *eager, ws)
+        side.synchronize()
+        graph = fresh()
+        graph = [graph[0], graph[1], graph[2], graph[4], graph[3], graph[5]]
+        start = [{k: v.clone() for k, v in n.items()} for n in graph]
+        pr.ppo_learner_step(cfg, *batch, *graph, ws)        # warm-up outside the capture
+        for n, s0 in zip(graph, start):
+            for k in n:
+                n[k].copy_(s0[k])
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            pr.ppo_learner_step(cfg, *batch, *graph, ws)
+        # capture does not execute: the tensors still hold the start values
+        for rep in range(3):
+            g.replay()
+            torch.cuda.synchronize()
+        for a, b in zip(eager, graph):
+            for k in a:
+                assert torch.equal(a[k], b[k]), k
+    assert not torch.equal(graph[0]["W2"], start[0]["W2"])
