@@ -93,77 +93,13 @@ def cpu_baseline(w, n_envs: int, steps: int, threads: int):
                          "sample": f"{one.size} envs x {steps} steps, {dt1:.1f} s wall"}}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="large")
-    ap.add_argument("--schedule", default="fused", choices=["stepwise", "fused"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-envs", type=int, default=192)
-    ap.add_argument("--cpu-steps", type=int, default=1024)
-    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
-                    help="also launch one plain elementwise copy of this many MiB (read + write that much each), "
-                         "the known-size kernel hardware traffic counters are scaled by")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (envs shard trivially across GPUs; no multi-GPU "
-                 "path is built or measured). Use --gpus 1.")
-
-    import torch
-    from paper_2112_05923_amd import inputs, podrollout as pr
-
-    if not torch.cuda.is_available():
-        sys.exit("bench.py needs a GPU")
-    dev = torch.device("cuda:0")
-    w = inputs.WORKLOADS[args.workload]
-    T, N, D, S = w.steps, w.n_envs, w.n_stocks, w.state_dim
-    d = inputs.make_all_device(w, dev)
-    sched = pr.PR_SCHED_FUSED if args.schedule == "fused" else pr.PR_SCHED_STEPWISE
-    ro = pr.Rollout(pr.make_config(w, schedule=sched), d["price"], d["ind"], d["actor"], d["critic"])
-    out = ro.alloc_buffers(T, value=True, logp=True, mu=False, shares=False)
-    roll = dict(out)
-    roll["value"] = None
-    adv = torch.empty((T, N), dtype=torch.float32, device=dev)
-    ret = torch.empty((T, N), dtype=torch.float32, device=dev)
-    obs2d = out["obs"].view((T + 1) * N, S)
-    val2d = out["value"].view((T + 1) * N, 1)
-
-    def one_step(ev=None):
-        ro.reset()
-        if ev:
-            ev[0].record()
-        ro.step_T(T, d["noise"], roll)
-        if ev:
-            ev[1].record()
-        ro.mlp_forward(pr.PR_NET_CRITIC, obs2d, val2d)
-        if ev:
-            ev[2].record()
-        pr.compute_gae(out["reward"], out["value"], out["done"], w.gamma, w.lam, adv, ret)
-        if ev:
-            ev[3].record()
-
-    for _ in range(args.warmup):
-        one_step()
-    torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        one_step(events[k])
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-
-    if args.copy_calibration:
-        src = torch.ones(args.copy_calibration << 18, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        torch.mul(src, 1.0, out=dst)  # one vectorised elementwise kernel: reads and writes copy_calibration MiB
-        torch.cuda.synchronize()
-
-    # outside the timed region: the evaluator's trading figures over the record just produced
+def side_measurements(torch, pr, inputs, w, d, out, roll, adv, ret, obs2d, val2d, sched, dev):
+    """Untimed companions of the path, measured on the record the timed steps just produced; none of them is part
+    of `value`."""
+    T, N, D = w.steps, w.n_envs, w.n_stocks
+    env_steps = N * T
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    # the evaluator's trading figures
     pr.trading_metrics(out["obs"], out["done"], D, w.obs_scale, 252.0 * 390.0)
     e0.record()
     for _ in range(3):
@@ -237,6 +173,96 @@ def main():
         ro2.close()
         del tab
 
+    extras = {"trading_metrics": {"ms": t_metrics, "note": "not part of value; reads 4(1+2D) of every 4S-byte row",
+                                  "GBps": (4 * (1 + 2 * D) + 1) * (T + 1) * N / t_metrics / 1e6},
+              "population_refill": {"ms": t_pop, "note": "not part of value; 48 of 64 agents x 512 x 512 weights, "
+                                                         "12 B per rewritten weight",
+                                    "GBps": 48 * 512 * 512 * 12 / t_pop / 1e6}}
+    if t_learn is not None:
+        extras["ppo_learner_step"] = {"ms": t_learn, "samples_per_s": 1024 / t_learn * 1e3,
+                                      "note": "not part of value; minibatch 1024 gathered from this buffer, both "
+                                              "networks forward + backward + Adam, fp32, eager launches"}
+    if t_replay is not None:
+        extras["replay_shared_table"] = {"ms": t_replay, "env_steps_per_s": env_steps / t_replay * 1e3,
+                                         "note": "not part of value; the same step with M = 1, a table of 131072 "
+                                                 "rows, random per-env start rows, cost 0.2 %"}
+    return extras
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="large")
+    ap.add_argument("--schedule", default="fused", choices=["stepwise", "fused"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-envs", type=int, default=192)
+    ap.add_argument("--cpu-steps", type=int, default=1024)
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the untimed side measurements (metrics, population, learner, replay): profiler runs "
+                         "then see only the timed path's kernels")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="also launch one plain elementwise copy of this many MiB (read + write that much each), "
+                         "the known-size kernel hardware traffic counters are scaled by")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (envs shard trivially across GPUs; no multi-GPU "
+                 "path is built or measured). Use --gpus 1.")
+
+    import torch
+    from paper_2112_05923_amd import inputs, podrollout as pr
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    dev = torch.device("cuda:0")
+    w = inputs.WORKLOADS[args.workload]
+    T, N, D, S = w.steps, w.n_envs, w.n_stocks, w.state_dim
+    d = inputs.make_all_device(w, dev)
+    sched = pr.PR_SCHED_FUSED if args.schedule == "fused" else pr.PR_SCHED_STEPWISE
+    ro = pr.Rollout(pr.make_config(w, schedule=sched), d["price"], d["ind"], d["actor"], d["critic"])
+    out = ro.alloc_buffers(T, value=True, logp=True, mu=False, shares=False)
+    roll = dict(out)
+    roll["value"] = None
+    adv = torch.empty((T, N), dtype=torch.float32, device=dev)
+    ret = torch.empty((T, N), dtype=torch.float32, device=dev)
+    obs2d = out["obs"].view((T + 1) * N, S)
+    val2d = out["value"].view((T + 1) * N, 1)
+
+    def one_step(ev=None):
+        ro.reset()
+        if ev:
+            ev[0].record()
+        ro.step_T(T, d["noise"], roll)
+        if ev:
+            ev[1].record()
+        ro.mlp_forward(pr.PR_NET_CRITIC, obs2d, val2d)
+        if ev:
+            ev[2].record()
+        pr.compute_gae(out["reward"], out["value"], out["done"], w.gamma, w.lam, adv, ret)
+        if ev:
+            ev[3].record()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        one_step(events[k])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    if args.copy_calibration:
+        src = torch.ones(args.copy_calibration << 18, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 1.0, out=dst)  # one vectorised elementwise kernel: reads and writes copy_calibration MiB
+        torch.cuda.synchronize()
+
+    extras = {} if args.no_extras else side_measurements(torch, pr, inputs, w, d, out, roll, adv, ret, obs2d, val2d,
+                                                         sched, dev)
     ms = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in events) / args.steps
     t_roll, t_critic, t_gae = ms(0, 1), ms(1, 2), ms(2, 3)
     env_steps = N * T
@@ -273,20 +299,8 @@ def main():
                    "env_steps_per_step": env_steps},
         "roofline": dom,
         "stages": stages,
-        "extras": {"trading_metrics": {"ms": t_metrics, "note": "not part of value; reads 4(1+2D) of every 4S-byte row",
-                                       "GBps": (4 * (1 + 2 * D) + 1) * (T + 1) * N / t_metrics / 1e6},
-                   "population_refill": {"ms": t_pop, "note": "not part of value; 48 of 64 agents x 512 x 512 weights, "
-                                                              "12 B per rewritten weight",
-                                         "GBps": 48 * 512 * 512 * 12 / t_pop / 1e6}},
+        "extras": extras,
     }
-    if t_learn is not None:
-        res["extras"]["ppo_learner_step"] = {"ms": t_learn, "samples_per_s": 1024 / t_learn * 1e3,
-                                             "note": "not part of value; minibatch 1024 gathered from this buffer, "
-                                                     "both networks forward + backward + Adam, fp32"}
-    if t_replay is not None:
-        res["extras"]["replay_shared_table"] = {"ms": t_replay, "env_steps_per_s": env_steps / t_replay * 1e3,
-                                                "note": "not part of value; the same step with M = 1, a table of "
-                                                        "131072 rows, random per-env start rows, cost 0.2 %"}
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)
         res["cpu_baseline"] = cpu_baseline(w, args.cpu_envs, min(args.cpu_steps, T), threads)
