@@ -9,7 +9,8 @@
 // flight at once), scans it locally, publishes its (a, p) through LDS, composes
 // the summaries of the later chunks to get its incoming A, and patches its
 // results.  Segments of NW * GAE_L steps are walked from the end of the rollout
-// to the start with the boundary advantage carried in a register.
+// to the start with the boundary advantage carried in a register; the rows of the
+// next segment are requested before the current one is patched and stored.
 #include "pod_internal.h"
 
 namespace pod {
@@ -30,26 +31,28 @@ __global__ __launch_bounds__(GAE_NW * 64) void gae_kernel(int T, int N, const fl
   const int seg = GAE_NW * GAE_L;
   float carry = 0.0f;  // advantage at the first step of the segment handled before (later in time)
 
-  for (int hi = T; hi > 0; hi -= seg) {
-    // chunks are numbered from the end of the segment: chunk w covers [c_lo, c_lo + GAE_L)
+  // chunks are numbered from the end of a segment: chunk w of the segment ending at hi covers [c_lo, c_lo + GAE_L)
+  float r[GAE_L], v[GAE_L], v_after;
+  uint8_t dn[GAE_L];
+  auto load = [&](int hi, bool en, float (&r_)[GAE_L], float (&v_)[GAE_L], uint8_t (&dn_)[GAE_L], float &va_) {
     const int c_lo = hi - (w + 1) * GAE_L;
-    float a[GAE_L], p[GAE_L], v[GAE_L];
-    float r[GAE_L];
-    uint8_t dn[GAE_L];
-    float v_after = 0.0f;
 #pragma unroll
     for (int i = 0; i < GAE_L; ++i) {
       const int t = c_lo + i;
-      const bool ok = live && t >= 0;
+      const bool ok = en && live && t >= 0;
       const size_t idx = (size_t)(ok ? t : 0) * N + (live ? n : 0);
-      r[i] = ok ? reward[idx] : 0.0f;
-      v[i] = ok ? value[idx] : 0.0f;
-      dn[i] = ok ? done[idx] : (uint8_t)1;
+      r_[i] = ok ? __builtin_nontemporal_load(reward + idx) : 0.0f;
+      v_[i] = ok ? __builtin_nontemporal_load(value + idx) : 0.0f;
+      dn_[i] = ok ? __builtin_nontemporal_load(done + idx) : (uint8_t)1;
     }
-    {
-      const int t = c_lo + GAE_L;  // <= T: value has T+1 rows
-      if (live && t >= 0) v_after = value[(size_t)t * N + n];
-    }
+    const int t = c_lo + GAE_L;  // <= T: value has T+1 rows
+    va_ = (en && live && t >= 0) ? __builtin_nontemporal_load(value + (size_t)t * N + n) : 0.0f;
+  };
+  load(T, true, r, v, dn, v_after);
+
+  for (int hi = T; hi > 0; hi -= seg) {
+    const int c_lo = hi - (w + 1) * GAE_L;
+    float a[GAE_L], p[GAE_L];
     // local scan, newest step first
     float a_next = 0.0f, p_next = 1.0f, v_next = v_after;
 #pragma unroll
@@ -68,6 +71,11 @@ __global__ __launch_bounds__(GAE_NW * 64) void gae_kernel(int T, int N, const fl
     }
     s_a[w][lane] = a_next;
     s_p[w][lane] = p_next;
+    // the next (earlier) segment's rows are requested now, so that they travel while this segment's summaries
+    // meet in LDS and its results are written
+    float rn[GAE_L], vn[GAE_L], vn_after = 0.0f;
+    uint8_t dnn[GAE_L];
+    load(hi - seg, hi - seg > 0, rn, vn, dnn, vn_after);
     __syncthreads();
     // advantage just after this chunk = later chunks of the segment applied to the carry
     float a_in = carry;
@@ -81,10 +89,13 @@ __global__ __launch_bounds__(GAE_NW * 64) void gae_kernel(int T, int N, const fl
       if (live && t >= 0) {
         const float A = fmaf(p[i], a_in, a[i]);
         const size_t idx = (size_t)t * N + n;
-        adv[idx] = A;
-        ret[idx] = A + v[i];
+        __builtin_nontemporal_store(A, adv + idx);
+        __builtin_nontemporal_store(A + v[i], ret + idx);
       }
     }
+#pragma unroll
+    for (int i = 0; i < GAE_L; ++i) r[i] = rn[i], v[i] = vn[i], dn[i] = dnn[i];
+    v_after = vn_after;
     __syncthreads();  // summaries are rewritten by the next segment
   }
 }
