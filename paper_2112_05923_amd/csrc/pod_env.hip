@@ -65,13 +65,16 @@ __global__ __launch_bounds__(kThreads) void observe_kernel(EnvDims d, EnvState s
 // arrays (Dp odd so that the per-env serial loops of the trade pass hit
 // distinct banks): wanted shares, eps^2, unit value of the trade (sale proceeds
 // or purchase cost per share), executed shares, valuation prices, holdings.
-//  1. all lanes, one wavefront per env row (no index divisions): sample and clamp the action, size the
-//     order, fetch prices; holdings come in from their [D][N] layout with lanes across envs;
+// The kernel is a chain of memory round trips, so each phase requests everything it needs at once:
+//  0. cursors, holdings (from their [D][N] layout, lanes across envs), means and noise;
+//  1. prices at the cursor and at the valuation row; sample and clamp the action, size the orders (a group of
+//     32 or 64 lanes per env row, no index divisions);
 //  2. wavefront 0, one lane per env: the serial trade pass in branch-free code (a lane's branch costs all 64
-//     a round trip through the scalar unit; what bounds the pass is the dependent chain on the running cash),
-//     reward and episode bookkeeping in binary64 -- meanwhile the other wavefronts stream the market part of
-//     the next observation, 16 bytes per lane where the indicator rows allow it;
-//  3. all lanes: holdings / cash part of the next observation, executed shares, state write-back.
+//     a round trip through the scalar unit; what bounds the pass is the dependent chain on the running cash)
+//     -- meanwhile wavefront 1 sums the account value before the trades and all others stream the market part
+//     of the next observation, several env rows in flight per wavefront, 16 bytes per lane where the rows allow;
+//  3. wavefront 0: reward and episode bookkeeping in binary64;
+//  4. all lanes: holdings / cash part of the next observation, executed shares, state write-back.
 constexpr int kEnvThreads = 512;
 typedef float env_f32x4 __attribute__((ext_vector_type(4)));
 
@@ -81,70 +84,146 @@ __global__ __launch_bounds__(kEnvThreads) void env_step_kernel(EnvDims d, EnvSta
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const int D = d.D, Dp = D | 1;
   double *s_a0 = reinterpret_cast<double *>(lds_raw);  // [E] account value before the trades
-  int32_t *s_k = reinterpret_cast<int32_t *>(s_a0 + E);
+  double *s_a1 = s_a0 + E;                             // [E] account value after them, at the valuation prices
+  int32_t *s_k = reinterpret_cast<int32_t *>(s_a1 + E);
   float *s_e2 = reinterpret_cast<float *>(s_k + E * Dp);
   float *s_val = s_e2 + E * Dp;
   int32_t *s_q = reinterpret_cast<int32_t *>(s_val + E * Dp);
   float *s_pv = reinterpret_cast<float *>(s_q + E * Dp);
   int32_t *s_h = reinterpret_cast<int32_t *>(s_pv + E * Dp);
-  RowInfo *s_row = reinterpret_cast<RowInfo *>(s_h + E * Dp);
-  float *s_cash = reinterpret_cast<float *>(s_row + E);
+  float *s_pn = reinterpret_cast<float *>(s_h + E * Dp);  // prices the trades execute at
+  RowInfo *s_row = reinterpret_cast<RowInfo *>(s_pn + E * Dp);
+  float *s_cash = reinterpret_cast<float *>(s_row + E);   // cash after the trades, then after the reset
+  float *s_e2sum = s_cash + E;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   constexpr int NWV = kEnvThreads / 64;
   const int n0 = blockIdx.x * E;
   const int ne = min(E, d.N - n0);  // live envs of this tile
 
-  if (tid < ne) s_row[tid] = rows_of(d, s.tau[n0 + tid], s.start[n0 + tid], n0 + tid);
+  // order slots: a group of GW lanes per env row, G rows per pass, U passes in flight
+  constexpr int U = 4;
+  const int GW = D <= 32 ? 32 : 64, G = kEnvThreads / GW;
+  const int gl = tid & (GW - 1), grp = tid / GW;  // (GW is 32 or 64)
+
+  // -- 0. everything that does not depend on the cursor
+  int32_t tau_in = 0, start_in = 0;
+  if (tid < ne) {
+    tau_in = s.tau[n0 + tid], start_in = s.start[n0 + tid];
+    s_row[tid] = rows_of(d, tau_in, start_in, n0 + tid);
+  }
   for (int dd = wave; dd < D; dd += NWV)
     for (int e = lane; e < ne; e += 64) s_h[e * Dp + dd] = s.h[(size_t)dd * d.N + n0 + e];
+  float mu0[U], eps0[U];  // first column chunk of the first U passes (the whole tile when D <= 64 and E <= U G)
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int e = u * G + grp;
+    const bool ok = e < ne && gl < D;
+    const size_t g = (size_t)(n0 + (ok ? e : 0)) * D + (ok ? gl : 0);
+    mu0[u] = ok ? io.mu[g] : 0.0f;
+    eps0[u] = ok ? io.noise[g] : 0.0f;
+  }
+  // wavefront 0, lane e: the env's scalars, held in registers until the bookkeeping of phase 3 (E <= 64)
+  float cash_in = 0.0f;
+  double ep_ret = 0.0, ep_sum = 0.0, ep_sqsum = 0.0;
+  int32_t ep_cnt = 0;
+  if (tid < ne) {
+    const int n = n0 + tid;
+    cash_in = s.cash[n], ep_ret = s.ep_ret[n], ep_sum = s.ep_sum[n], ep_sqsum = s.ep_sqsum[n], ep_cnt = s.ep_cnt[n];
+    s_cash[tid] = cash_in;
+  }
   __syncthreads();
 
-  // -- 1. sample, size the orders, fetch prices
-  for (int e = wave; e < ne; e += NWV) {
-    const RowInfo ri = s_row[e];
-    const size_t g0 = (size_t)(n0 + e) * D;
-    for (int dd = lane; dd < D; dd += 64) {
-      const int o = e * Dp + dd;
-      const float mu = io.mu[g0 + dd];
-      const float eps = io.noise[g0 + dd];
-      const float a_raw = mu + d.sigma * eps;  // two roundings (contraction is off)
-      io.act_raw[g0 + dd] = a_raw;
-      const float ac = fminf(1.0f, fmaxf(-1.0f, a_raw));
-      const int32_t k = (int32_t)truncf(ac * d.hmax);
-      const float p = price[(size_t)ri.row_now * D + dd];
-      const int32_t h = s_h[o];
-      int32_t q = 0;
-      float val = 1.0f;  // (holds: a harmless divisor)
-      if (k < 0) {
-        q = min(-k, h);
-        s_h[o] = h - q;
-        const float gross = p * (float)q;
-        val = gross * d.one_minus_c;
-        q = -q;
-      } else if (k > 0) {
-        val = p * d.one_plus_c;
+  // -- 1a. request the market part of the next observation (it only depends on the cursor): one wavefront per env
+  // row, all of a wavefront's rows in flight; stored after the orders are sized
+  const int DK = D * d.K;
+  const bool vec = (DK & 3) == 0 && (reinterpret_cast<uintptr_t>(ind) & 15u) == 0;
+  constexpr int UE = (E + NWV - 1) / NWV;  // env rows per wavefront
+  const bool one_pass = D <= 64 && DK <= 256 && vec;
+  float m_pr[UE];
+  env_f32x4 m_ind[UE];
+  if (one_pass) {
+#pragma unroll
+    for (int u = 0; u < UE; ++u) {
+      const int e = wave + u * NWV;
+      m_pr[u] = 0.0f;
+      m_ind[u] = env_f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+      if (e < ne) {
+        const size_t row = (size_t)s_row[e].row_obs;
+        if (lane < D) m_pr[u] = price[row * D + lane];
+        if (4 * lane < DK) m_ind[u] = *reinterpret_cast<const env_f32x4 *>(ind + row * DK + 4 * lane);
       }
-      s_k[o] = k;
-      s_e2[o] = eps * eps;
-      s_val[o] = val;
-      s_q[o] = q;
-      s_pv[o] = price[(size_t)ri.row_val * D + dd];
     }
   }
-  // account value before the trades: cash + sum h p in stock order, binary64 (lane per env, needs the prices)
-  __syncthreads();
-  if (wave == 1) {
-    for (int e = lane; e < ne; e += 64) {
-      const RowInfo ri = s_row[e];
-      double v = (double)s.cash[n0 + e];
-      for (int dd = 0; dd < D; ++dd) {
-        // holdings before the sales = holdings now + what the sale pass took
-        const int32_t k = s_k[e * Dp + dd];
-        const int32_t h0 = s_h[e * Dp + dd] + (k < 0 ? -s_q[e * Dp + dd] : 0);
-        v += (double)h0 * (double)price[(size_t)ri.row_now * D + dd];
+
+  // -- 1. prices, then sample and size the orders
+  for (int eb = 0; eb < ne; eb += U * G) {
+    for (int d0 = 0; d0 < D; d0 += GW) {
+      const int dd = d0 + gl;
+      float mu[U], eps[U], pn[U], pv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int e = eb + u * G + grp;
+        const bool ok = e < ne && dd < D;
+        const RowInfo ri = s_row[ok ? e : 0];
+        if (eb == 0 && d0 == 0) {
+          mu[u] = mu0[u], eps[u] = eps0[u];
+        } else {
+          const size_t g = (size_t)(n0 + (ok ? e : 0)) * D + (ok ? dd : 0);
+          mu[u] = ok ? io.mu[g] : 0.0f;
+          eps[u] = ok ? io.noise[g] : 0.0f;
+        }
+        pn[u] = ok ? price[(size_t)ri.row_now * D + dd] : 1.0f;
+        pv[u] = ok ? price[(size_t)ri.row_val * D + dd] : 1.0f;
       }
-      s_a0[e] = v;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int e = eb + u * G + grp;
+        if (e < ne && dd < D) {
+          const int o = e * Dp + dd;
+          const float a_raw = mu[u] + d.sigma * eps[u];  // two roundings (contraction is off)
+          io.act_raw[(size_t)(n0 + e) * D + dd] = a_raw;
+          const float ac = fminf(1.0f, fmaxf(-1.0f, a_raw));
+          const int32_t k = (int32_t)truncf(ac * d.hmax);
+          const float p = pn[u];
+          const int32_t h = s_h[o];
+          int32_t q = 0;
+          float val = 1.0f;  // (holds: a harmless divisor)
+          if (k < 0) {
+            q = min(-k, h);
+            s_h[o] = h - q;
+            const float gross = p * (float)q;
+            val = gross * d.one_minus_c;
+            q = -q;
+          } else if (k > 0) {
+            val = p * d.one_plus_c;
+          }
+          s_k[o] = k;
+          s_e2[o] = eps[u] * eps[u];
+          s_val[o] = val;
+          s_q[o] = q;
+          s_pv[o] = pv[u];
+          s_pn[o] = p;
+        }
+      }
+    }
+  }
+  if (one_pass) {
+#pragma unroll
+    for (int u = 0; u < UE; ++u) {
+      const int e = wave + u * NWV;
+      if (e < ne) {
+        float *o = io.obs_next + (size_t)(n0 + e) * d.S;
+        if (lane < D) o[1 + lane] = m_pr[u] * d.s_price;
+        if (4 * lane < DK) {
+          env_f32x4 t = m_ind[u];
+          t[0] *= d.s_ind;
+          t[1] *= d.s_ind;
+          t[2] *= d.s_ind;
+          t[3] *= d.s_ind;
+          *reinterpret_cast<env_f32x4 *>(o + 1 + 2 * D + 4 * lane) = t;  // (4-byte aligned is enough for a global store)
+        }
+      }
     }
   }
   __syncthreads();
@@ -152,8 +231,8 @@ __global__ __launch_bounds__(kEnvThreads) void env_step_kernel(EnvDims d, EnvSta
   if (wave == 0) {
     // -- 2a. one lane per env: the serial part (Table 1 actions: sell / buy / hold)
     for (int e = lane; e < ne; e += 64) {
-      const int n = n0 + e, o0 = e * Dp;
-      float cash = s.cash[n];
+      const int o0 = e * Dp;
+      float cash = cash_in;  // (e == lane: E <= 64)
       float e2 = 0.0f;
       for (int dd = 0; dd < D; ++dd) {
         e2 += s_e2[o0 + dd];
@@ -177,72 +256,138 @@ __global__ __launch_bounds__(kEnvThreads) void env_step_kernel(EnvDims d, EnvSta
         q = over ? q - 1 : q;
         const float outlay = over ? out_q1 : out_q;
         cash = buy ? cash - outlay : cash;
-        s_h[o0 + dd] += q;
-        s_q[o0 + dd] += q;  // (a purchase slot held 0)
+        // (a purchase slot held 0, any other slot is rewritten with what it held: wavefront 1 reads the sale
+        // slots meanwhile.)  s_h keeps the holdings after the sales; purchases are added on the way out.
+        s_q[o0 + dd] += q;
       }
       double asset1 = (double)cash;
-      for (int dd = 0; dd < D; ++dd) asset1 += (double)s_h[o0 + dd] * (double)s_pv[o0 + dd];
-      const double r = (asset1 - s_a0[e]) * (double)d.rho;
-      const RowInfo ri = s_row[e];
-      double ep = s.ep_ret[n] + r;
-      if (ri.done) {
-        s.ep_sum[n] += ep;
-        s.ep_sqsum[n] += ep * ep;
-        s.ep_cnt[n] += 1;
-        ep = 0.0;
-        cash = d.cash0;
-        for (int dd = 0; dd < D; ++dd) s_h[o0 + dd] = 0;
-      }
-      s.ep_ret[n] = ep;
-      s.cash[n] = cash;
-      s.tau[n] = ri.done ? s.start[n] : s.tau[n] + 1;
-      s_cash[e] = cash;
-      io.reward[n] = (float)r;
-      io.done[n] = (uint8_t)ri.done;
-      if (io.logp) io.logp[n] = fmaf(-0.5f, e2, d.logp_const);
+      for (int dd = 0; dd < D; ++dd)
+        asset1 += (double)(s_h[o0 + dd] + max(s_q[o0 + dd], 0)) * (double)s_pv[o0 + dd];
+      s_a1[e] = asset1;
+      cash_in = cash;  // now: cash after the trades
+      s_e2sum[e] = e2;
     }
   } else {
-    // -- 2b. the other wavefronts stream the market part of the next observation, one env row at a time
-    const int DK = D * d.K;
-    const bool vec = (DK & 3) == 0 && (reinterpret_cast<uintptr_t>(ind) & 15u) == 0;
-    for (int e = wave - 1; e < ne; e += NWV - 1) {
-      const size_t row = (size_t)s_row[e].row_obs;
-      float *o = io.obs_next + (size_t)(n0 + e) * d.S;
-      for (int j = lane; j < D; j += 64) o[1 + j] = price[row * D + j] * d.s_price;
-      const float *src = ind + row * DK;
-      float *dst = o + 1 + 2 * D;
+    if (wave == 1) {
+      // account value before the trades: cash + sum h p in stock order, binary64 (lane per env)
+      for (int e = lane; e < ne; e += 64) {
+        double v = (double)s_cash[e];
+        for (int dd = 0; dd < D; ++dd) {
+          // holdings before the sales = holdings after them + what the sale pass took (the slots of sales are
+          // stable while wavefront 0 books the purchases)
+          const int32_t k = s_k[e * Dp + dd];
+          const int32_t h0 = s_h[e * Dp + dd] + (k < 0 ? -s_q[e * Dp + dd] : 0);
+          v += (double)h0 * (double)s_pn[e * Dp + dd];
+        }
+        s_a0[e] = v;
+      }
+    }
+    // -- 2b. wide rows: stream the market part of the next observation here, UB env rows in flight per wavefront
+    constexpr int UB = 5;
+    for (int eb = wave - 1; eb < ne && !one_pass; eb += UB * (NWV - 1)) {
+      for (int j0 = 0; j0 < D; j0 += 64) {
+        float pr[UB];
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+          const int e = eb + u * (NWV - 1);
+          const bool ok = e < ne && j0 + lane < D;
+          pr[u] = ok ? price[(size_t)s_row[e].row_obs * D + j0 + lane] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+          const int e = eb + u * (NWV - 1);
+          if (e < ne && j0 + lane < D) io.obs_next[(size_t)(n0 + e) * d.S + 1 + j0 + lane] = pr[u] * d.s_price;
+        }
+      }
       if (vec) {
-        for (int j = 4 * lane; j < DK; j += 256) {
-          env_f32x4 v = *reinterpret_cast<const env_f32x4 *>(src + j);
-          v[0] *= d.s_ind;
-          v[1] *= d.s_ind;
-          v[2] *= d.s_ind;
-          v[3] *= d.s_ind;
-          *reinterpret_cast<env_f32x4 *>(dst + j) = v;  // 4-byte aligned is enough for a global store
+        for (int j0 = 0; j0 < DK; j0 += 256) {
+          const int j = j0 + 4 * lane;
+          env_f32x4 v[UB];
+#pragma unroll
+          for (int u = 0; u < UB; ++u) {
+            const int e = eb + u * (NWV - 1);
+            if (e < ne && j < DK)
+              v[u] = *reinterpret_cast<const env_f32x4 *>(ind + (size_t)s_row[e].row_obs * DK + j);
+          }
+#pragma unroll
+          for (int u = 0; u < UB; ++u) {
+            const int e = eb + u * (NWV - 1);
+            if (e < ne && j < DK) {
+              env_f32x4 t = v[u];
+              t[0] *= d.s_ind;
+              t[1] *= d.s_ind;
+              t[2] *= d.s_ind;
+              t[3] *= d.s_ind;
+              // (4-byte aligned is enough for a global store)
+              *reinterpret_cast<env_f32x4 *>(io.obs_next + (size_t)(n0 + e) * d.S + 1 + 2 * D + j) = t;
+            }
+          }
         }
       } else {
-        for (int j = lane; j < DK; j += 64) dst[j] = src[j] * d.s_ind;
+        for (int j0 = 0; j0 < DK; j0 += 64) {
+          const int j = j0 + lane;
+          float v[UB];
+#pragma unroll
+          for (int u = 0; u < UB; ++u) {
+            const int e = eb + u * (NWV - 1);
+            v[u] = (e < ne && j < DK) ? ind[(size_t)s_row[e].row_obs * DK + j] : 0.0f;
+          }
+#pragma unroll
+          for (int u = 0; u < UB; ++u) {
+            const int e = eb + u * (NWV - 1);
+            if (e < ne && j < DK) io.obs_next[(size_t)(n0 + e) * d.S + 1 + 2 * D + j] = v[u] * d.s_ind;
+          }
+        }
       }
     }
   }
   __syncthreads();
 
-  // -- 3. write back what the trade pass produced
-  if (tid < ne) io.obs_next[(size_t)(n0 + tid) * d.S] = s_cash[tid] * d.s_cash;
+  // -- 3. reward and episode bookkeeping (binary64), reset of the envs whose episode ended
+  if (tid < ne) {
+    const int e = tid, n = n0 + e;
+    const double r = (s_a1[e] - s_a0[e]) * (double)d.rho;
+    const RowInfo ri = s_row[e];
+    float cash = cash_in;
+    double ep = ep_ret + r;
+    if (ri.done) {
+      s.ep_sum[n] = ep_sum + ep;
+      s.ep_sqsum[n] = ep_sqsum + ep * ep;
+      s.ep_cnt[n] = ep_cnt + 1;
+      ep = 0.0;
+      cash = d.cash0;
+    }
+    s.ep_ret[n] = ep;
+    s.cash[n] = cash;
+    s.tau[n] = ri.done ? start_in : tau_in + 1;
+    io.obs_next[(size_t)n * d.S] = cash * d.s_cash;
+    io.reward[n] = (float)r;
+    io.done[n] = (uint8_t)ri.done;
+    if (io.logp) io.logp[n] = fmaf(-0.5f, s_e2sum[e], d.logp_const);
+  }
+
+  // -- 4. write back what the trade pass produced
+  // holdings after the step: after the sales + purchases, none after a reset
   for (int e = wave; e < ne; e += NWV) {
     const size_t g0 = (size_t)(n0 + e) * D;
+    const bool dn = s_row[e].done;
     for (int dd = lane; dd < D; dd += 64) {
-      io.obs_next[(size_t)(n0 + e) * d.S + 1 + D + dd] = (float)s_h[e * Dp + dd] * d.s_hold;
-      if (io.shares) io.shares[g0 + dd] = s_q[e * Dp + dd];
+      const int32_t q = s_q[e * Dp + dd];
+      const int32_t h = dn ? 0 : s_h[e * Dp + dd] + max(q, 0);
+      io.obs_next[(size_t)(n0 + e) * d.S + 1 + D + dd] = (float)h * d.s_hold;
+      if (io.shares) io.shares[g0 + dd] = q;
     }
   }
   for (int dd = wave; dd < D; dd += NWV)
-    for (int e = lane; e < ne; e += 64) s.h[(size_t)dd * d.N + n0 + e] = s_h[e * Dp + dd];
+    for (int e = lane; e < ne; e += 64) {
+      const int o = e * Dp + dd;
+      s.h[(size_t)dd * d.N + n0 + e] = s_row[e].done ? 0 : s_h[o] + max(s_q[o], 0);
+    }
 }
 
 size_t env_lds(int E, int D) {
   const int Dp = D | 1;
-  return (size_t)6 * E * Dp * 4 + (size_t)E * (sizeof(RowInfo) + sizeof(float) + sizeof(double));
+  return (size_t)7 * E * Dp * 4 + (size_t)E * (sizeof(RowInfo) + 2 * sizeof(float) + 2 * sizeof(double));
 }
 
 // ------------------------------------------------------------ state plumbing
