@@ -486,7 +486,7 @@ size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 }  // namespace
 
 // partial products of a split weight gradient: up to 8 copies of the largest (Hd x Hd; S <= 2 Hd assumed else fewer splits)
-static size_t splitk_floats(int B, int Hd) {
+static size_t splitk_floats(int Hd) {
   const size_t a = (size_t)8 * Hd * Hd, b = (size_t)CS_MAX_CHUNKS * Hd;  // split products / column-sum chunks
   return a > b ? a : b;
 }
@@ -495,7 +495,7 @@ size_t ppo_scratch_bytes(int B, int Hd, int D, int S) {
   const size_t f = 4, Sp = (size_t)(S + 3) / 4 * 4;
   return align256((size_t)B * Sp * f) + 4 * align256((size_t)B * Hd * f) + 2 * align256((size_t)B * D * f) +
          2 * align256((size_t)B * Hd * f) + 2 * align256((size_t)B * f) + align256((size_t)((B + 7) / 8) * 4 * f) +
-         align256(splitk_floats(B, Hd) * f);
+         align256(splitk_floats(Hd) * f);
 }
 
 hipError_t launch_ppo_grads(hipStream_t st, const pr_ppo_config &c, const float *obs, const float *act,
@@ -523,7 +523,7 @@ hipError_t launch_ppo_grads(hipStream_t st, const pr_ppo_config &c, const float 
   w.dzc = take((size_t)B * 4);
   const int blocks = (B + 7) / 8;
   w.partial = take((size_t)blocks * 4 * 4);
-  w.splitk_floats = splitk_floats(B, Hd);
+  w.splitk_floats = splitk_floats(Hd);
   w.splitk = take(w.splitk_floats * 4);
   // gather once, both forwards (each network keeps its own activations), the loss, both backward passes
   hipLaunchKernelGGL(gather_pad_kernel, dim3((unsigned)((B + 3) / 4)), dim3(256), 0, st, B, S, Sp, obs, rows, w.xp);
