@@ -594,6 +594,7 @@ def test_population_cycle_rank_refill_and_roll_again():
 REPLAY_CASES = [
     # name, base workload, overrides, table rows, H, T, schedule
     ("tiny_stepwise", "tiny", dict(n_envs=70), 97, 24, 64, pr.PR_SCHED_STEPWISE),
+    ("no_indicators_stepwise", "tiny", dict(n_envs=33, n_stocks=3, n_ind=0), 61, 16, 40, pr.PR_SCHED_STEPWISE),
     ("dow30_fused", "large", dict(n_envs=192, hidden=256, cost=2.0e-3), 301, 40, 100, 1),
     ("hundred_stocks_stepwise", "large", dict(n_envs=200, n_stocks=100, hidden=256, cost=2.0e-3), 211, 40, 90,
      pr.PR_SCHED_STEPWISE),
