@@ -404,22 +404,30 @@ __global__ __launch_bounds__(NW * 64) void mlp_tiles_kernel(TileArgs a) {
     }
   };
 
+  // The first tile's rows are requested before anything else, so that they travel while the tile is cleared and
+  // the first network's biases and output weights are staged; every tile's first weight blocks are requested
+  // before the barrier that completes its inputs.
+  int64_t t = blockIdx.x;
+  int staged_agent = -1;
+  if (t < ntiles) fetch(t);
   // k columns beyond the last group (when Kp > 4 * groups) are never written by stash: clear the tile once
   for (int i = tid; i < BM * a.xpitch / 4; i += NT) reinterpret_cast<uint32_t *>(ldsX)[i] = 0u;
   __syncthreads();
-
-  int64_t t = blockIdx.x;
-  int staged_agent = -1;
   if (t < ntiles) {
-    fetch(t);
+    const int agent = (int)(((a.row_base + t * BM) % a.N) / a.envs_per_agent);
+    stage_net<NT>(net_of(a.net, agent), ldsBias, ldsW3, tid);
+    staged_agent = agent;
     stash();
   }
+  const int lane_p = tid & 63, ct0_p = __builtin_amdgcn_readfirstlane(tid >> 6) * CTH;
+  u32x4 ring[ring_depth(CTH)][CTH];
   for (; t < ntiles; t += gridDim.x) {
     const int64_t row0 = t * BM;
     const int64_t tn = t + gridDim.x;
     const bool more = tn < ntiles;
     const int agent = (int)(((a.row_base + row0) % a.N) / a.envs_per_agent);
     const Net net = net_of(a.net, agent);
+    if (ct0_p < net.nct[0]) prime<CTH, ring_depth(CTH)>(ring, net.W[0], net.nkb[0], net.nct[0], ct0_p, lane_p);
     if (agent != staged_agent) {
       __syncthreads();  // the previous tile's output layer may still read its weights and biases
       stage_net<NT>(net, ldsBias, ldsW3, tid);
@@ -428,8 +436,7 @@ __global__ __launch_bounds__(NW * 64) void mlp_tiles_kernel(TileArgs a) {
     __syncthreads();  // input tile, biases and W3 complete; previous tile's output layer is done with ldsH
     const int O_dim = net.out_dim;
     float *Y = a.Y + row0 * O_dim;
-    u32x4 ring[ring_depth(CTH)][CTH];
-    mlp_tile<BF16, NW, CTH, false, NKB1, NKB2, false, false>(
+    mlp_tile<BF16, NW, CTH, false, NKB1, NKB2, true, false>(
         net, ring, ldsX, a.xpitch, ldsH, a.hpitch, ldsBias, ldsW3, tid,
         [&]() {
           if (more) fetch(tn);
