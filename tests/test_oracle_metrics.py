@@ -118,3 +118,39 @@ def test_value_curve_agrees_with_the_rewards_of_the_rollout():
     assert np.all(L == 9)                      # the step that reaches the horizon carries the flag
     dv = (V[1:10] - V[:9]) * w.reward_scale
     np.testing.assert_allclose(dv, out["reward"][:9], rtol=1e-5, atol=1e-7)
+
+
+def _table2():
+    import pathlib
+    rows = []
+    for line in (pathlib.Path(__file__).parent / "golden" / "table2_trading_metrics.txt").read_text().splitlines():
+        if line and not line.startswith("#"):
+            p = line.split()
+            rows.append((p[0],) + tuple(float(x) for x in p[1:]))
+    assert len(rows) == 3
+    return rows
+
+
+@pytest.mark.parametrize("row", _table2(), ids=lambda r: r[0])
+def test_definitions_reproduce_the_papers_printed_table(row):
+    """Table 2 prints cumulative return, annual return, maximum drawdown and Calmar ratio of three strategies over
+    254 trading days.  A daily value curve with the printed cumulative return and the printed maximum drawdown
+    (rise to a peak, fall by the drawdown, rise monotonically to the end) must get the printed annual return
+    (within the rounding of the two printed figures: geometric annualisation with 252 periods a year) and the printed Calmar ratio (to 0.01)."""
+    name, cum, annual, vol, mdd, sharpe, calmar = row
+    L = 254
+    end, peak = 1.0 + cum / 100.0, 1.15
+    trough = peak * (1.0 + mdd / 100.0)
+    V = np.concatenate([np.linspace(1.0, peak, 40), np.linspace(peak, trough, 21)[1:],
+                        np.linspace(trough, end, L + 2 - 60)[1:]])
+    assert V.size == L + 1 and trough < peak < end
+    got = _m(V, periods=252.0)
+    assert 100.0 * got[0] == pytest.approx(cum, abs=1e-9)
+    # both figures are printed to 0.001 %: half a unit of the input's rounding plus half a unit of the output's
+    assert 100.0 * got[1] == pytest.approx(annual, abs=1.1e-3)
+    # (one trading day more or less in the window would move it by 0.2-0.6 %)
+    assert abs(100.0 * ((1.0 + cum / 100.0) ** (252.0 / 253.0) - 1.0) - annual) > 0.1
+    assert -100.0 * got[3] == pytest.approx(mdd, abs=1e-9)
+    assert got[5] == pytest.approx(calmar, abs=1e-2)                # printed to 0.01
+    # an arithmetic annualisation (cum * 252 / 254) or the plain cumulative figure would miss the printed value
+    assert abs(cum * 252.0 / 254.0 - annual) > 0.05 and abs(cum - annual) > 0.3
