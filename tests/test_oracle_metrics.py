@@ -154,3 +154,25 @@ def test_definitions_reproduce_the_papers_printed_table(row):
     assert got[5] == pytest.approx(calmar, abs=1e-2)                # printed to 0.01
     # an arithmetic annualisation (cum * 252 / 254) or the plain cumulative figure would miss the printed value
     assert abs(cum * 252.0 / 254.0 - annual) > 0.05 and abs(cum - annual) > 0.3
+
+
+@pytest.mark.parametrize("row", _table2(), ids=lambda r: r[0])
+def test_sharpe_form_is_consistent_with_the_printed_table(row):
+    """A daily series with the printed volatility (returns m +/- s, alternating) compounding to the printed
+    cumulative return has sqrt(252) mean / std within 0.02 of the printed Sharpe ratio for all three strategies
+    (the exact series is not printed, so this pins the form -- mean over deviation of per-period returns, zero
+    risk-free rate -- not the last digit); annual return / annual volatility would be off by 0.2 to 0.7."""
+    name, cum, annual, vol, mdd, sharpe, calmar = row
+    L = 254
+    eps = np.where(np.arange(L) % 2 == 0, 1.0, -1.0)
+    s = vol / 100.0 / np.sqrt(252.0) / np.sqrt(L / (L - 1.0))      # sample deviation of m + s eps is s sqrt(L/(L-1))
+    lo, hi = 0.0, 0.01
+    for _ in range(200):                                            # bisection on the mean
+        m = 0.5 * (lo + hi)
+        lo, hi = (m, hi) if np.prod(1.0 + m + s * eps) < 1.0 + cum / 100.0 else (lo, m)
+    V = np.concatenate([[1.0], np.cumprod(1.0 + m + s * eps)])
+    got = _m(V, periods=252.0)
+    assert 100.0 * got[0] == pytest.approx(cum, abs=1e-6)
+    assert 100.0 * got[2] == pytest.approx(vol, rel=1e-9)
+    assert got[4] == pytest.approx(sharpe, abs=0.02)
+    assert abs(annual / vol - sharpe) > 0.2
