@@ -46,6 +46,13 @@ struct Op<true> {
                                                 0);
   }
   static __device__ inline void store(unsigned char *p, float v) { *reinterpret_cast<__bf16 *>(p) = (__bf16)v; }
+  // four consecutive elements, p 8-byte aligned
+  static __device__ inline void store4(unsigned char *p, const f32x4 &v) {
+    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+    bf16x4 t;
+    t[0] = (__bf16)v[0], t[1] = (__bf16)v[1], t[2] = (__bf16)v[2], t[3] = (__bf16)v[3];
+    *reinterpret_cast<bf16x4 *>(p) = t;
+  }
 };
 
 template <>
@@ -60,6 +67,8 @@ struct Op<false> {
     c = __builtin_amdgcn_mfma_f32_32x32x2f32(af[3], bf[3], c, 0, 0, 0);
   }
   static __device__ inline void store(unsigned char *p, float v) { *reinterpret_cast<float *>(p) = v; }
+  // four consecutive elements, p 16-byte aligned
+  static __device__ inline void store4(unsigned char *p, const f32x4 &v) { *reinterpret_cast<f32x4 *>(p) = v; }
 };
 
 // tanh to a few 1e-7 relative: odd Taylor polynomial below 1/4, 1 - 2/(e^{2|x|}+1) above.
@@ -146,7 +155,7 @@ __device__ inline void layer_from_global(f32x16 (&acc)[RT][CT], unsigned char *l
   using O = Op<BF16>;
   constexpr int BM = 32 * RT;
   constexpr int KC = PD * O::KB;             // inputs per staged chunk (power of two)
-  constexpr int NPRE = BM * KC / kThreads;   // elements each thread stages per chunk
+  constexpr int NPRE = BM * KC / 4 / kThreads;  // groups of four columns each thread stages per chunk
   const int lane = tid & 63;
   const int arow = lane & 31, g = lane >> 5;
   const int nch = (nkb + PD - 1) / PD;
@@ -165,21 +174,35 @@ __device__ inline void layer_from_global(f32x16 (&acc)[RT][CT], unsigned char *l
       }
   }
 
-  float pre[NPRE];
+  // a thread moves groups of four consecutive columns of one row: one 16-byte load (rows are only 4-byte
+  // aligned, which a global load allows) and one 8- or 16-byte LDS store; the group that straddles the end of
+  // the row is read element by element
+  f32x4 pre[NPRE];
   auto gload = [&](int ch) {
 #pragma unroll
     for (int i = 0; i < NPRE; ++i) {
       const int idx = tid + kThreads * i;
-      const int row = idx / KC, col = ch * KC + (idx % KC);
-      pre[i] = (row < nrows && col < S) ? X[(row0 + row) * ldx + col] : 0.0f;
+      const int row = idx / (KC / 4), col = ch * KC + 4 * (idx % (KC / 4));
+      f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (row < nrows) {
+        const float *src = X + (row0 + row) * ldx + col;
+        if (col + 3 < S) {
+          v = *reinterpret_cast<const f32x4 *>(src);
+        } else {
+          if (col < S) v[0] = src[0];
+          if (col + 1 < S) v[1] = src[1];
+          if (col + 2 < S) v[2] = src[2];
+        }
+      }
+      pre[i] = v;
     }
   };
   auto sstore = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < NPRE; ++i) {
       const int idx = tid + kThreads * i;
-      const int row = idx / KC, col = idx % KC;
-      O::store(ldsX + buf * xbuf + (size_t)row * xpitch + col * O::ESZ, pre[i]);
+      const int row = idx / (KC / 4), col = 4 * (idx % (KC / 4));
+      O::store4(ldsX + buf * xbuf + (size_t)row * xpitch + col * O::ESZ, pre[i]);
     }
   };
 
