@@ -472,6 +472,110 @@ __global__ __launch_bounds__(NW * 64) void mlp_tiles_kernel(TileArgs a) {
 }
 
 
+// ------------------------------------------------ whole-tile kernel for wide inputs
+// Observation rows that do not fit in LDS next to the hidden tile (S > 320: a hundred and more stocks) or an
+// output layer with several feature tiles: the same tile engine, but layer 1's activations arrive in chunks of
+// CC input columns through two LDS buffers.  A chunk is fetched into registers (16-byte loads; rows need only be
+// 4-byte aligned) behind the matrix work of the chunk before it, converted and dropped into the other buffer;
+// one barrier per chunk; the weight ring runs on across the chunks.  Rows past `rows` (ragged last tile) are
+// read as zeros and not stored.
+struct WideArgs {
+  const float *X;
+  int64_t ldx, rows;
+  int64_t row_base;
+  float *Y;
+  PackedNet net;
+  int32_t N, envs_per_agent;
+  int32_t S;
+  int32_t cpitch, hpitch;
+};
+
+template <int NW, int CTH, bool WIDE_OUT, int CC>
+__global__ __launch_bounds__(NW * 64) void mlp_wide_kernel(WideArgs a) {
+  using namespace tile;
+  using O = tile::Op<true>;
+  constexpr int NT = NW * 64;
+  constexpr int NG = BM * CC / 4 / NT;  // 16-byte groups per thread and chunk
+  constexpr int CKB = CC / O::KB;       // k-blocks per chunk
+  constexpr int PD = ring_depth(CTH);
+  static_assert(NG >= 1 && CKB % PD == 0, "chunk geometry");
+  extern __shared__ __align__(16) unsigned char lds[];
+  unsigned char *ldsH = lds;
+  unsigned char *ldsC = lds + (size_t)BM * a.hpitch;  // two chunk buffers
+  const size_t cbuf = (size_t)BM * a.cpitch;
+  u32x4 *ldsW3 = reinterpret_cast<u32x4 *>(ldsC + 2 * cbuf);
+  float *ldsBias = reinterpret_cast<float *>(ldsW3 + (WIDE_OUT ? 0 : (size_t)a.net.nkb[2] * 64));
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int ct0 = __builtin_amdgcn_readfirstlane(tid >> 6) * CTH;
+  const int S = a.S;
+  const int64_t ntiles = (a.rows + BM - 1) / BM;
+  int staged_agent = -1;
+
+  for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const int64_t row0 = t * BM;
+    const int nrows = (int)min((int64_t)BM, a.rows - row0);
+    const int agent = (int)(((a.row_base + row0) % a.N) / a.envs_per_agent);
+    const Net net = net_of(a.net, agent);
+    const int nkb = net.nkb[0], nch = (nkb + CKB - 1) / CKB;
+
+    f32x4 pre[NG];
+    auto fetch = [&](int ch) {
+#pragma unroll
+      for (int i = 0; i < NG; ++i) {
+        const int idx = tid + NT * i;
+        const int row = idx / (CC / 4), col = ch * CC + 4 * (idx % (CC / 4));
+        f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (row < nrows) {
+          const float *src = a.X + (row0 + row) * a.ldx + col;
+          if (col + 3 < S) {
+            v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(src));
+          } else {
+            if (col < S) v[0] = src[0];
+            if (col + 1 < S) v[1] = src[1];
+            if (col + 2 < S) v[2] = src[2];
+          }
+        }
+        pre[i] = v;
+      }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+      for (int i = 0; i < NG; ++i) {
+        const int idx = tid + NT * i;
+        const int row = idx / (CC / 4), c4 = 4 * (idx % (CC / 4));
+        O::store4(ldsC + buf * cbuf + (size_t)row * a.cpitch + c4 * O::ESZ, pre[i][0], pre[i][1], pre[i][2], pre[i][3]);
+      }
+    };
+
+    fetch(0);
+    if (agent != staged_agent) {
+      __syncthreads();  // the previous tile's output layer may still read its weights and biases
+      stage_net<NT>(net, ldsBias, WIDE_OUT ? nullptr : ldsW3, tid);
+      staged_agent = agent;
+    }
+    float *Y = a.Y + row0 * net.out_dim;
+    const int O_dim = net.out_dim;
+    u32x4 ring[PD][CTH];
+    mlp_tile<true, NW, CTH, WIDE_OUT, 0, 0, true, false>(
+        net, ring, nullptr, 0, ldsH, a.hpitch, ldsBias, ldsW3, tid, [] {}, [] {},
+        [&](int b, int f, float y) {
+          if (b < nrows) Y[(size_t)b * O_dim + f] = y;
+        },
+        [&](f32x16 (&acc)[CTH][2], u32x4 (&rg)[PD][CTH], bool act) {
+          if (act) prime<CTH, PD>(rg, net.W[0], nkb, net.nct[0], ct0, lane);
+          for (int ch = 0; ch < nch; ++ch) {
+            stash(ch & 1);
+            __syncthreads();  // chunk ch complete; everybody is done with the buffer chunk ch + 1 goes into
+            if (ch + 1 < nch) fetch(ch + 1);
+            if (act)
+              mma_layer_range<true, CTH, 2, PD>(acc, rg, ldsC + (ch & 1) * cbuf, a.cpitch, ch * CKB,
+                                                min(nkb, (ch + 1) * CKB), nkb, net.W[0], net.nct[0], ct0, 0, lane);
+          }
+        });
+    __syncthreads();  // the hidden tile and the chunk buffers are free again
+  }
+}
+
 // ------------------------------------------------ 128-row value-head kernel
 // The critic (one output feature, Sec. 4.1) over a long buffer of observations.
 // A 128-row tile halves the weight traffic per row of the 64-row kernel above:
@@ -916,6 +1020,51 @@ static bool try_launch_value(hipStream_t st, const PackedNet &net, int64_t rows,
   return true;
 }
 
+template <int CTH, bool WIDE_OUT, int CC>
+static hipError_t launch_wide(hipStream_t st, const WideArgs &a, unsigned blocks, size_t lds) {
+  auto kern = mlp_wide_kernel<8, CTH, WIDE_OUT, CC>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(512), lds, st, a);
+  return hipGetLastError();
+}
+
+// The wide-input kernel covers bf16 networks with 512 or 1024 hidden units whatever the input width, with one
+// output feature tile (weights in LDS) or several (streamed); any row stride, any number of rows.
+static bool try_launch_wide(hipStream_t st, const PackedNet &net, int64_t rows, int64_t row_base, const float *X,
+                            int64_t ldx, float *Y, int32_t N, int32_t envs_per_agent, hipError_t *err) {
+  const int Hd = net.out_dim[0];
+  if (!net.bf16 || (Hd != 512 && Hd != 1024) || net.out_dim[1] != Hd || (reinterpret_cast<uintptr_t>(X) & 3u)) return false;
+  if (net.nct[2] > 32) return false;
+  if (envs_per_agent < N && envs_per_agent % tile::BM != 0) return false;  // a tile must not straddle two agents
+  // measured: with 512 hidden units and at most a tile or two per compute unit the chunk-staged kernel below is
+  // as fast or faster (its four-wavefront workgroups start sooner); long buffers and 1024 hidden units win here
+  if (Hd == 512 && rows < (int64_t)4 * tile::BM * compute_units()) return false;
+  const bool wide_out = net.nct[2] > 1;
+  const int cc = Hd == 512 ? 128 : 64;
+  WideArgs a;
+  a.X = X, a.ldx = ldx, a.rows = rows, a.row_base = row_base, a.Y = Y, a.net = net, a.N = N;
+  a.envs_per_agent = envs_per_agent, a.S = net.in_dim[0];
+  a.cpitch = tile::tile_pitch(cc, 2);
+  a.hpitch = tile::tile_pitch(Hd, 2);
+  const size_t lds = (size_t)tile::BM * a.hpitch + 2 * (size_t)tile::BM * a.cpitch +
+                     (wide_out ? 0 : (size_t)net.nkb[2] * 1024) +
+                     (size_t)(net.nct[0] + net.nct[1] + net.nct[2]) * 32 * 4;
+  if (lds > 160 * 1024) return false;
+  const int64_t ntiles = (rows + tile::BM - 1) / tile::BM;
+  const unsigned blocks = (unsigned)(ntiles < compute_units() ? ntiles : compute_units());
+  if (Hd == 512)
+    *err = wide_out ? launch_wide<2, true, 128>(st, a, blocks, lds) : launch_wide<2, false, 128>(st, a, blocks, lds);
+  else
+    *err = wide_out ? launch_wide<4, true, 64>(st, a, blocks, lds) : launch_wide<4, false, 64>(st, a, blocks, lds);
+  return true;
+}
+
 hipError_t launch_mlp(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx, float *Y,
                       int32_t N, int32_t envs_per_agent) {
   Shape s;
@@ -945,6 +1094,11 @@ hipError_t launch_mlp(hipStream_t st, const PackedNet &net, int64_t rows, const 
       row_offset += full;
       rows -= full;
     }
+  }
+  if (rows > 0) {
+    // wide inputs or outputs: the chunked whole-tile kernel, ragged tail included
+    hipError_t terr = hipSuccess;
+    if (try_launch_wide(st, net, rows, row_offset, X, ldx, Y, N, envs_per_agent, &terr)) return terr;
   }
   const int esz = net.bf16 ? 2 : 4, KB = kblock(net.bf16);
   const int pd = s.cth >= 8 ? 2 : 4;

@@ -21,6 +21,7 @@
 #pragma once
 
 #include "pod_internal.h"
+#include <type_traits>
 
 namespace pod {
 namespace tile {
@@ -174,6 +175,55 @@ __device__ inline void mma_layer(f32x16 (&acc)[CT][NBT], u32x4 (&ring)[PD][CT], 
       u32x4 x[NBT];
 #pragma unroll
       for (int t = 0; t < NBT; ++t) x[t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)t * 32 * pitch + kb * 32);
+#pragma unroll
+      for (int c = 0; c < CT; ++c)
+#pragma unroll
+        for (int t = 0; t < NBT; ++t) O::mma(ring[s][c], x[t], acc[c][t]);
+    }
+  }
+}
+
+// k-blocks [kb_lo, kb_hi) of a layer whose activations arrive in chunks: ldsX holds the chunk that starts at k-block
+// kb_lo.  kb_lo is a multiple of PD; kb_hi is a multiple of PD or equals nkb.  The ring runs on across the calls
+// (primed once for the layer; refills are addressed by the layer-wide k-block index).
+template <bool BF16, int CT, int NBT, int PD>
+__device__ inline void mma_layer_range(f32x16 (&acc)[CT][NBT], u32x4 (&ring)[PD][CT], const unsigned char *ldsX,
+                                       int pitch, int kb_lo, int kb_hi, int nkb, const u32x4 *W, int nct, int ct0,
+                                       int bt0, int lane) {
+  using O = Op<BF16>;
+  const int brow = lane & 31, g = lane >> 5;
+  const unsigned char *xbase = ldsX + (size_t)(bt0 * 32 + brow) * pitch + 16 * g;
+  const u32x4 *wp[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) wp[c] = W + (size_t)min(ct0 + c, nct - 1) * 64 + lane;
+  int kb0 = kb_lo;
+  for (; kb0 + PD <= kb_hi; kb0 += PD) {
+#pragma unroll
+    for (int s = 0; s < PD; ++s) {
+      const int kb = kb0 + s;
+      u32x4 x[NBT];
+#pragma unroll
+      for (int t = 0; t < NBT; ++t)
+        x[t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)t * 32 * pitch + (kb - kb_lo) * 32);
+#pragma unroll
+      for (int c = 0; c < CT; ++c)
+#pragma unroll
+        for (int t = 0; t < NBT; ++t) O::mma(ring[s][c], x[t], acc[c][t]);
+      const int kn = min(kb + PD, nkb - 1);
+#pragma unroll
+      for (int c = 0; c < CT; ++c) ring[s][c] = wp[c][(size_t)kn * nct * 64];
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  const int rem = kb_hi - kb0;  // < PD blocks left (only at the end of the layer), already in ring[0 .. rem-1]
+#pragma unroll
+  for (int s = 0; s < PD - 1; ++s) {
+    if (s < rem) {
+      const int kb = kb0 + s;
+      u32x4 x[NBT];
+#pragma unroll
+      for (int t = 0; t < NBT; ++t)
+        x[t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)t * 32 * pitch + (kb - kb_lo) * 32);
 #pragma unroll
       for (int c = 0; c < CT; ++c)
 #pragma unroll
@@ -352,11 +402,16 @@ constexpr int ring_depth(int cth) { return cth >= 8 ? 2 : 4; }
 // KSPLIT > 1 (RAW_OUT, one output feature tile, NKB2 known): the output layer's k range is split over KSPLIT
 // wavefronts per batch tile, so that all 2 KSPLIT wavefronts share its matrix work; the sink is then called
 // as sink(row, feature, partial_sum, part) and the caller adds the KSPLIT parts.
+// Layer1: by default layer 1 reads a whole input tile from ldsX.  A caller whose input rows do not fit in LDS passes
+// a functor instead; it is called by EVERY wavefront as layer1(acc, ring, active) (it may contain barriers), must
+// leave layer 1's sums of the active wavefronts in acc, and owns the ring while it runs.
+struct WholeTileLayer1 {};
 template <bool BF16, int NW, int CTH, bool WIDE_OUT, int NKB1, int NKB2, bool PRIMED, bool RAW_OUT, int KSPLIT = 1,
-          class Early, class Late, class Sink>
+          class Early, class Late, class Sink, class Layer1 = WholeTileLayer1>
 __device__ inline void mlp_tile(const Net &net, u32x4 (&ring)[ring_depth(CTH)][CTH], const unsigned char *ldsX,
                                 int xpitch, unsigned char *ldsH, int hpitch, const float *ldsBias,
-                                const u32x4 *ldsW3, int tid, Early early, Late late, Sink sink) {
+                                const u32x4 *ldsW3, int tid, Early early, Late late, Sink sink,
+                                Layer1 layer1 = Layer1()) {
   constexpr int PD = ring_depth(CTH);
   // the wavefront index is uniform: tell the compiler, so that block addresses live in scalar registers
   const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -366,7 +421,10 @@ __device__ inline void mlp_tile(const Net &net, u32x4 (&ring)[ring_depth(CTH)][C
   {
     f32x16 acc[CTH][2];
     zero_acc<CTH, 2>(acc);
-    if (act) {
+    if constexpr (!std::is_same<Layer1, WholeTileLayer1>::value) {
+      layer1(acc, ring, act);
+      if (act) prime<CTH, PD>(ring, net.W[1], net.nkb[1], net.nct[1], ct0, lane);
+    } else if (act) {
       if (!PRIMED) prime<CTH, PD>(ring, net.W[0], net.nkb[0], net.nct[0], ct0, lane);
       if (NKB1 > 0)
         mma_layer_static<BF16, CTH, 2, PD, NKB1>(acc, ring, ldsX, xpitch, net.W[0], net.nct[0], ct0, 0, lane);
