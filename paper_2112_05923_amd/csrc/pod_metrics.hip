@@ -81,12 +81,23 @@ __global__ __launch_bounds__(ME * MW) void metrics_kernel(MetricArgs a) {
     for (int d0 = 0; d0 < D; d0 += MB) {
       const int bw = min(MB, D - d0);
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // the previous block's reads are done
+      // all of the block's loads are issued before the first of them is stored (one round trip per block, not one
+      // per pair of rows)
+      float pr[ME / RPI], ho[ME / RPI];
+#pragma unroll
+      for (int rr = 0; rr < ME / RPI; ++rr) {
+        const int row = RPI * rr + sub;
+        const bool ok = c < bw && n0 + row < N;
+        const float *o = base + (size_t)(n0 + (ok ? row : 0)) * S;
+        pr[rr] = ok ? __builtin_nontemporal_load(o + 1 + d0 + c) : 0.0f;
+        ho[rr] = ok ? __builtin_nontemporal_load(o + 1 + D + d0 + c) : 0.0f;
+      }
+#pragma unroll
       for (int rr = 0; rr < ME / RPI; ++rr) {
         const int row = RPI * rr + sub;
         if (c < bw && n0 + row < N) {
-          const float *o = base + (size_t)(n0 + row) * S;
-          stage[row * MP + c] = o[1 + d0 + c];
-          stage[row * MP + MB + c] = o[1 + D + d0 + c];
+          stage[row * MP + c] = pr[rr];
+          stage[row * MP + MB + c] = ho[rr];
         }
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // LDS executes a wavefront's accesses in order
