@@ -112,8 +112,22 @@ __global__ __launch_bounds__(kEnvThreads) void env_step_kernel(EnvDims d, EnvSta
     tau_in = s.tau[n0 + tid], start_in = s.start[n0 + tid];
     s_row[tid] = rows_of(d, tau_in, start_in, n0 + tid);
   }
-  for (int dd = wave; dd < D; dd += NWV)
-    for (int e = lane; e < ne; e += 64) s_h[e * Dp + dd] = s.h[(size_t)dd * d.N + n0 + e];
+  {
+    // holdings: up to 8 stocks per wavefront in flight (E <= 64: one env per lane), the rest (D > 64) in a plain loop
+    int32_t hreg[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int dd = wave + NWV * i;
+      hreg[i] = (dd < D && lane < ne) ? s.h[(size_t)dd * d.N + n0 + lane] : 0;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int dd = wave + NWV * i;
+      if (dd < D && lane < ne) s_h[lane * Dp + dd] = hreg[i];
+    }
+    for (int dd = wave + NWV * 8; dd < D; dd += NWV)
+      if (lane < ne) s_h[lane * Dp + dd] = s.h[(size_t)dd * d.N + n0 + lane];
+  }
   float mu0[U], eps0[U];  // first column chunk of the first U passes (the whole tile when D <= 64 and E <= U G)
 #pragma unroll
   for (int u = 0; u < U; ++u) {

@@ -347,8 +347,18 @@ __device__ inline void stage_net(const Net &net, float *ldsBias, u32x4 *ldsW3, i
     for (int i = tid; i < n; i += NT) ldsBias[off + i] = net.b[l][i];
     off += n;
   }
-  if (ldsW3 && net.nct[2] == 1)
-    for (int i = tid; i < net.nkb[2] * 64; i += NT) ldsW3[i] = net.W[2][i];
+  if (ldsW3 && net.nct[2] == 1) {
+    // four loads in flight per thread before the first LDS store (a plain copy loop pays one round trip per pass)
+    const int n3 = net.nkb[2] * 64;
+    for (int base = tid; base < n3; base += 4 * NT) {
+      u32x4 v[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] = net.W[2][min(base + j * NT, n3 - 1)];
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (base + j * NT < n3) ldsW3[base + j * NT] = v[j];
+    }
+  }
 }
 
 // Output layer with one feature tile: weights from LDS (block kb = 64 lanes x 16 B), activations from ldsH.
