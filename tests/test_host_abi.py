@@ -104,3 +104,24 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(pr, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libpodrollout.so"))
     with pytest.raises(FileNotFoundError):
         pr.lib()
+
+
+def test_bench_refuses_more_than_one_gpu_and_reads_the_recorded_traffic():
+    """bench.py is a one-GPU benchmark: --gpus 2 must exit with a message before touching a device.  The traffic
+    figure it reports is the recorded one only while the kernel sources still hash to the recorded digest."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stderr + r.stdout)
+    sys.path.insert(0, ROOT)
+    import bench
+    digest = bench.kernel_sources_digest()
+    assert re.fullmatch(r"[0-9a-f]{16}", digest)
+    text = open(os.path.join(ROOT, "profiles", "pmc_fused_large.txt")).read()
+    recorded = re.search(r"kernel_sources_digest: (\w+)", text).group(1)
+    got = bench.recorded_traffic("fused", "large")
+    if recorded == digest:
+        assert got == pytest.approx(float(re.search(r"hbm_bytes_per_launch: (\d+)", text).group(1)))
+    else:
+        assert got is None
