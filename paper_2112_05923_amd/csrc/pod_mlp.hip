@@ -878,9 +878,9 @@ hipError_t launch_pack_layer(hipStream_t st, const float *W, const float *b, int
   return hipGetLastError();
 }
 
-template <bool BF16, int CTH, int CTO, int TAG>
+template <bool BF16, int CTH, int CTO, int TAG, int RT = 2>
 static hipError_t launch_tagged(hipStream_t st, const MlpArgs &a, unsigned blocks, size_t lds) {
-  auto kern = mlp3_kernel<BF16, 2, CTH, CTO, TAG>;
+  auto kern = mlp3_kernel<BF16, RT, CTH, CTO, TAG>;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -1116,6 +1116,14 @@ hipError_t launch_mlp(hipStream_t st, const PackedNet &net, int64_t rows, const 
   const size_t lds = (size_t)BM * a.hpitch + 2 * (size_t)BM * a.xpitch;
   if (lds > 160 * 1024) return hipErrorInvalidValue;
   const unsigned blocks = (unsigned)((rows + BM - 1) / BM);
+  // fp32 networks on fewer 64-row tiles than compute units (4096 envs per step): 32-row tiles put twice as many
+  // compute units to work, and the fp32 matrix time per tile halves
+  if (!net.bf16 && s.cto == 1 && rows > 32 && (rows + BM - 1) / BM < compute_units()) {
+    const unsigned blocks32 = (unsigned)((rows + 31) / 32);
+    if (s.cth == 1) return launch_tagged<false, 1, 1, 0, 1>(st, a, blocks32, lds);
+    if (s.cth == 2) return launch_tagged<false, 2, 1, 0, 1>(st, a, blocks32, lds);
+    if (s.cth == 4) return launch_tagged<false, 4, 1, 0, 1>(st, a, blocks32, lds);
+  }
 #define POD_CASE(B, H, O_) \
   if ((net.bf16 != 0) == B && s.cth == H && s.cto == O_) return launch_one<B, H, O_>(st, a, blocks, lds);
   POD_CASE(true, 1, 1)
