@@ -34,7 +34,9 @@
  * closed forms, numpy std / maximum.accumulate / prod and the rollout's own
  * rewards for the trading metrics of Sec. 5.3 (whose annualisation period,
  * risk-free rate and deviation estimator the paper leaves open: parameters and
- * the sample estimator here).  The whole free-running rollout
+ * the sample estimator here); the per-agent network selection of a free-running
+ * population by equality with one single-agent run per agent and the numpy
+ * matmul chain on that agent's weights.  The whole free-running rollout
  * has no printed trajectory in the paper to compare with: parity unpinned for
  * the composition, pinned stage by stage.
  */

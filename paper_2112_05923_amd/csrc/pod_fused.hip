@@ -42,6 +42,11 @@ constexpr int kDp = DMAX + 1;    // odd row pitch: the per-env serial walks of t
 constexpr int IND_MAX = 9;       // 16-byte indicator groups per lane (lanes 64..511): D*K <= 252, D*K % 4 == 0
 constexpr int NT_IND = NT - 64;  // lanes that carry indicator values
 
+constexpr int MUP = 33;         // row pitch of a policy-mean plane (lanes of one store differ in the row: 32 would hit one bank)
+// Planes the output layer's k range is split into (one per group of wavefronts), by the compile-time k-block count
+// of the kernel instance.
+constexpr int mu_planes(int nkb2) { return (nkb2 > 0 && nkb2 % 4 == 0) ? 4 : 1; }
+
 struct Row {
   int32_t row_val;  // market row the portfolio is valued at (cursor + 1)
   int32_t row_obs;  // market row of the next observation (row 0 of the path after an episode end)
@@ -49,8 +54,20 @@ struct Row {
   int32_t pad;
 };
 
+// Byte offsets of the LDS regions, computed once on the host (the launch size, the shape check and the kernel
+// all read this one carve-up).  The env scratch arrays alias the hidden tile: they live between the end of the
+// output layer and the next step's first epilogue.  The policy-mean planes alias the head of the input region,
+// which is dead between layer 1 and the write of the next observation; the region is sized for whichever of the
+// two is larger.
+struct FusedLayout {
+  int32_t xpitch, hpitch;  // bytes per row of the input / hidden tile
+  int32_t off_x, off_w3, off_bias, off_h, off_p, off_row, off_cash, off_done;
+  int32_t total;
+};
+
 struct FusedArgs {
   EnvDims d;
+  FusedLayout L;
   EnvState st;
   const float *price, *ind;
   PackedNet actor;
@@ -65,7 +82,6 @@ struct FusedArgs {
   float *logp;             // opt [T, N]
   float *mu_out;           // opt [T, N, D]
   int32_t *shares;         // opt [T, N, D]
-  int32_t xpitch, hpitch;
   uint32_t d_magic, g_magic;  // ceil(2^32 / D), ceil(2^32 / (D K / 4))
 };
 
@@ -99,26 +115,23 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   const int n0 = blockIdx.x * E;
   const size_t N = (size_t)d.N;
 
-  // ---- LDS carve-up.  The env scratch arrays alias the hidden tile: they live between the end of the output
-  // layer and the next step's first epilogue.  The policy means alias the head of the input tile, which is dead
-  // between layer 1 and the write of the next observation.
+  // ---- LDS carve-up (see FusedLayout)
   unsigned char *ldsH = lds;
-  unsigned char *ldsX = ldsH + (size_t)BM * a.hpitch;
-  u32x4 *ldsW3 = reinterpret_cast<u32x4 *>(ldsX + (size_t)BM * a.xpitch);
-  float *ldsBias = reinterpret_cast<float *>(ldsW3 + (ACTOR ? (size_t)a.actor.nkb[2] * 64 : 0));
-  int32_t *s_h = reinterpret_cast<int32_t *>(ldsBias + (ACTOR ? (a.actor.nct[0] + a.actor.nct[1] + a.actor.nct[2]) * 32 : 0));
-  float *s_p = reinterpret_cast<float *>(s_h + E * Dp);  // prices the trades execute at
-  Row *s_row = reinterpret_cast<Row *>(s_p + E * Dp);
-  float *s_cash = reinterpret_cast<float *>(s_row + E);
-  int32_t *s_done = reinterpret_cast<int32_t *>(s_cash + E);  // episode-end flags of the step just taken
+  unsigned char *ldsX = lds + a.L.off_x;
+  u32x4 *ldsW3 = reinterpret_cast<u32x4 *>(lds + a.L.off_w3);
+  float *ldsBias = reinterpret_cast<float *>(lds + a.L.off_bias);
+  int32_t *s_h = reinterpret_cast<int32_t *>(lds + a.L.off_h);
+  float *s_p = reinterpret_cast<float *>(lds + a.L.off_p);  // prices the trades execute at
+  Row *s_row = reinterpret_cast<Row *>(lds + a.L.off_row);
+  float *s_cash = reinterpret_cast<float *>(lds + a.L.off_cash);
+  int32_t *s_done = reinterpret_cast<int32_t *>(lds + a.L.off_done);  // episode-end flags of the step just taken
   // scratch in the hidden tile
   Slot *s_slot = reinterpret_cast<Slot *>(ldsH);            // what the ledger needs per (env, stock), one 16-byte read
   int32_t *s_q = reinterpret_cast<int32_t *>(s_slot + E * Dp);  // executed shares, signed
   float *s_pv = reinterpret_cast<float *>(s_q + E * Dp);    // valuation prices
   float *s_e2 = s_pv + E * Dp;                              // squared noise
   // output-layer accumulators of the actor, one [E][32] plane per k part of that layer (summed in the pre-compute)
-  constexpr int KS = (NKB2 > 0 && NKB2 % 4 == 0) ? 4 : 1;
-  constexpr int MUP = 33;  // row pitch of a plane (lanes of one store differ in the row: 32 would hit one bank)
+  constexpr int KS = mu_planes(NKB2);
   float *s_mu = reinterpret_cast<float *>(ldsX);
 
   // ---- ledger lanes (wavefront 0): per-env scalars in registers for the whole rollout
@@ -131,7 +144,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     net = net_of(a.actor, (n0 % d.N) / a.envs_per_agent);
     stage_net<NT>(net, ldsBias, ldsW3, tid);
     // padded k columns of the input tile must read as zero
-    for (int i = tid; i < BM * a.xpitch / 4; i += NT) reinterpret_cast<uint32_t *>(ldsX)[i] = 0u;
+    for (int i = tid; i < BM * a.L.xpitch / 4; i += NT) reinterpret_cast<uint32_t *>(ldsX)[i] = 0u;
   }
   __syncthreads();
 
@@ -182,7 +195,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         s_p[e * Dp + dd] = v;
         const float sv = v * d.s_price;
         __builtin_nontemporal_store(sv, &obs_row[(size_t)(n0 + e) * S + 1 + dd]);
-        if (ACTOR) O::store1(ldsX + (size_t)e * a.xpitch + (DK + 1 + dd) * O::ESZ, sv);
+        if (ACTOR) O::store1(ldsX + (size_t)e * a.L.xpitch + (DK + 1 + dd) * O::ESZ, sv);
       }
     }
     if (tid >= 64) {
@@ -200,7 +213,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
           // observation rows are 4-byte aligned only; a 16-byte store needs no more than that
           __builtin_nontemporal_store(sv, reinterpret_cast<f32x4 *>(obs_row + (size_t)(n0 + e) * S + 1 + 2 * D + j));
           // (indicators lead the LDS tile, so a group of four is one aligned store)
-          if (ACTOR) O::store4(ldsX + (size_t)e * a.xpitch + j * O::ESZ, sv[0], sv[1], sv[2], sv[3]);
+          if (ACTOR) O::store4(ldsX + (size_t)e * a.L.xpitch + j * O::ESZ, sv[0], sv[1], sv[2], sv[3]);
         }
       }
     }
@@ -216,10 +229,10 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       const float sv = s_cash[tid] * d.s_cash;
       __builtin_nontemporal_store(sv, &obs_row[(size_t)(n0 + tid) * S]);
       if (ACTOR) {
-        O::store1(ldsX + (size_t)tid * a.xpitch + DK * O::ESZ, sv);
+        O::store1(ldsX + (size_t)tid * a.L.xpitch + DK * O::ESZ, sv);
         // the policy means were parked over the head of this tile: restore the zero k padding of every row
-        const int kp = (a.xpitch - 16) / O::ESZ;
-        for (int c = S; c < kp; ++c) O::store1(ldsX + (size_t)tid * a.xpitch + c * O::ESZ, 0.0f);
+        const int kp = (a.L.xpitch - 16) / O::ESZ;
+        for (int c = S; c < kp; ++c) O::store1(ldsX + (size_t)tid * a.L.xpitch + c * O::ESZ, 0.0f);
       }
     }
 #pragma unroll
@@ -237,7 +250,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         }
         const float sv = (float)h * d.s_hold;
         __builtin_nontemporal_store(sv, &obs_row[(size_t)(n0 + e) * S + 1 + D + dd]);
-        if (ACTOR) O::store1(ldsX + (size_t)e * a.xpitch + (DK + 1 + D + dd) * O::ESZ, sv);
+        if (ACTOR) O::store1(ldsX + (size_t)e * a.L.xpitch + (DK + 1 + D + dd) * O::ESZ, sv);
       }
     }
   };
@@ -305,7 +318,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
 
     if (ACTOR) {
       mlp_tile<BF16, NW, CTH, false, NKB1, NKB2, true, true, KS>(
-          net, ring, ldsX, a.xpitch, ldsH, a.hpitch, ldsBias, ldsW3, tid,
+          net, ring, ldsX, a.L.xpitch, ldsH, a.L.hpitch, ldsBias, ldsW3, tid,
           [&]() {
             fetch_step_inputs(t);
             fetch_market();
@@ -397,7 +410,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
 #pragma unroll
         for (int j = 0; j < CH; ++j) cash = sl[j].k < 0 ? cash + sl[j].val : cash;
       }
-      // Purchases in stock order, the rule of the reference in straight-line code:
+      // Purchases in stock order, the trading rule in straight-line code:
       //   m = floor(cash / u); q = min(k, max(m, 0)); if (q u > cash) q -= 1; cash -= q u        (binary32)
       // One lane per env walks a dependent chain on `cash`, so what counts is the length of that chain, not
       // the instruction count: no data-dependent branches (a branch taken for one lane costs all 64 the round
@@ -506,9 +519,57 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   }
 }
 
+// Kernel instance for a configuration: feature tiles per wavefront and, for the named shape, compile-time k-block
+// counts of layers 1 and 2 (0: read at run time).
 struct FusedShape {
   int cth, nkb1, nkb2;
 };
+
+FusedShape fused_shape(const pr_config &c) {
+  const int S = 1 + 2 * c.n_stocks + c.n_stocks * c.n_ind;
+  FusedShape f;
+  f.cth = (c.hidden / 32) / NW;
+  f.nkb1 = f.nkb2 = 0;
+  if (f.cth == 2 && (S + 15) / 16 == 19 && c.hidden / 16 == 32) f.nkb1 = 19, f.nkb2 = 32;
+  return f;
+}
+
+// The one carve-up of the kernel's LDS (bf16 operands).
+FusedLayout fused_layout(const pr_config &c, bool with_actor) {
+  const int D = c.n_stocks, S = 1 + 2 * D + D * c.n_ind, Hd = c.hidden;
+  constexpr int KB = 16, esz = 2;
+  const int nkb1 = (S + KB - 1) / KB, nct = Hd / 32;
+  FusedLayout L;
+  L.xpitch = tile_pitch(nkb1 * KB, esz);
+  L.hpitch = tile_pitch(Hd, esz);
+  // the env scratch (slots 16 B, executed shares, valuation prices, squared noise) must fit in the hidden tile
+  const size_t env_scratch = (size_t)7 * E * kDp * 4;
+  if ((size_t)BM * L.hpitch < env_scratch) L.hpitch = (int32_t)(((env_scratch + BM - 1) / BM + 15) / 16 * 16);
+  size_t off = (size_t)BM * L.hpitch;
+  L.off_x = (int32_t)off;
+  size_t xbytes = (size_t)BM * L.xpitch;
+  const size_t mu_bytes = with_actor ? (size_t)mu_planes(fused_shape(c).nkb2) * E * MUP * 4 : 0;
+  if (xbytes < mu_bytes) xbytes = (mu_bytes + 15) / 16 * 16;
+  off += xbytes;
+  L.off_w3 = (int32_t)off;
+  if (with_actor) off += (size_t)(Hd / KB) * 1024;  // output layer: one feature tile, Hd / 16 k-blocks of 1 KiB
+  L.off_bias = (int32_t)off;
+  if (with_actor) off += (size_t)(2 * nct + 1) * 32 * 4;
+  L.off_h = (int32_t)off;
+  off += (size_t)E * kDp * 4;
+  L.off_p = (int32_t)off;
+  off += (size_t)E * kDp * 4;
+  L.off_row = (int32_t)off;
+  off += (size_t)E * sizeof(Row);
+  L.off_cash = (int32_t)off;
+  off += (size_t)E * 4;
+  L.off_done = (int32_t)off;
+  off += (size_t)E * 4;
+  L.total = (int32_t)off;
+  return L;
+}
+
+constexpr size_t kLdsMax = kMaxLdsBytes;
 
 }  // namespace
 
@@ -521,32 +582,16 @@ bool fused_supported(const pr_config &c) {
   if (c.mlp_dtype != PR_MLP_BF16) return false;
   if (Hd % 32 != 0 || Hd < 256 || Hd > 512 || (Hd / 32) % NW != 0) return false;
   if (c.n_agents > 1 && (c.n_envs / c.n_agents) % 64 != 0) return false;
-  return fused_lds_bytes(c, true) + 1024 <= 160 * 1024;
+  return fused_lds_bytes(c, true) <= kLdsMax;
 }
 
-size_t fused_lds_bytes(const pr_config &c, bool with_actor) {
-  const int D = c.n_stocks, DK = c.n_stocks * c.n_ind, S = 1 + 2 * D + DK, Hd = c.hidden, Dp = kDp;
-  const int bf = c.mlp_dtype == PR_MLP_BF16, esz = bf ? 2 : 4, KB = bf ? 16 : 8;
-  const int kp = (S + KB - 1) / KB * KB;
-  size_t env_scratch = (size_t)7 * E * Dp * 4;
-  size_t hid = (size_t)BM * tile_pitch(Hd, esz);
-  if (hid < env_scratch) hid = env_scratch;
-  size_t n = hid + (size_t)BM * tile_pitch(kp, esz);
-  if (with_actor) n += (size_t)(Hd / KB) * 1024 + (size_t)(2 * (Hd / 32) + 1) * 32 * 4;
-  n += (size_t)2 * E * Dp * 4 + (size_t)E * (sizeof(Row) + sizeof(float) + sizeof(int32_t));
-  return n;
-}
+size_t fused_lds_bytes(const pr_config &c, bool with_actor) { return (size_t)fused_layout(c, with_actor).total; }
 
 template <bool ACTOR, int CTH, int NKB1, int NKB2>
 static hipError_t launch_fused_inst(hipStream_t st, const FusedArgs &a, unsigned blocks, size_t lds) {
-  auto kern = rollout_fused_kernel<true, CTH, NKB1, NKB2, ACTOR>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  constexpr auto kern = rollout_fused_kernel<true, CTH, NKB1, NKB2, ACTOR>;
+  const hipError_t e = allow_full_lds<kern>();
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(NT), lds, st, a);
   return hipGetLastError();
 }
@@ -572,28 +617,23 @@ hipError_t launch_rollout_fused(hipStream_t st, const pr_config &c, const EnvDim
   a.logp = out.logp;
   a.mu_out = mu_forced ? nullptr : out.mu;
   a.shares = out.shares;
-  const int KB = 16, esz = 2;
   const int DK = d.D * d.K;
-  a.xpitch = tile_pitch(actor.nkb[0] * KB, esz);
-  a.hpitch = tile_pitch(c.hidden, esz);
-  // the env scratch must fit in the hidden tile
-  const size_t env_scratch = (size_t)7 * E * kDp * 4;
-  if ((size_t)BM * a.hpitch < env_scratch) a.hpitch = (int32_t)((env_scratch + BM - 1) / BM + 15) / 16 * 16;
+  const bool with_actor = mu_forced == nullptr;
+  a.L = fused_layout(c, with_actor);
   a.d_magic = (uint32_t)((0x100000000ull + (uint64_t)d.D - 1) / (uint64_t)d.D);
   a.g_magic = (uint32_t)((0x100000000ull + (uint64_t)(DK / 4) - 1) / (uint64_t)(DK / 4));
   if (reinterpret_cast<uintptr_t>(ind) & 15u) return hipErrorInvalidValue;  // 16-byte indicator loads
-  const bool with_actor = mu_forced == nullptr;
-  // must mirror the carve-up at the top of the kernel
-  size_t lds = (size_t)BM * a.hpitch + (size_t)BM * a.xpitch;
-  if (with_actor) lds += (size_t)actor.nkb[2] * 1024 + (size_t)(actor.nct[0] + actor.nct[1] + actor.nct[2]) * 32 * 4;
-  lds += (size_t)2 * E * kDp * 4 + (size_t)E * (sizeof(Row) + sizeof(float) + sizeof(int32_t));
-  if (lds > 160 * 1024) return hipErrorInvalidValue;
+  const size_t lds = (size_t)a.L.total;
+  if (lds > kLdsMax) return hipErrorInvalidValue;
   const unsigned blocks = (unsigned)(d.N / E);
-  const int cth = (c.hidden / 32) / NW;
+  const FusedShape fs = fused_shape(c);
+  if (with_actor && (actor.nkb[0] * 32 + 16 != a.L.xpitch || actor.nkb[1] * 32 + 16 > a.L.hpitch ||
+                     actor.nkb[2] != actor.nkb[1] || actor.nct[2] != 1))
+    return hipErrorInvalidValue;  // the packed network is not the one the layout was made for
   if (!with_actor) return launch_fused_inst<false, 1, 0, 0>(st, a, blocks, lds);
-  if (cth == 2 && actor.nkb[0] == 19 && actor.nkb[1] == 32) return launch_fused_inst<true, 2, 19, 32>(st, a, blocks, lds);
-  if (cth == 2) return launch_fused_inst<true, 2, 0, 0>(st, a, blocks, lds);
-  if (cth == 1) return launch_fused_inst<true, 1, 0, 0>(st, a, blocks, lds);
+  if (fs.cth == 2 && fs.nkb1 == 19 && fs.nkb2 == 32) return launch_fused_inst<true, 2, 19, 32>(st, a, blocks, lds);
+  if (fs.cth == 2) return launch_fused_inst<true, 2, 0, 0>(st, a, blocks, lds);
+  if (fs.cth == 1) return launch_fused_inst<true, 1, 0, 0>(st, a, blocks, lds);
   return hipErrorInvalidValue;
 }
 

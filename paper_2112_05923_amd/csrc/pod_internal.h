@@ -6,9 +6,30 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "podrollout.h"
 
 namespace pod {
+
+// Kernels that use more than the default 64 KiB of dynamic LDS need the limit raised once per device (the
+// attribute belongs to that device's copy of the code object).  One bit per device ordinal and kernel; safe to
+// call from several host threads (a second call on a device is harmless).
+constexpr int kMaxLdsBytes = 160 * 1024;
+template <auto Kern>
+inline hipError_t allow_full_lds() {
+  static std::atomic<uint64_t> done{0};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (dev < 64 && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(Kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          kMaxLdsBytes);
+  if (e != hipSuccess) return e;
+  if (dev < 64) done.fetch_or(bit, std::memory_order_release);
+  return hipSuccess;
+}
 
 // ---------------------------------------------------------------- env state
 // Structure-of-arrays env state in the workspace; n is the fastest axis of

@@ -214,13 +214,8 @@ hipError_t launch_trading_metrics(hipStream_t st, int32_t T, int32_t N, int32_t 
   size_t lds = (size_t)MW * ME * MP * 4;
   if (lds < (size_t)MW * ME * sizeof(Chunk)) lds = (size_t)MW * ME * sizeof(Chunk);
   lds += (size_t)MW * ME * 4;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(metrics_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  const hipError_t e = allow_full_lds<metrics_kernel>();
+  if (e != hipSuccess) return e;
   const unsigned blocks = (unsigned)((N + ME - 1) / ME);
   hipLaunchKernelGGL(metrics_kernel, dim3(blocks), dim3(ME * MW), lds, st, a);
   return hipGetLastError();

@@ -26,69 +26,14 @@ namespace pod {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+using tile::f32x16;
+using tile::f32x4;
+using tile::u32x4;
+using tile::Op;  // operand types: k-block size, element size, the matrix instruction, LDS stores
+using tile::tanh_accurate;
 
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
-
-template <bool BF16>
-struct Op;
-
-template <>
-struct Op<true> {
-  static constexpr int KB = 16;   // inputs per k-block
-  static constexpr int ESZ = 2;   // bytes per LDS element
-  static __device__ inline void mma(const u32x4 &a, const u32x4 &b, f32x16 &c) {
-    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0,
-                                                0);
-  }
-  static __device__ inline void store(unsigned char *p, float v) { *reinterpret_cast<__bf16 *>(p) = (__bf16)v; }
-  // four consecutive elements, p 8-byte aligned
-  static __device__ inline void store4(unsigned char *p, const f32x4 &v) {
-    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-    bf16x4 t;
-    t[0] = (__bf16)v[0], t[1] = (__bf16)v[1], t[2] = (__bf16)v[2], t[3] = (__bf16)v[3];
-    *reinterpret_cast<bf16x4 *>(p) = t;
-  }
-};
-
-template <>
-struct Op<false> {
-  static constexpr int KB = 8;
-  static constexpr int ESZ = 4;
-  static __device__ inline void mma(const u32x4 &a, const u32x4 &b, f32x16 &c) {
-    const f32x4 af = __builtin_bit_cast(f32x4, a), bf = __builtin_bit_cast(f32x4, b);
-    c = __builtin_amdgcn_mfma_f32_32x32x2f32(af[0], bf[0], c, 0, 0, 0);
-    c = __builtin_amdgcn_mfma_f32_32x32x2f32(af[1], bf[1], c, 0, 0, 0);
-    c = __builtin_amdgcn_mfma_f32_32x32x2f32(af[2], bf[2], c, 0, 0, 0);
-    c = __builtin_amdgcn_mfma_f32_32x32x2f32(af[3], bf[3], c, 0, 0, 0);
-  }
-  static __device__ inline void store(unsigned char *p, float v) { *reinterpret_cast<float *>(p) = v; }
-  // four consecutive elements, p 16-byte aligned
-  static __device__ inline void store4(unsigned char *p, const f32x4 &v) { *reinterpret_cast<f32x4 *>(p) = v; }
-};
-
-// tanh to a few 1e-7 relative: odd Taylor polynomial below 1/4, 1 - 2/(e^{2|x|}+1) above.
-__device__ inline float tanh_accurate(float x) {
-  const float ax = fabsf(x);
-  const float x2 = x * x;
-  float ps = fmaf(x2, 62.0f / 2835.0f, -17.0f / 315.0f);
-  ps = fmaf(x2, ps, 2.0f / 15.0f);
-  ps = fmaf(x2, ps, -1.0f / 3.0f);
-  const float small = fmaf(x2 * x, ps, x);
-  const float e = __builtin_amdgcn_exp2f(ax * 2.8853900817779268f);  // exp(2|x|)
-  const float big = copysignf(1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f), x);
-  return ax < 0.25f ? small : big;
-}
-
-// tanh good to ~1e-7 absolute; used where the result is rounded to bf16 anyway.
-__device__ inline float tanh_fast(float x) {
-  const float e = __builtin_amdgcn_exp2f(x * 2.8853900817779268f);
-  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
-}
 
 struct MlpArgs {
   const float *X;
@@ -202,7 +147,7 @@ __device__ inline void layer_from_global(f32x16 (&acc)[RT][CT], unsigned char *l
     for (int i = 0; i < NPRE; ++i) {
       const int idx = tid + kThreads * i;
       const int row = idx / (KC / 4), col = 4 * (idx % (KC / 4));
-      O::store4(ldsX + buf * xbuf + (size_t)row * xpitch + col * O::ESZ, pre[i]);
+      O::store4(ldsX + buf * xbuf + (size_t)row * xpitch + col * O::ESZ, pre[i][0], pre[i][1], pre[i][2], pre[i][3]);
     }
   };
 
@@ -266,8 +211,8 @@ __device__ inline void epilogue_to_lds(const f32x16 (&acc)[RT][CT], const float 
         for (int i = 0; i < 16; ++i) {
           const int row = r * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
           const float z = acc[r][c][i] + bv;
-          const float hval = BF16 ? tanh_fast(z) : tanh_accurate(z);
-          O::store(ldsH + (size_t)row * hpitch + col * O::ESZ, hval);
+          const float hval = BF16 ? tile::tanh_from_scaled(z * tile::kTwoLog2e) : tanh_accurate(z);
+          O::store1(ldsH + (size_t)row * hpitch + col * O::ESZ, hval);
         }
     }
   }
@@ -880,14 +825,9 @@ hipError_t launch_pack_layer(hipStream_t st, const float *W, const float *b, int
 
 template <bool BF16, int CTH, int CTO, int TAG, int RT = 2>
 static hipError_t launch_tagged(hipStream_t st, const MlpArgs &a, unsigned blocks, size_t lds) {
-  auto kern = mlp3_kernel<BF16, RT, CTH, CTO, TAG>;
-  static bool attr_set = false;  // per instantiation
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  constexpr auto kern = mlp3_kernel<BF16, RT, CTH, CTO, TAG>;
+  const hipError_t e = allow_full_lds<kern>();
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(kThreads), lds, st, a);
   return hipGetLastError();
 }
@@ -901,14 +841,9 @@ static hipError_t launch_one(hipStream_t st, const MlpArgs &a, unsigned blocks, 
 
 template <bool BF16, int NW, int CTH, int NKB1, int NKB2, int TAG>
 static hipError_t launch_tiles_tagged(hipStream_t st, const TileArgs &a, unsigned blocks, size_t lds) {
-  auto kern = mlp_tiles_kernel<BF16, NW, CTH, NKB1, NKB2, TAG>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  constexpr auto kern = mlp_tiles_kernel<BF16, NW, CTH, NKB1, NKB2, TAG>;
+  const hipError_t e = allow_full_lds<kern>();
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, st, a);
   return hipGetLastError();
 }
@@ -977,14 +912,9 @@ static bool try_launch_tiles(hipStream_t st, const PackedNet &net, int64_t rows,
 
 template <int NKB1, int NKB2, int SS>
 static hipError_t launch_value(hipStream_t st, const ValueArgs &a, unsigned blocks, size_t lds) {
-  auto kern = value_kernel<NKB1, NKB2, SS>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  constexpr auto kern = value_kernel<NKB1, NKB2, SS>;
+  const hipError_t e = allow_full_lds<kern>();
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(512), lds, st, a);
   return hipGetLastError();
 }
@@ -1022,14 +952,9 @@ static bool try_launch_value(hipStream_t st, const PackedNet &net, int64_t rows,
 
 template <int CTH, bool WIDE_OUT, int CC>
 static hipError_t launch_wide(hipStream_t st, const WideArgs &a, unsigned blocks, size_t lds) {
-  auto kern = mlp_wide_kernel<8, CTH, WIDE_OUT, CC>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  constexpr auto kern = mlp_wide_kernel<8, CTH, WIDE_OUT, CC>;
+  const hipError_t e = allow_full_lds<kern>();
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(512), lds, st, a);
   return hipGetLastError();
 }

@@ -27,3 +27,14 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Worst observed error / allowed error of the network comparisons of this run (tests/parity.py)."""
+    try:
+        import parity
+    except Exception:
+        return
+    if parity.WORST:
+        terminalreporter.write_line("parity: worst observed error as a fraction of the bound: " +
+                                    ", ".join(f"{k}={v:.3f}" for k, v in sorted(parity.WORST.items())))

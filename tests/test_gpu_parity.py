@@ -105,7 +105,7 @@ def test_value_head_over_many_tiles_matches_checker(name, agents):
     val2 = ro.mlp_forward(pr.PR_NET_CRITIC, X[:4096].contiguous())
     torch.cuda.synchronize()
     scale = float(val2.abs().max())
-    tol = (parity.TOL_BF16 if w.mlp_dtype else parity.TOL_F32) * scale
+    tol = 2.0 * (parity.TOL_NORM_BF16 if w.mlp_dtype else parity.TOL_NORM_F32) * scale   # two approximations
     assert float((val[:4096] - val2).abs().max()) <= tol
 
 
@@ -267,6 +267,39 @@ def test_rollout_free_running_tiny_fp32():
     assert compared > 0.9 * T * w.n_envs
 
 
+def test_rollout_free_running_dow30_first_64_steps():
+    """The Dow-30-shaped fp32 workload at its real width (4096 envs: the per-step actor runs on 32-row tiles),
+    both sides free-running over the first 64 steps.  The checker replays a sample of the envs from the same
+    inputs; integers agree until the first site it flags as a rounding boundary, floats within tolerance."""
+    w = inputs.WORKLOADS["dow30"]
+    T, N, D = 64, w.n_envs, w.n_stocks
+    d, ro, ocfg = _make(w.replace(steps=T), horizon=T)
+    out = ro.alloc_buffers(T, value=True, logp=True, mu=True, shares=True)
+    ro.step_T(T, torch.from_numpy(d["noise"]).to(DEV), out)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(64)
+    idx = np.unique(np.concatenate([[0, 31, 32, 63, 64, N - 33, N - 32, N - 1], rng.integers(0, N, 56)]))
+    rec = {k: parity.to_np(v)[:, idx] for k, v in out.items()}
+    chk, _ = oracle.rollout(ocfg, w.hidden, False, T, d["price"][:, idx], d["ind"][:, idx], d["noise"][:, idx],
+                            actor=d["actor"], critic=d["critic"])
+    alive = np.ones(idx.size, bool)
+    compared = 0
+    for t in range(T):
+        same = (rec["shares"][t] == chk["shares"][t]).all(axis=1)
+        flagged = (chk["flags"][t] != 0).any(axis=1)
+        assert (same | flagged | ~alive).all(), f"unflagged share mismatch at t={t}"
+        a = alive                                  # envs whose histories agree up to step t: same observation in
+        assert np.array_equal(rec["obs"][t][a], chk["obs"][t][a]), t
+        np.testing.assert_allclose(rec["mu"][t][a], chk["mu"][t][a], rtol=2e-4, atol=2e-6)
+        np.testing.assert_allclose(rec["value"][t][a], chk["value"][t][a], rtol=2e-4, atol=2e-6)
+        alive = alive & same
+        compared += int(alive.sum())
+        assert np.array_equal(rec["done"][t][alive], chk["done"][t][alive])
+        tol = parity.reward_tolerance(w, chk["reward"][t][alive])
+        assert (np.abs(rec["reward"][t][alive] - chk["reward"][t][alive]) <= tol).all(), t
+    assert compared > 0.9 * T * idx.size, compared
+
+
 def test_rollout_is_deterministic():
     w = inputs.WORKLOADS["dow30"].replace(n_envs=192, steps=12)
     d, ro, _ = _make(w, horizon=12)
@@ -351,15 +384,19 @@ def _run(w, H, T, schedule, n_market=None, forced_mu=None, calls=1):
     return d, ro, ocfg, outs, state
 
 
-@pytest.mark.parametrize("hidden,N,agents,H,n_market", [(512, 128, 1, 10, None), (256, 192, 1, 24, None),
-                                                         (512, 128, 2, 7, None), (512, 64, 1, 24, 1)])
-def test_fused_schedule_equals_stepwise_given_the_same_means(hidden, N, agents, H, n_market):
-    """The persistent kernel feeds its actor the observation columns in another order than the per-step
+@pytest.mark.parametrize("hidden,N,agents,H,n_market,D,K", [(512, 128, 1, 10, None, 30, 8), (256, 192, 1, 24, None, 30, 8),
+                                                             (512, 128, 2, 7, None, 30, 8), (512, 64, 1, 24, 1, 30, 8),
+                                                             (256, 128, 1, 9, None, 5, 4), (512, 64, 1, 24, None, 2, 2),
+                                                             (256, 64, 1, 24, None, 32, 1)])
+def test_fused_schedule_equals_stepwise_given_the_same_means(hidden, N, agents, H, n_market, D, K):
+    """(Also at observation widths far below the 301 of the named workloads, where the policy-mean planes of the
+    persistent kernel are larger than its input tile.)
+    The persistent kernel feeds its actor the observation columns in another order than the per-step
     kernels, so the two schedules' policy means agree to the order of fp32 sums only.  Everything downstream
     of the means must agree bit for bit: the per-step schedule, forced onto the means the persistent kernel
     produced, has to reproduce its whole record and final state."""
     T = 24
-    w = inputs.WORKLOADS["large"].replace(n_envs=N, n_agents=agents, hidden=hidden, steps=T)
+    w = inputs.WORKLOADS["large"].replace(n_envs=N, n_agents=agents, hidden=hidden, steps=T, n_stocks=D, n_ind=K)
     _, ro_f, _, (b,), sb = _run(w, H, T, FUSED, n_market)
     mu_f = parity.to_np(b["mu"])
     _, ro_s, _, (a,), sa = _run(w, H, T, pr.PR_SCHED_STEPWISE, n_market, forced_mu=mu_f)
@@ -393,7 +430,44 @@ def test_fused_forced_env_stage_matches_checker_with_resets_and_cash_starved():
     wanted = np.trunc(np.clip(rec["act_raw"], -1, 1) * np.float32(100.0))
     assert ((wanted > 0) & (rec["shares"] < wanted) & (rec["shares"] > 0)).any()   # the division path ran
     assert ((wanted > 0) & (rec["shares"] == 0)).any()                               # and the cannot-afford-one path
-    assert (chk["flags"] & oracle.FLAG_GUARD).sum() >= 0
+
+
+@pytest.mark.parametrize("schedule", [pr.PR_SCHED_STEPWISE, pr.PR_SCHED_FUSED])
+def test_purchase_guard_fires_and_matches_checker(schedule):
+    """Envs planted at (price, cash) pairs where fl32(cash / u) rounds up to an integer m whose binary32 outlay
+    exceeds the cash: the rule buys m - 1.  Every env of this test takes that branch, in both schedules; shares,
+    cash and the whole record must match the checker bit for bit (the persistent kernel takes the quotient from a
+    binary64 reciprocal product instead of a division)."""
+    D, K, N, T = 4, 1, 192, 1
+    w = inputs.WORKLOADS["large"].replace(n_envs=N, n_stocks=D, n_ind=K, steps=T, hidden=256)
+    p, m, cash = parity.guard_cases(N, w.cost)
+    d = inputs.make_all(w, horizon=4, steps=T)
+    col = np.arange(N) % D                       # the stock that is bought; the other means are zero (no trade)
+    price = d["price"].copy()
+    price[0, np.arange(N), col] = p
+    cfg = pr.make_config(w, horizon=4, schedule=schedule)
+    ro = pr.Rollout(cfg, torch.from_numpy(price).to(DEV), torch.from_numpy(d["ind"]).to(DEV), _dev(d["actor"]),
+                    _dev(d["critic"]))
+    st = ro.get_state()
+    st["cash"].copy_(torch.from_numpy(cash))
+    ro.set_state(st)
+    mu = np.zeros((T, N, D), np.float32)
+    mu[0, np.arange(N), col] = 1.0
+    noise = np.zeros((T, N, D), np.float32)
+    out = ro.alloc_buffers(T, value=False, logp=True, mu=False, shares=True)
+    ro.step_forced(T, torch.from_numpy(mu).to(DEV), torch.from_numpy(noise).to(DEV), out)
+    torch.cuda.synchronize()
+    rec = _rec(out)
+    ocfg = oracle.cfg_from_workload(w, horizon=4)
+    ost = oracle.State(ocfg, N)
+    ost.cash[:] = cash
+    ost.asset[:] = cash.astype(np.float64)
+    chk, ost = parity.check_env_record(w, ocfg, rec, price, d["ind"], noise, mu, state0=ost)
+    assert ((chk["flags"][0, np.arange(N), col] & oracle.FLAG_GUARD) != 0).all()
+    assert np.array_equal(rec["shares"][0, np.arange(N), col], m - 1)
+    gst = ro.get_state()
+    torch.cuda.synchronize()
+    assert np.array_equal(parity.to_np(gst["cash"]), ost.cash) and float(gst["cash"].min()) >= 0.0
 
 
 def test_fused_rollout_stagewise_against_checker_and_carry_across_calls():

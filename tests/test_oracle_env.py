@@ -255,6 +255,40 @@ def test_env_permutation_equivariance_and_shared_market():
         assert np.array_equal(shared[k], repl[k]), k
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_free_running_population_equals_one_run_per_agent(bf16):
+    """Several agents in one free-running call (Sec. 4.1: a population of pods): env n acts with the networks of
+    agent_of[n].  The record must equal, env for env, what single-agent calls with each agent's own networks give
+    (the single-agent path is pinned by the network and environment tests), whatever the order of the agents among
+    the envs; and the first policy means must be the numpy matmul chain with that agent's weights."""
+    w = inputs.WORKLOADS["tiny"].replace(n_envs=12, n_agents=3, steps=20)
+    d = inputs.make_all(w, horizon=8)
+    cfg = oracle.cfg_from_workload(w, horizon=8)
+    agent_of = np.array([2, 0, 1, 1, 0, 2, 2, 2, 0, 1, 0, 1], np.int32)     # interleaved on purpose
+    T = w.steps
+    pop, _ = oracle.rollout(cfg, w.hidden, bf16, T, d["price"], d["ind"], d["noise"], actor=d["actor"],
+                            critic=d["critic"], agent_of=agent_of)
+    for g in range(w.n_agents):
+        envs = np.nonzero(agent_of == g)[0]
+        one = lambda net: {k: v[g:g + 1] for k, v in net.items()}
+        solo, _ = oracle.rollout(cfg, w.hidden, bf16, T, d["price"][:, envs], d["ind"][:, envs], d["noise"][:, envs],
+                                 actor=one(d["actor"]), critic=one(d["critic"]))
+        for k in ("obs", "mu", "act_raw", "logp", "reward", "done", "value", "shares"):
+            assert np.array_equal(pop[k][:, envs], solo[k]), (g, k)
+    # the agents really differ, so a wrong weight offset could not pass the comparison above
+    assert not np.array_equal(pop["mu"][0, 0], pop["mu"][0, 1])
+    if not bf16:
+        f = lambda a: a.astype(np.float64)
+        for n in range(w.n_envs):
+            a = {k: f(v[agent_of[n]]) for k, v in d["actor"].items()}
+            c = {k: f(v[agent_of[n]]) for k, v in d["critic"].items()}
+            x = f(pop["obs"][0, n])
+            mu = np.tanh(np.tanh(np.tanh(x @ a["W1"] + a["b1"]) @ a["W2"] + a["b2"]) @ a["W3"] + a["b3"])
+            v = np.tanh(np.tanh(x @ c["W1"] + c["b1"]) @ c["W2"] + c["b2"]) @ c["W3"] + c["b3"]
+            np.testing.assert_allclose(pop["mu"][0, n], mu, rtol=1e-12, atol=1e-13)
+            np.testing.assert_allclose(pop["value"][0, n], v[0], rtol=1e-12, atol=1e-13)
+
+
 def test_forced_mean_equals_free_running_when_fed_its_own_means():
     w, cfg, d, out, _ = _tiny_rollout()
     forced, _ = oracle.rollout(cfg, w.hidden, False, w.steps, d["price"], d["ind"], d["noise"],
