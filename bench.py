@@ -189,7 +189,89 @@ def side_measurements(torch, pr, inputs, w, d, out, roll, adv, ret, obs2d, val2d
     return extras
 
 
+def calibrate():
+    """Measured machine figures the roofline fractions can be read against: streaming copy and read bandwidth,
+    the matrix pipe alone, and how matrix instructions share a SIMD with the vector / transcendental
+    instructions of a tanh epilogue (issued by another wavefront of the SIMD, or interleaved in one wavefront).
+    Prints one JSON line; every entry is one launch timed with events (after one untimed launch)."""
+    import torch
+    from paper_2112_05923_amd import podrollout as pr
+
+    dev = torch.device("cuda:0")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    res = {}
+    src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+    dst = torch.empty_like(src)
+    nbytes = src.numel() * 4
+    ms = timed(lambda: pr.calibrate_stream(pr.PR_CAL_COPY, src, dst))
+    res["copy"] = {"GiB": 1, "ms": ms, "GBps_read_plus_write": 2 * nbytes / ms / 1e6}
+    ms = timed(lambda: pr.calibrate_stream(pr.PR_CAL_READ, src, dst))
+    res["read"] = {"GiB": 1, "ms": ms, "GBps": nbytes / ms / 1e6}
+    del src, dst
+
+    M, V, B, P, O = pr.ROLE_MATRIX, pr.ROLE_VECTOR, pr.ROLE_BOTH, pr.ROLE_PLAIN, pr.ROLE_NONE
+    IM, IV = 4096, 1024           # 32768 matrix instructions / 32768 activations per lane and wavefront
+    flop_per_wave = IM * 8 * 2 * 32 * 32 * 16
+    cases = {
+        "matrix_1_per_simd": ([M, M, M, M, O, O, O, O], 0, False),
+        "matrix_2_per_simd": ([M] * 8, 0, False),
+        "matrix_2_per_simd_lds_operand": ([M] * 8, 0, True),
+        "vector_1_per_simd": ([V, V, V, V, O, O, O, O], 0, False),
+        "vector_2_per_simd": ([V] * 8, 0, False),
+        "plain_1_per_simd": ([P, P, P, P, O, O, O, O], 0, False),
+        "plain_2_per_simd": ([P] * 8, 0, False),
+        "matrix_and_vector_wavefronts_share_simd": ([M, M, M, M, V, V, V, V], 0, False),
+        "matrix_lds_and_vector_wavefronts_share_simd": ([M, M, M, M, V, V, V, V], 0, True),
+        "matrix_and_plain_wavefronts_share_simd": ([M, M, M, M, P, P, P, P], 0, False),
+        "one_wavefront_both_2_acts_per_8": ([B, B, B, B, O, O, O, O], 2, False),
+        "one_wavefront_both_4_acts_per_8": ([B, B, B, B, O, O, O, O], 4, False),
+        "one_wavefront_both_8_acts_per_8": ([B, B, B, B, O, O, O, O], 8, False),
+        "two_wavefronts_both_4_acts_per_8": ([B] * 8, 4, False),
+        "two_wavefronts_both_8_acts_per_8": ([B] * 8, 8, False),
+    }
+    probes = {}
+    for name, (roles, acts, lds) in cases.items():
+        ticks = torch.full((256, 8), -1, dtype=torch.int64, device=dev)
+        ms = timed(lambda: pr.calibrate_probe(roles, IM, IV, acts, lds, 256, ticks), reps=2)
+        t = ticks.cpu().numpy().astype("float64") * 10.0      # ns per wavefront
+        entry = {"launch_ms": ms}
+        for role, label in ((M, "matrix"), (V, "vector"), (B, "both"), (P, "plain")):
+            cols = [i for i, r in enumerate(roles) if r == role]
+            if cols:
+                entry[label + "_wavefront_us"] = float(t[:, cols].mean() / 1e3)
+        n_m = sum(1 for r in roles if r in (M, B))
+        if n_m:
+            tm = entry.get("matrix_wavefront_us", entry.get("both_wavefront_us"))
+            entry["matrix_TFLOPs_chip"] = flop_per_wave * n_m * 256 / (tm * 1e-6) / 1e12
+            entry["ns_per_matrix_instruction_per_simd"] = tm * 1e3 / (IM * 8) / max(1, n_m // 4)
+        n_v = sum(1 for r in roles if r in (V, P))
+        if n_v:
+            tv = entry.get("vector_wavefront_us", entry.get("plain_wavefront_us"))
+            entry["ns_per_activation_per_simd"] = tv * 1e3 / (IV * 32) / max(1, n_v // 4)
+        if acts:
+            entry["activations_per_matrix_instruction"] = acts / 8
+        probes[name] = entry
+    res["probes"] = probes
+    res["note"] = ("probe wavefronts: matrix = 32768 independent v_mfma_f32_32x32x16_bf16 each; vector = 32768 "
+                   "activations (fma, exp2, add, rcp, fma) per lane each; both = the matrix loop with that many "
+                   "activations interleaved in program order; 256 workgroups, one per compute unit")
+    print(json.dumps({"calibration": res}))
+
+
 def main():
+    if "--calibrate" in sys.argv[1:]:
+        return calibrate()
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
@@ -284,7 +366,7 @@ def main():
         dom = {"kernel": "rollout_fused_kernel", "bound": "mfma", "achieved": flops_actor / t_roll / 1e9,
                "peak": PEAK[mf][0], "unit": "TFLOP/s", "ms_per_launch": t_roll}
     else:
-        dom = {"kernel": "mlp3_kernel(critic, whole buffer)", "bound": "mfma", "achieved": flops_critic / t_critic / 1e9,
+        dom = {"kernel": "critic over the whole buffer (value_kernel / mlp_tiles_kernel / mlp_wide_kernel by shape)", "bound": "mfma", "achieved": flops_critic / t_critic / 1e9,
                "peak": PEAK[mf][0], "unit": "TFLOP/s", "ms_per_launch": t_critic}
     dom["frac"] = dom["achieved"] / dom["peak"]
     dom["traffic"] = recorded_traffic("fused" if args.schedule == "fused" else "critic", w.name)

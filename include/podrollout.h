@@ -276,6 +276,23 @@ int ppo_learner_step(void *hip_stream, const pr_ppo_config *cfg, const float *ob
  * score_mean, score_var: [P] f64; rank: [P] agent ids. */
 int rollout_leaderboard(pr_handle *h, double *score_mean, double *score_var, int32_t *rank);
 
+/* Machine calibration for the roofline figures reported beside the worker's throughput (the paper names data
+ * collection as the bottleneck, Sec. 1 and Sec. 4.2, and prints no kernel-level figure; the kernels of this library
+ * are therefore measured against what this chip delivers).  Enqueues ONE launch on hip_stream; timing it (events)
+ * is the caller's business.  Stateless, allocates nothing.
+ *   kind PR_CAL_COPY:  streams n bytes from buf_a to buf_b (device, 16-byte aligned, n % 16 == 0).
+ *   kind PR_CAL_READ:  streams n bytes from buf_a; buf_b: device, >= 4 bytes (never written in practice).
+ *   kind PR_CAL_PROBE: n workgroups of up to 8 wavefronts, each wavefront playing the role params[w]
+ *        (0 none, 1 matrix: params[8] trips of 8 independent bf16 32x32x16 matrix instructions, 2 vector:
+ *        params[9] trips of 32 tanh-epilogue activations per lane, 3 both in one wavefront: params[10] in
+ *        {0, 2, 4, 6, 8} activations issued behind every 8 matrix instructions, 4 plain: as 2 with full-rate
+ *        instructions only); params[11] != 0: the matrix role also reads its operand from LDS, 16 bytes per
+ *        instruction.  buf_a: device int64 [n, 8], receives each wavefront's elapsed time in 10 ns ticks (entries of
+ *        wavefronts without a role are left alone); buf_b: device, >= 4 bytes.
+ * params: HOST pointer to 12 int32 (PR_CAL_PROBE only, else may be NULL).  PR_EINVAL on bad arguments. */
+enum { PR_CAL_COPY = 0, PR_CAL_READ = 1, PR_CAL_PROBE = 2 };
+int rollout_calibrate(void *hip_stream, int32_t kind, int64_t n, const int32_t *params, void *buf_a, void *buf_b);
+
 /* Free the host handle.  Device memory stays with the caller. */
 int rollout_destroy(pr_handle *h);
 

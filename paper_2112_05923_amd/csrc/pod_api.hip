@@ -501,6 +501,30 @@ int rollout_leaderboard(pr_handle *h, double *score_mean, double *score_var, int
   return PR_OK;
 }
 
+int rollout_calibrate(void *hip_stream, int32_t kind, int64_t n, const int32_t *params, void *buf_a, void *buf_b) {
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (!buf_a || !buf_b || n < 1) return PR_EINVAL;
+  if (kind == PR_CAL_COPY || kind == PR_CAL_READ) {
+    if (n % 16 != 0 || (reinterpret_cast<uintptr_t>(buf_a) & 15u) || (kind == PR_CAL_COPY && (reinterpret_cast<uintptr_t>(buf_b) & 15u)))
+      return PR_EINVAL;
+    const int blocks = 256 * 16;  // sixteen 256-thread workgroups per compute unit, grid-stride over the buffer
+    POD_HIP(kind == PR_CAL_COPY ? launch_calib_copy(st, buf_a, buf_b, n, blocks) : launch_calib_read(st, buf_a, buf_b, n, blocks));
+    return PR_OK;
+  }
+  if (kind != PR_CAL_PROBE || !params || n > 65535) return PR_EINVAL;
+  bool any = false;
+  for (int w = 0; w < 8; ++w) {
+    if (params[w] < 0 || params[w] > 4) return PR_EINVAL;
+    any = any || params[w] != 0;
+  }
+  if (!any || params[8] < 0 || params[9] < 0 || params[8] > (1 << 24) || params[9] > (1 << 24)) return PR_EINVAL;
+  if (params[10] != 0 && params[10] != 2 && params[10] != 4 && params[10] != 6 && params[10] != 8) return PR_EINVAL;
+  if (reinterpret_cast<uintptr_t>(buf_a) & 7u) return PR_EINVAL;
+  POD_HIP(launch_calib_probe(st, params, params[8], params[9], params[10], params[11] != 0, (int)n,
+                             static_cast<int64_t *>(buf_a), static_cast<float *>(buf_b)));
+  return PR_OK;
+}
+
 int rollout_destroy(pr_handle *h) {
   if (!h) return PR_EINVAL;
   delete h;

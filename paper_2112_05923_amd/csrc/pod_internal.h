@@ -93,6 +93,13 @@ hipError_t launch_adam(hipStream_t st, int64_t n, float *theta, const float *g, 
 hipError_t launch_gae(hipStream_t st, int32_t T, int32_t N, const float *reward, const float *value,
                       const uint8_t *done, float gamma, float lambda, float *adv, float *ret);
 
+// -------------------------------------------------------------- calibration
+hipError_t launch_calib_copy(hipStream_t st, const void *src, void *dst, int64_t bytes, int blocks);
+hipError_t launch_calib_read(hipStream_t st, const void *src, void *sink, int64_t bytes, int blocks);
+hipError_t launch_calib_probe(hipStream_t st, const int32_t role_of_wave[8], int32_t iters_matrix,
+                              int32_t iters_vector, int32_t acts_per_group, int32_t lds_reads, int blocks,
+                              int64_t *ticks, float *sink);
+
 // ---------------------------------------------------------------------- MLP
 // Packed network of one agent set.  Weight blocks are stored in the register
 // layout of the matrix-core instruction: block (kb, ct) holds, for the 64 lanes

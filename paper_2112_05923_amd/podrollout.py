@@ -24,7 +24,8 @@ EXPORTS = ["rollout_workspace_bytes", "rollout_init", "rollout_set_weights", "ro
            "rollout_step_T",
            "rollout_step_forced", "rollout_mlp_forward", "rollout_get_state", "rollout_set_state", "compute_gae",
            "trading_metrics", "population_refill", "ppo_workspace_bytes",
-           "ppo_minibatch_grads", "adam_update", "ppo_learner_step", "rollout_leaderboard", "rollout_destroy", "rollout_strerror", "rollout_last_hip_error"]
+           "ppo_minibatch_grads", "adam_update", "ppo_learner_step", "rollout_leaderboard", "rollout_calibrate",
+           "rollout_destroy", "rollout_strerror", "rollout_last_hip_error"]
 
 
 class PrPpoConfig(C.Structure):
@@ -110,6 +111,7 @@ def lib():
         l.ppo_learner_step.argtypes = [C.c_void_p, C.POINTER(PrPpoConfig)] + [C.c_void_p] * 6 + [NP] * 6 + [
             C.c_void_p, C.c_size_t, C.c_void_p]
         l.rollout_leaderboard.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.rollout_calibrate.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.POINTER(C.c_int32), C.c_void_p, C.c_void_p]
         l.rollout_destroy.argtypes = [C.c_void_p]
         _lib = l
     return _lib
@@ -429,3 +431,29 @@ def ppo_learner_step(cfg: PrPpoConfig, obs, act_raw, logp_old, adv, ret, rows, a
     _check(lib().ppo_learner_step(_stream_ptr(), C.byref(cfg), *_batch_args(cfg, obs, act_raw, logp_old, adv, ret, rows),
                                   *[C.byref(x) for x in st], ptr, nbytes, stats.data_ptr()), "ppo_learner_step")
     return stats
+
+
+# -------------------------------------------------------------- calibration
+
+PR_CAL_COPY, PR_CAL_READ, PR_CAL_PROBE = 0, 1, 2
+ROLE_NONE, ROLE_MATRIX, ROLE_VECTOR, ROLE_BOTH, ROLE_PLAIN = 0, 1, 2, 3, 4
+
+
+def calibrate_stream(kind: int, src: torch.Tensor, dst: torch.Tensor):
+    """One streaming launch over all of src (copy into dst, or read only); the caller times it."""
+    n = src.numel() * src.element_size()
+    _check(lib().rollout_calibrate(_stream_ptr(), kind, n, None, src.data_ptr(), dst.data_ptr()), "rollout_calibrate")
+
+
+def calibrate_probe(roles, iters_matrix: int, iters_vector: int, acts_per_group: int = 0, lds_reads: bool = False,
+                    blocks: int = 256, ticks: Optional[torch.Tensor] = None):
+    """One launch of the matrix / vector co-issue probe: roles = 8 ROLE_* values, one per wavefront of a workgroup.
+    Returns ticks [blocks, 8] (int64, 10 ns units; -1 where a wavefront had no role)."""
+    assert len(roles) == 8
+    if ticks is None:
+        ticks = torch.full((blocks, 8), -1, dtype=torch.int64, device="cuda")
+    sink = torch.zeros(4, dtype=torch.float32, device=ticks.device)
+    params = (C.c_int32 * 12)(*roles, iters_matrix, iters_vector, acts_per_group, int(lds_reads))
+    _check(lib().rollout_calibrate(_stream_ptr(), PR_CAL_PROBE, blocks, params, ticks.data_ptr(), sink.data_ptr()),
+           "rollout_calibrate")
+    return ticks
