@@ -92,6 +92,12 @@ struct __attribute__((aligned(16))) Slot {
   double rcp;  // 1 / unit cost in binary64 (k > 0), else 0
 };
 
+// idx / div for the small indices used here, with magic = ceil(2^32 / div) (div >= 2; the magic of 1 does not fit
+// in 32 bits, so that divisor is handled apart -- uniformly, div is a launch constant).
+__device__ inline int div_small(int idx, int div, uint32_t magic) {
+  return div == 1 ? idx : (int)__umulhi((unsigned)idx, magic);
+}
+
 __device__ inline Row row_of(const EnvDims &d, int32_t tau, int32_t start, int32_t n) {
   const int32_t m = d.M == 1 ? 0 : n;
   Row r;
@@ -190,7 +196,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     for (int i = 0; i < PAIRS_MAX; ++i) {
       const int idx = tid + NT * i;
       if (idx < E * D) {
-        const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
+        const int e = div_small(idx, D, a.d_magic), dd = idx - e * D;
         const float v = p_obs[i];
         s_p[e * Dp + dd] = v;
         const float sv = v * d.s_price;
@@ -204,7 +210,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       for (int i = 0; i < IND_MAX; ++i) {
         const int idx = (tid - 64) + NT_IND * i;
         if (idx < E * G) {
-          const int e = (int)__umulhi((unsigned)idx, a.g_magic), j = 4 * (idx - e * G);
+          const int e = div_small(idx, G, a.g_magic), j = 4 * (idx - e * G);
           f32x4 sv = ind_v[i];
           sv[0] *= d.s_ind;
           sv[1] *= d.s_ind;
@@ -239,7 +245,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     for (int i = 0; i < PAIRS_MAX; ++i) {
       const int idx = tid + NT * i;
       if (idx < E * D) {
-        const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
+        const int e = div_small(idx, D, a.d_magic), dd = idx - e * D;
         int32_t h = s_h[e * Dp + dd];
         if (AFTER_STEP) {
           // sales were booked when they were sized; purchases (q > 0) are booked here
@@ -263,7 +269,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
 #pragma unroll
     for (int i = 0; i < PAIRS_MAX; ++i) {
       const int idx = min(tid + NT * i, E * D - 1);
-      const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
+      const int e = div_small(idx, D, a.d_magic), dd = idx - e * D;
       const Row r = s_row[e];
       r_pv[i] = __builtin_nontemporal_load(&a.price[(size_t)r.row_val * D + dd]);
       r_po[i] = __builtin_nontemporal_load(&a.price[(size_t)r.row_obs * D + dd]);
@@ -273,7 +279,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
 #pragma unroll
       for (int i = 0; i < IND_MAX; ++i) {
         const int idx = min((tid - 64) + NT_IND * i, E * G - 1);
-        const int e = (int)__umulhi((unsigned)idx, a.g_magic), j = 4 * (idx - e * G);
+        const int e = div_small(idx, G, a.g_magic), j = 4 * (idx - e * G);
         r_ind[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.ind + (size_t)s_row[e].row_obs * DK + j));
       }
     }
@@ -338,7 +344,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     for (int i = 0; i < PAIRS_MAX; ++i) {
       const int idx = tid_p + NT * i;
       if (idx < E * D) {
-        const int e = (int)__umulhi((unsigned)idx, a.d_magic), dd = idx - e * D;
+        const int e = div_small(idx, D, a.d_magic), dd = idx - e * D;
         const int o = e * Dp + dd;
         float mu;
         if (ACTOR) {

@@ -871,7 +871,8 @@ int compute_units() {
 static bool try_launch_tiles(hipStream_t st, const PackedNet &net, int64_t rows, int64_t row_base, const float *X,
                              int64_t ldx, float *Y, int32_t N, int32_t envs_per_agent, hipError_t *err) {
   const int S = net.in_dim[0], Hd = net.out_dim[0];
-  if (ldx != S || S < 4 || (reinterpret_cast<uintptr_t>(X) & 3u) || net.nct[2] != 1 || Hd > 512) return false;
+  // (S >= 5: at least two 16-byte groups per row, the reciprocal of one group does not fit the 32-bit magic)
+  if (ldx != S || S < 5 || (reinterpret_cast<uintptr_t>(X) & 3u) || net.nct[2] != 1 || Hd > 512) return false;
   const int G = (S + 3) / 4;
   // eight wavefronts when every one of them gets at least one feature tile
   const int nct = net.nct[0];
