@@ -44,7 +44,8 @@ typedef enum pr_status {
   PR_EINVAL = -1,       /* bad shape, null pointer, scale not a power of two, ... */
   PR_ENOMEM = -2,       /* workspace too small / host handle allocation failed    */
   PR_EHIP = -3,         /* a HIP call failed; see rollout_last_hip_error()        */
-  PR_EUNSUPPORTED = -4  /* valid request outside the shapes the kernels cover     */
+  PR_EUNSUPPORTED = -4, /* valid request outside the shapes the kernels cover     */
+  PR_ETOOBIG = -5       /* request needs more than the fixed scratch of a no-allocation entry point */
 } pr_status;
 
 enum { PR_MLP_F32 = 0, PR_MLP_BF16 = 1 };        /* pr_config.mlp_dtype */
@@ -255,6 +256,23 @@ int ppo_minibatch_grads(void *hip_stream, const pr_ppo_config *cfg, const float 
                         const float *logp_old, const float *adv, const float *ret, const int32_t *rows,
                         const pr_net_params *actor, const pr_net_params *critic, const pr_net_params *grad_actor,
                         const pr_net_params *grad_critic, void *workspace, size_t workspace_bytes, float *stats);
+
+/* ppo_minibatch_grads for callers that cannot allocate device memory and own no workspace: code running under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * results bit for bit, but the scratch lives in a fixed device array inside the library:
+ * PR_STATIC_SCRATCH_BYTES (24 MiB) per GPU the library is used on, held until the process ends -- enough for the
+ * paper's minibatch of 1024 with 512 hidden units and 30 stocks x 8 indicators (22.5 MB); ppo_workspace_bytes minus
+ * the gradient tensors is what a shape needs.  A shape that needs more is refused with PR_ETOOBIG before any device
+ * work.  The call allocates nothing (no hipMalloc / hipFree, no allocating library routine) and only enqueues on
+ * hip_stream.  All calls on one GPU share that GPU's array, which keeps the previous call's contents (nothing in
+ * it has to start at zero): calls whose device work overlaps on one GPU -- two streams, two host threads -- race;
+ * serialise them.  The first call on a device looks up the array's address there (not a stream operation, so make
+ * that first call outside graph capture). */
+#define PR_STATIC_SCRATCH_BYTES ((size_t)24 << 20)
+int ppo_minibatch_grads_noalloc(void *hip_stream, const pr_ppo_config *cfg, const float *obs, const float *act_raw,
+                                const float *logp_old, const float *adv, const float *ret, const int32_t *rows,
+                                const pr_net_params *actor, const pr_net_params *critic,
+                                const pr_net_params *grad_actor, const pr_net_params *grad_critic, float *stats);
 
 /* Adam on one tensor of n elements:  m = b1 m + (1 - b1) g;  v = b2 v + (1 - b2) g^2;
  *   theta -= lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps).  All device, fp32, in place. */

@@ -439,6 +439,24 @@ int ppo_minibatch_grads(void *hip_stream, const pr_ppo_config *cfg, const float 
   return PR_OK;
 }
 
+int ppo_minibatch_grads_noalloc(void *hip_stream, const pr_ppo_config *cfg, const float *obs, const float *act_raw,
+                                const float *logp_old, const float *adv, const float *ret, const int32_t *rows,
+                                const pr_net_params *actor, const pr_net_params *critic,
+                                const pr_net_params *grad_actor, const pr_net_params *grad_critic, float *stats) {
+  const int rc = ppo_config_ok(cfg);
+  if (rc != PR_OK) return rc;
+  if (!obs || !act_raw || !logp_old || !adv || !ret) return PR_EINVAL;
+  if (!net_ok(actor) || !net_ok(critic) || !net_ok(grad_actor) || !net_ok(grad_critic)) return PR_EINVAL;
+  static_assert(PR_STATIC_SCRATCH_BYTES == (size_t)24 << 20, "header and library disagree on the scratch size");
+  if (ppo_static_scratch_bytes() != PR_STATIC_SCRATCH_BYTES ||
+      ppo_scratch_bytes(cfg->batch, cfg->hidden, cfg->n_stocks, 1 + cfg->n_stocks * (2 + cfg->n_ind)) >
+          PR_STATIC_SCRATCH_BYTES)
+    return PR_ETOOBIG;
+  POD_HIP(launch_ppo_grads_static(static_cast<hipStream_t>(hip_stream), *cfg, obs, act_raw, logp_old, adv, ret, rows,
+                                  *actor, *critic, *grad_actor, *grad_critic, stats));
+  return PR_OK;
+}
+
 int adam_update(void *hip_stream, int64_t n, float *theta, const float *grad, float *m, float *v, float lr, float beta1,
                 float beta2, float eps, int32_t t) {
   if (n < 1 || !theta || !grad || !m || !v || t < 1) return PR_EINVAL;
@@ -538,6 +556,7 @@ const char *rollout_strerror(int code) {
     case PR_ENOMEM: return "workspace too small or out of host memory";
     case PR_EHIP: return "HIP call failed";
     case PR_EUNSUPPORTED: return "shape or schedule not covered by the kernels";
+    case PR_ETOOBIG: return "request needs more than the fixed scratch of this no-allocation entry point";
     default: return "unknown status";
   }
 }

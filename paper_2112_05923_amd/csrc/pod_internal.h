@@ -86,6 +86,13 @@ hipError_t launch_ppo_grads(hipStream_t st, const pr_ppo_config &c, const float 
                             const float *logp_old, const float *adv, const float *ret, const int32_t *rows,
                             const pr_net_params &actor, const pr_net_params &critic, const pr_net_params &ga,
                             const pr_net_params &gc, void *scratch, float *stats);
+// The same with the scratch in a fixed device array of ppo_static_scratch_bytes() (no workspace, no allocation);
+// hipErrorInvalidValue when the shape needs more.
+size_t ppo_static_scratch_bytes();
+hipError_t launch_ppo_grads_static(hipStream_t st, const pr_ppo_config &c, const float *obs, const float *act,
+                                   const float *logp_old, const float *adv, const float *ret, const int32_t *rows,
+                                   const pr_net_params &actor, const pr_net_params &critic, const pr_net_params &ga,
+                                   const pr_net_params &gc, float *stats);
 hipError_t launch_adam12(hipStream_t st, const int64_t *n, float *const *theta, float *const *g, float *const *m,
                          float *const *v, float lr, float b1, float b2, float eps, int32_t t);
 hipError_t launch_adam(hipStream_t st, int64_t n, float *theta, const float *g, float *m, float *v, float lr, float b1,

@@ -540,6 +540,41 @@ hipError_t launch_ppo_grads(hipStream_t st, const pr_ppo_config &c, const float 
   return hipGetLastError();
 }
 
+// ---- the same minibatch for callers that cannot allocate or own a workspace: scratch in a fixed device array
+// (one copy per GPU the library runs on, held until the process ends).  In host code the array's name is only a
+// stand-in for the symbol: its device address is looked up once per device and that pointer is what kernels get.
+constexpr size_t kStaticScratchBytes = (size_t)24 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+}  // namespace
+
+size_t ppo_static_scratch_bytes() { return kStaticScratchBytes; }
+
+hipError_t launch_ppo_grads_static(hipStream_t st, const pr_ppo_config &c, const float *obs, const float *act,
+                                   const float *logp_old, const float *adv, const float *ret, const int32_t *rows,
+                                   const pr_net_params &actor, const pr_net_params &critic, const pr_net_params &ga,
+                                   const pr_net_params &gc, float *stats) {
+  const int S = 1 + 2 * c.n_stocks + c.n_stocks * c.n_ind;
+  if (ppo_scratch_bytes(c.batch, c.hidden, c.n_stocks, S) > kStaticScratchBytes) return hipErrorInvalidValue;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    // first call on this device (with it current): every GPU holds its own copy of the array at its own address
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
+  // nothing in the scratch has to start at zero: every region is written by this call before it is read
+  return launch_ppo_grads(st, c, obs, act, logp_old, adv, ret, rows, actor, critic, ga, gc, ptr, stats);
+}
+
 hipError_t launch_adam12(hipStream_t st, const int64_t *n, float *const *theta, float *const *g, float *const *m,
                          float *const *v, float lr, float b1, float b2, float eps, int32_t t) {
   AdamBatch bt;

@@ -15,7 +15,8 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpodrollout.so")
 
-PR_OK, PR_EINVAL, PR_ENOMEM, PR_EHIP, PR_EUNSUPPORTED = 0, -1, -2, -3, -4
+PR_OK, PR_EINVAL, PR_ENOMEM, PR_EHIP, PR_EUNSUPPORTED, PR_ETOOBIG = 0, -1, -2, -3, -4, -5
+PR_STATIC_SCRATCH_BYTES = 24 << 20
 PR_MLP_F32, PR_MLP_BF16 = 0, 1
 PR_SCHED_STEPWISE, PR_SCHED_FUSED = 0, 1
 PR_NET_ACTOR, PR_NET_CRITIC = 0, 1
@@ -24,7 +25,7 @@ EXPORTS = ["rollout_workspace_bytes", "rollout_init", "rollout_set_weights", "ro
            "rollout_step_T",
            "rollout_step_forced", "rollout_mlp_forward", "rollout_get_state", "rollout_set_state", "compute_gae",
            "trading_metrics", "population_refill", "ppo_workspace_bytes",
-           "ppo_minibatch_grads", "adam_update", "ppo_learner_step", "rollout_leaderboard", "rollout_calibrate",
+           "ppo_minibatch_grads", "ppo_minibatch_grads_noalloc", "adam_update", "ppo_learner_step", "rollout_leaderboard", "rollout_calibrate",
            "rollout_destroy", "rollout_strerror", "rollout_last_hip_error"]
 
 
@@ -106,6 +107,8 @@ def lib():
         l.ppo_workspace_bytes.argtypes = [C.POINTER(PrPpoConfig), C.POINTER(C.c_size_t)]
         l.ppo_minibatch_grads.argtypes = [C.c_void_p, C.POINTER(PrPpoConfig)] + [C.c_void_p] * 6 + [NP] * 4 + [
             C.c_void_p, C.c_size_t, C.c_void_p]
+        l.ppo_minibatch_grads_noalloc.argtypes = [C.c_void_p, C.POINTER(PrPpoConfig)] + [C.c_void_p] * 6 + [NP] * 4 + [
+            C.c_void_p]
         l.adam_update.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float,
                                   C.c_float, C.c_float, C.c_float, C.c_int32]
         l.ppo_learner_step.argtypes = [C.c_void_p, C.POINTER(PrPpoConfig)] + [C.c_void_p] * 6 + [NP] * 6 + [
@@ -408,6 +411,18 @@ def ppo_minibatch_grads(cfg: PrPpoConfig, obs, act_raw, logp_old, adv, ret, rows
                                      C.byref(sa), C.byref(sc), C.byref(sga), C.byref(sgc), ptr, nbytes,
                                      stats.data_ptr()), "ppo_minibatch_grads")
     return ga, gc, stats
+
+
+def ppo_minibatch_grads_noalloc(cfg: PrPpoConfig, obs, act_raw, logp_old, adv, ret, rows, actor, critic, grad_actor,
+                                grad_critic, stats):
+    """The same gradients through the entry point that owns its scratch: every output tensor is the caller's."""
+    sa, sc = _net_struct(actor, cfg, cfg.n_stocks, "actor"), _net_struct(critic, cfg, 1, "critic")
+    sga, sgc = _net_struct(grad_actor, cfg, cfg.n_stocks, "grad_actor"), _net_struct(grad_critic, cfg, 1, "grad_critic")
+    _check(lib().ppo_minibatch_grads_noalloc(_stream_ptr(), C.byref(cfg),
+                                             *_batch_args(cfg, obs, act_raw, logp_old, adv, ret, rows), C.byref(sa),
+                                             C.byref(sc), C.byref(sga), C.byref(sgc),
+                                             _dev(stats, torch.float32, (4,), "stats")), "ppo_minibatch_grads_noalloc")
+    return grad_actor, grad_critic, stats
 
 
 def adam_update(theta, grad, m, v, lr, beta1, beta2, eps, t):
