@@ -526,16 +526,40 @@ __global__ __launch_bounds__(NW * 64) void mlp_wide_kernel(WideArgs a) {
 // A 128-row tile halves the weight traffic per row of the 64-row kernel above:
 // every weight block a wavefront streams from L2 feeds four 32-row batch tiles,
 // which makes the two hidden layers matrix-core bound instead of L2 bound.
-//  - LDS holds one 128-row hidden tile; the input tile aliases its head (layer 1
-//    has consumed it before its epilogue writes the hidden tile).
+//
+// Matrix instructions and the vector / transcendental instructions of the tanh
+// epilogues co-issue on a SIMD when they come from DIFFERENT wavefronts, so the
+// eight wavefronts work as two groups that are half a layer out of step: group
+// A (wavefronts 0-3, hidden features 0-255) and group B (wavefronts 4-7,
+// features 256-511), one wavefront of each per SIMD.  Per tile, with a
+// workgroup barrier between the phases:
+//
+//   phase   group A                                group B
+//   1       layer 1 (matrix)                       epilogue 2 + output dot of the PREVIOUS tile
+//   2       epilogue 1 -> hidden half A            layer 1 (matrix)
+//   3       layer 2 over k in half A (matrix)      epilogue 1 -> hidden half B
+//   4       layer 2 over k in half B (matrix)      layer 2 over k in half B (matrix)
+//   5       epilogue 2 + output dot                layer 2 over k in half A (matrix)
+//
+// so in four of the five phases one wavefront of every SIMD feeds the matrix
+// pipe while the other runs an epilogue.  LDS: hidden half A; one region that
+// holds the input tile (phases 1-2), then hidden half B (phases 3-4), then the
+// next input tile (written in phase 5, behind loads issued in phase 4).
 //  - The output layer is folded into layer 2's epilogue: each lane multiplies
 //    its bf16-rounded activations by the output weights of its features and the
-//    16 partial sums per row (8 wavefronts x 2 lane halves) meet in LDS.  The
-//    hidden tile is therefore dead after layer 2's matrix work, and the next
-//    tile's rows (fetched into registers behind that matrix work) are dropped
-//    into LDS while the epilogue arithmetic runs.
+//    16 partial sums per row (8 wavefronts x 2 lane halves) meet in LDS; they
+//    are added up one phase after group B has delivered its share.
+//  - Every wavefront's weight ring runs on across the phases: the last blocks of
+//    a range are replaced by the first blocks of the wavefront's next range, so
+//    no matrix phase starts with a round trip to L2.
+#ifndef POD_VK_PRIO
+#define POD_VK_PRIO 3
+#endif
+constexpr int kMatrixPrio = POD_VK_PRIO;  // wavefront priority of the matrix steps (epilogue steps run at 0)
 constexpr int VBM = 128;
 constexpr int VPRE_MAX = 19;  // 16-byte loads per thread and tile: k-blocks of layer 1
+constexpr int VHALF = 256;    // hidden features per group
+constexpr int VHPITCH = VHALF * 2 + 16;  // bytes per row of a hidden half
 
 struct ValueArgs {
   const float *X;
@@ -546,24 +570,26 @@ struct ValueArgs {
   int32_t S;
   int32_t groups;    // 16-byte groups per LDS row: padded k columns / 4
   uint32_t g_magic;  // ceil(2^32 / groups)
-  int32_t xpitch, hpitch;
+  int32_t xpitch;
+  int32_t off_xb, off_bias, off_w3, off_part;  // LDS byte offsets: input tile / hidden half B, b1 | b2, output weights, partial sums
 };
 
-template <int NKB1, int NKB2, int SS>
+template <int NKB1, int SS>
 __global__ __launch_bounds__(512) void value_kernel(ValueArgs a) {
   using namespace tile;
   using O = tile::Op<true>;
   typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-  constexpr int NW = 8, NBT = 4, NT = NW * 64, CTH = 16 / NW, PD = 4;
+  constexpr int NW = 8, NBT = 4, NT = NW * 64, CTH = 16 / NW, PD = 4, NKBH = VHALF / 16;
   extern __shared__ __align__(16) unsigned char lds[];
-  unsigned char *ldsH = lds;
-  unsigned char *ldsX = lds;  // alias: see above
-  float *ldsBias = reinterpret_cast<float *>(lds + (size_t)VBM * a.hpitch);  // b1 | b2
-  const int nct = a.net.nct[0];
-  __bf16 *ldsW3 = reinterpret_cast<__bf16 *>(ldsBias + 2 * nct * 32);  // output weights, one per hidden feature
-  float *ldsPart = reinterpret_cast<float *>(ldsW3 + nct * 32);        // [2 NW][VBM] partial sums of the output layer
+  unsigned char *ldsHA = lds;                 // hidden features 0..255, [VBM][VHPITCH]
+  unsigned char *ldsXB = lds + a.off_xb;      // input tile [VBM][xpitch], later hidden features 256..511 [VBM][VHPITCH]
+  float *ldsBias = reinterpret_cast<float *>(lds + a.off_bias);  // b1 | b2
+  __bf16 *ldsW3 = reinterpret_cast<__bf16 *>(lds + a.off_w3);    // output weights, one per hidden feature
+  float *ldsPart = reinterpret_cast<float *>(lds + a.off_part);  // [2 NW][VBM] partial sums of the output layer
+  const int nct = a.net.nct[0];               // 16 feature tiles in both hidden layers
   const int tid = threadIdx.x;
   const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const bool grpB = w >= NW / 2;
   const int ct0 = w * CTH;
   const int S = SS > 0 ? SS : a.S;           // (compile-time for the named workloads: the index
   const int G = NKB1 > 0 ? 4 * NKB1 : a.groups;  //  arithmetic of fetch and stash folds into constants)
@@ -571,164 +597,371 @@ __global__ __launch_bounds__(512) void value_kernel(ValueArgs a) {
   const int last_c4 = 4 * ((S + 3) / 4 - 1);  // first column of the last group that holds data
   const int64_t ntiles = a.rows / VBM;
 
-  constexpr int NX = NKB1 > 0 ? VBM * 4 * NKB1 / NT : VPRE_MAX;  // 16-byte groups per thread and tile
+  // The next input tiles travel through registers, 16-byte groups of four columns (76 per row at most), 19 per
+  // thread.  Two rules shape this.  (1) A wavefront's loads return in order, so a row request in flight during one
+  // of its matrix steps would hold up the weight blocks (L2 hits) behind it: rows are requested and received
+  // only inside the epilogue steps (b) and (e), and carried across matrix steps packed in the operand type.
+  // (2) All compute units walk their tiles in step, so a whole tile per compute unit requested at once would be a
+  // 39 MB burst: the requests are spread over four of the five phases.
+  //   chunk 0 (NX0 groups): requested at the start of step (b), packed at its end, carried to phase 5 (group A:
+  //            start of its step (e); group B: start of its step (d)) and written to the input region there.
+  //   chunk 1 (NX1 groups): requested at the start of step (e).  Group A is in phase 5 then: written at the end of
+  //            the step.  Group B is already in phase 1 of the next tile, whose input must not be touched: it
+  //            requests the rows of the tile AFTER the next one, packs them and carries them to its next step (d).
+  constexpr int NX0 = 10, NX1 = 9;
+  static_assert(NT * (NX0 + NX1) >= VBM * 4 * VPRE_MAX, "every group of the input tile has an owner");
   const int sh = 4 * ((S + 3) / 4) - S;            // floats the row-end group is shifted by (0..3), uniform
-  f32x4 pre[NX];
-  // Every thread issues its 16-byte loads unconditionally.  The group that straddles the end of a row is read
-  // as the four floats that END at the row end; groups that lie wholly in the k padding re-read it.
-  // (issued in two parts, [0, NX_A) behind layer 2's matrix work and the rest once half of that layer's
-  // accumulators have been consumed, so that registers for the rows in flight are there without spilling)
-  constexpr int NX_A = NX / 2;
+  f32x4 pre[NX0 > NX1 ? NX0 : NX1];                // requests in flight
+  u32x2 held0[NX0], held1[NX1];                    // chunks in the operand type
+  // Every thread issues its loads unconditionally.  The group that straddles the end of a row is read as the four
+  // floats that END at the row end; groups that lie wholly in the k padding, or past the tile, re-read a valid one.
+  // Which 16-byte group a thread moves with its i-th request of a chunk.
+  //  - Rows wider than 64 groups with the width known at compile time (the named workloads: 76 groups): every
+  //    wavefront owns 16 rows of the tile; a request of the "main" kind covers groups 0..63 of one row (lane =
+  //    group: 1 KiB contiguous, and the LDS address is the lane's base plus a constant), the remaining TG groups of
+  //    the 16 rows are covered by 64-lane "tail" requests in row-major order.  Chunk 0 = main rows 0..9, chunk 1 =
+  //    main rows 10..15 and the tail.  Only tail groups can hold a row end.
+  //  - Otherwise: groups dealt out to the threads in order (index arithmetic per group).
+  constexpr bool ROWS = NKB1 > 16 && SS > 0;
+  constexpr int GC = ROWS ? 4 * NKB1 : 65, TG = GC - 64, NTAIL = (16 * TG + 63) / 64;
+  static_assert(!ROWS || (NX0 == 10 && 6 + NTAIL <= NX1), "chunk sizes of the row-owning scheme");
+  auto group_index = [&](int tid_g, int i, auto part) { return (decltype(part)::value ? NX0 * NT : 0) + tid_g + NT * i; };
+  // float offset of the group inside the tile, as requested (the row-end group is read shifted)
+  auto src_offset_general = [&](int idx) {
+    const int idc = min(idx, VBM * G - 1);
+    const int row = row_of_group(idc);
+    const int c4 = min(4 * (idc - row * G), last_c4);
+    return row * S + (c4 == last_c4 ? c4 - sh : c4);
+  };
+  auto tail_group = [&](int lane_t, int j, int *row, int *g) {  // ROWS: tail request j of a lane
+    const int q = min(lane_t + 64 * j, 16 * TG - 1);
+    *row = q / TG;
+    *g = 64 + q - *row * TG;
+  };
   auto fetch = [&](int64_t t, auto part) {
-    constexpr int I0 = decltype(part)::value ? NX_A : 0, I1 = decltype(part)::value ? NX : NX_A;
-    const float *src = a.X + t * VBM * S;
+    constexpr bool P1 = decltype(part)::value;
+    constexpr int CNT = P1 ? NX1 : NX0;
     int tid_f = threadIdx.x;
     asm volatile("" : "+v"(tid_f));
+    if constexpr (ROWS) {
+      const int lane_f = tid_f & 63;
+      const float *src = a.X + (t * VBM + 16 * w) * S;
+      constexpr int R0 = P1 ? NX0 : 0, NR = P1 ? 16 - NX0 : NX0;
 #pragma unroll
-    for (int i = I0; i < I1; ++i) {
-      const int idx = min(tid_f + NT * i, VBM * G - 1);
-      const int row = row_of_group(idx);
-      const int c4 = min(4 * (idx - row * G), last_c4);
-      const int off = c4 == last_c4 ? c4 - sh : c4;
-      pre[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(src + (size_t)row * S + off));
+      for (int r = 0; r < NR; ++r)
+        pre[r] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(src + (R0 + r) * S + 4 * lane_f));
+      if constexpr (P1) {
+#pragma unroll
+        for (int j = 0; j < NTAIL; ++j) {
+          int row, g;
+          tail_group(lane_f, j, &row, &g);
+          const int c4 = 4 * g;
+          pre[NR + j] = __builtin_nontemporal_load(
+              reinterpret_cast<const f32x4 *>(src + row * S + (c4 == last_c4 ? c4 - sh : c4)));
+        }
+      }
+    } else {
+      const float *src = a.X + t * VBM * S;
+#pragma unroll
+      for (int i = 0; i < CNT; ++i)
+        pre[i] = __builtin_nontemporal_load(
+            reinterpret_cast<const f32x4 *>(src + src_offset_general(group_index(tid_f, i, part))));
     }
   };
-  auto stash = [&]() {
+  // a received group as four operand-type values; `end`: it is the row-end group (shifted down, zeros behind),
+  // `pad`: it lies wholly in the k padding
+  auto pack4 = [&](const f32x4 &v, bool end, bool pad) {
+    f32x4 e;  // (selects on the uniform sh, no branches)
+    e[0] = sh == 0 ? v[0] : sh == 1 ? v[1] : sh == 2 ? v[2] : v[3];
+    e[1] = sh == 0 ? v[1] : sh == 1 ? v[2] : sh == 2 ? v[3] : 0.0f;
+    e[2] = sh == 0 ? v[2] : sh == 1 ? v[3] : 0.0f;
+    e[3] = sh == 0 ? v[3] : 0.0f;
+    f32x4 o;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) o[q] = pad ? 0.0f : end ? e[q] : v[q];
+    const bf16x4 b = {(__bf16)o[0], (__bf16)o[1], (__bf16)o[2], (__bf16)o[3]};
+    return __builtin_bit_cast(u32x2, b);
+  };
+  auto pack_plain = [&](const f32x4 &v) {
+    const bf16x4 b = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};
+    return __builtin_bit_cast(u32x2, b);
+  };
+  auto hold = [&](auto part) {  // the chunk in flight -> held0 / held1
+    constexpr bool P1 = decltype(part)::value;
+    int tid_s = threadIdx.x;
+    asm volatile("" : "+v"(tid_s));
+    if constexpr (ROWS) {
+      if constexpr (P1) {
+#pragma unroll
+        for (int r = 0; r < 16 - NX0; ++r) held1[r] = pack_plain(pre[r]);
+#pragma unroll
+        for (int j = 0; j < NTAIL; ++j) {
+          int row, g;
+          tail_group(tid_s & 63, j, &row, &g);
+          held1[16 - NX0 + j] = pack4(pre[16 - NX0 + j], 4 * g == last_c4, 4 * g > last_c4);
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < NX0; ++r) held0[r] = pack_plain(pre[r]);
+      }
+    } else {
+      constexpr int CNT = P1 ? NX1 : NX0;
+#pragma unroll
+      for (int i = 0; i < CNT; ++i) {
+        const int idc = min(group_index(tid_s, i, part), VBM * G - 1);
+        const int c4 = 4 * (idc - row_of_group(idc) * G);
+        const u32x2 v = pack4(pre[i], c4 == last_c4, c4 > last_c4);
+        if constexpr (P1) held1[i] = v;
+        else held0[i] = v;
+      }
+    }
+  };
+  auto stash = [&](auto part) {  // held0 / held1 -> the input region
+    constexpr bool P1 = decltype(part)::value;
     int tid_s = threadIdx.x;
     asm volatile("" : "+v"(tid_s));  // keeps the LDS addresses out of registers across the matrix-core loops
+    if constexpr (ROWS) {
+      const int lane_s = tid_s & 63;
+      unsigned char *dst = ldsXB + (size_t)(16 * w) * a.xpitch;
+      constexpr int R0 = P1 ? NX0 : 0, NR = P1 ? 16 - NX0 : NX0;
 #pragma unroll
-    for (int i = 0; i < NX; ++i) {
-      const int idx = tid_s + NT * i;
-      const int idc = min(idx, VBM * G - 1);
-      const int row = row_of_group(idc);
-      const int c4 = 4 * (idc - row * G);
-      const f32x4 v = pre[i];
-      // the row-end group, shifted down by sh with zeros behind (selects on the uniform sh, no branches)
-      f32x4 e;
-      e[0] = sh == 0 ? v[0] : sh == 1 ? v[1] : sh == 2 ? v[2] : v[3];
-      e[1] = sh == 0 ? v[1] : sh == 1 ? v[2] : sh == 2 ? v[3] : 0.0f;
-      e[2] = sh == 0 ? v[2] : sh == 1 ? v[3] : 0.0f;
-      e[3] = sh == 0 ? v[3] : 0.0f;
-      const bool end = c4 == last_c4, pad = c4 > last_c4;
-      f32x4 o;
+      for (int r = 0; r < NR; ++r) {
+        u32x2 v;
+        if constexpr (P1) v = held1[r];
+        else v = held0[r];
+        *reinterpret_cast<u32x2 *>(dst + (size_t)(R0 + r) * a.xpitch + lane_s * 8) = v;
+      }
+      if constexpr (P1) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) o[q] = pad ? 0.0f : end ? e[q] : v[q];
-      if (NKB1 > 0 || idx < VBM * G) O::store4(ldsX + (size_t)row * a.xpitch + c4 * O::ESZ, o[0], o[1], o[2], o[3]);
+        for (int j = 0; j < NTAIL; ++j) {
+          int row, g;
+          tail_group(lane_s, j, &row, &g);
+          if (lane_s + 64 * j < 16 * TG) *reinterpret_cast<u32x2 *>(dst + (size_t)row * a.xpitch + g * 8) = held1[NR + j];
+        }
+      }
+    } else {
+      constexpr int CNT = P1 ? NX1 : NX0;
+#pragma unroll
+      for (int i = 0; i < CNT; ++i) {
+        const int idx = group_index(tid_s, i, part);
+        const int idc = min(idx, VBM * G - 1);
+        const int row = row_of_group(idc);
+        u32x2 v;
+        if constexpr (P1) v = held1[i];
+        else v = held0[i];
+        if (idx < VBM * G) *reinterpret_cast<u32x2 *>(ldsXB + (size_t)row * a.xpitch + (idc - row * G) * 8) = v;
+      }
     }
   };
+  auto agent_of_tile = [&](int64_t t) { return (int)(((t * VBM) % a.N) / a.envs_per_agent); };
+  // both hidden biases of one agent / the output weights of one agent into LDS (any subset of threads, strided by n)
+  auto stage_biases = [&](const Net &net, int i0, int n) {
+    for (int i = i0; i < nct * 32; i += n) {
+      ldsBias[i] = net.b[0][i];
+      ldsBias[nct * 32 + i] = net.b[1][i];
+    }
+  };
+  auto stage_w3 = [&](const Net &net, int i0, int n) {
+    for (int i = i0; i < nct * 32; i += n) {
+      // output weights of feature 0 out of the packed blocks: k = 16 kb + 8 g + e sits in lane 32 g
+      const int kb = i >> 4, gg = (i >> 3) & 1, e = i & 7;
+      ldsW3[i] = reinterpret_cast<const __bf16 *>(net.W[2])[((size_t)kb * 64 + 32 * gg) * 8 + e];
+    }
+  };
+  // Layer 2's epilogue with the output layer folded in: partial sums of this wavefront's 64 features, per row.
+  // Layer 2's epilogue with the output layer folded in (the accumulators started from the bias): partial sums of
+  // this wavefront's 64 features, per row.  Overwrites acc.
+  auto epilogue_out_dot = [&](f32x16 (&acc)[CTH][NBT]) {
+    int lane_e = threadIdx.x & 63;
+    asm volatile("" : "+v"(lane_e));
+    const int ge = lane_e >> 5;
+    float part[NBT][4];  // (one running sum per batch tile and feature group: four-deep dependent chains only)
+#pragma unroll
+    for (int q = 0; q < NBT; ++q)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) part[q][j] = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CTH; ++c) {
+      tanh_in_place<NBT>(acc[c]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int f0 = (ct0 + c) * 32 + 8 * j + 4 * ge;
+        const u32x2 wv = *reinterpret_cast<const u32x2 *>(ldsW3 + f0);  // four bf16 weights
+        const uint32_t wlo = wv[0], whi = wv[1];  // (scalars first: a bit cast straight from a vector element reads element 0)
+        const bf16x2 w01 = __builtin_bit_cast(bf16x2, wlo), w23 = __builtin_bit_cast(bf16x2, whi);
+#pragma unroll
+        for (int q = 0; q < NBT; ++q) {
+          // activations rounded to bf16 as the hidden tile would hold them; products summed in fp32
+          const bf16x2 h01 = {(__bf16)acc[c][q][4 * j], (__bf16)acc[c][q][4 * j + 1]};
+          const bf16x2 h23 = {(__bf16)acc[c][q][4 * j + 2], (__bf16)acc[c][q][4 * j + 3]};
+          part[q][j] = __builtin_amdgcn_fdot2_f32_bf16(h01, w01, part[q][j], false);
+          part[q][j] = __builtin_amdgcn_fdot2_f32_bf16(h23, w23, part[q][j], false);
+        }
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < NBT; ++q)
+      ldsPart[(2 * w + ge) * VBM + q * 32 + (lane_e & 31)] = (part[q][0] + part[q][1]) + (part[q][2] + part[q][3]);
+  };
 
-  int64_t t = blockIdx.x;
-  if (t >= ntiles) return;
-  fetch(t, std::false_type{});
-  fetch(t, std::true_type{});
-  int staged_agent = -1;
-  float b3 = 0.0f;
-  stash();
+  // ---- set-up: first input tile, first agent's vectors, first weight blocks
+  const int64_t t_first = blockIdx.x;
+  if (t_first >= ntiles) return;
+  fetch(t_first, std::false_type{});
+  {
+    const Net net0 = net_of(a.net, agent_of_tile(t_first));
+    stage_biases(net0, tid, NT);
+    stage_w3(net0, tid, NT);
+  }
+  hold(std::false_type{});
+  fetch(t_first, std::true_type{});
+  stash(std::false_type{});
+  hold(std::true_type{});
+  stash(std::true_type{});
+  // which tile a chunk-1 request of step (e) is for: the next one (group A), the one after it (group B); past the
+  // end it re-reads the last tile (never used)
+  auto tile_for_e = [&](int64_t t) {
+    const int64_t want = t + (grpB ? 2 : 1) * (int64_t)gridDim.x;
+    return want < ntiles ? want : ntiles - 1;
+  };
+  if (grpB) {
+    // group B's chunk 1 of the second tile (its step (e) of a tile before the first)
+    fetch(tile_for_e(t_first - gridDim.x), std::true_type{});
+    hold(std::true_type{});
+  }
+  auto wptr = [&](int layer, int ag) {
+    return reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(a.net.W[layer]) + (size_t)ag * a.net.w_stride[layer]);
+  };
+  const int nkb1 = a.net.nkb[0];
   u32x4 ring[PD][CTH];
-  for (; t < ntiles; t += gridDim.x) {
-    const int64_t row0 = t * VBM;
+  prime<CTH, PD>(ring, wptr(0, agent_of_tile(t_first)), nkb1, nct, ct0, lane);
+  int agent_b = agent_of_tile(t_first), agent_w3 = agent_b;  // whose vectors sit in LDS
+  float b3_prev = 0.0f;
+  // hidden halves as this wavefront sees them: its own group's (written by its epilogue 1, first half of its
+  // layer 2) and the other group's (second half of its layer 2); k-blocks of layer 2 in the same order
+  unsigned char *const ldsOwn = grpB ? ldsXB : ldsHA;
+  const unsigned char *const ldsOther = grpB ? ldsHA : ldsXB;
+  const int kb_own = grpB ? NKBH : 0, kb_other = grpB ? 0 : NKBH;
+  __syncthreads();
+  // Both groups run the same five steps per tile -- (a) layer 1, (b) epilogue 1, (c) layer 2 over the own half,
+  // (d) layer 2 over the other half, (e) epilogue 2 + output dot -- with a workgroup barrier after each; group B
+  // starts one barrier late, which puts it one step behind group A for the whole launch (the table above).
+  // Matrix steps run at raised wavefront priority: a matrix instruction occupies the pipe for 32 cycles, so the
+  // epilogue wavefront of the SIMD loses one issue slot in eight, while without it the older wavefront of a SIMD
+  // wins every arbitration and a younger matrix wavefront starves behind an older epilogue wavefront.
+  if (grpB) __syncthreads();
+
+  for (int64_t t = t_first; t < ntiles; t += gridDim.x) {
     const int64_t tn = t + gridDim.x;
-    const bool more = tn < ntiles;
-    const int agent = (int)((row0 % a.N) / a.envs_per_agent);
-    const Net net = net_of(a.net, agent);
-    if (agent != staged_agent) {
-      // nothing reads the staged vectors between the barrier that ended the previous tile and the one after
-      // layer 1, so they can be replaced here
-      for (int i = tid; i < nct * 32; i += NT) {
-        ldsBias[i] = net.b[0][i];
-        ldsBias[nct * 32 + i] = net.b[1][i];
-        // output weights of feature 0 out of the packed blocks: k = 16 kb + 8 g + e sits in lane 32 g
-        const int kb = i >> 4, gg = (i >> 3) & 1, e = i & 7;
-        ldsW3[i] = reinterpret_cast<const __bf16 *>(net.W[2])[((size_t)kb * 64 + 32 * gg) * 8 + e];
-      }
-      b3 = net.b[2][0];
-      staged_agent = agent;
-      prime<CTH, PD>(ring, net.W[0], net.nkb[0], nct, ct0, lane);
-    }
-    __syncthreads();  // input tile complete
-    // Each phase works from its own opaque copy of the lane index: every LDS and weight address below is
-    // invariant across tiles, and hoisted out of the tile loop they would occupy (and spill) dozens of registers.
+    const int64_t tf = tn < ntiles ? tn : t;  // tile fetched during this one (the last one re-reads itself)
+    const int agent = agent_of_tile(t);
+    const int agent_n = tn < ntiles ? agent_of_tile(tn) : agent;
+    const u32x4 *W1 = wptr(0, agent), *W2 = wptr(1, agent);
     f32x16 acc[CTH][NBT];
-    zero_acc<CTH, NBT>(acc);
-    int lane_1 = lane;
-    asm volatile("" : "+v"(lane_1));
-    if (NKB1 > 0)
-      mma_layer_static<true, CTH, NBT, PD, NKB1>(acc, ring, ldsX, a.xpitch, net.W[0], nct, ct0, 0, lane_1);
-    else
-      mma_layer<true, CTH, NBT, PD>(acc, ring, ldsX, a.xpitch, net.nkb[0], net.W[0], nct, ct0, 0, lane_1);
-    prime<CTH, PD>(ring, net.W[1], net.nkb[1], nct, ct0, lane_1);
-    __syncthreads();  // every wavefront has consumed the input tile; the hidden tile goes over it
-    int lane_2 = lane;
-    asm volatile("" : "+v"(lane_2));
-    epilogue_hidden<true, CTH, NBT>(acc, ldsBias, ldsH, a.hpitch, nct, ct0, 0, lane_2);
-    __syncthreads();
-    zero_acc<CTH, NBT>(acc);
-    int lane_3 = lane;
-    asm volatile("" : "+v"(lane_3));
-    if (NKB2 > 0)
-      mma_layer_static<true, CTH, NBT, PD, NKB2>(acc, ring, ldsH, a.hpitch, net.W[1], nct, ct0, 0, lane_3);
-    else
-      mma_layer<true, CTH, NBT, PD>(acc, ring, ldsH, a.hpitch, net.nkb[1], net.W[1], nct, ct0, 0, lane_3);
-    // (unconditional -- the last tile re-reads itself -- so that no register of the previous fetch stays live)
-    const int64_t tf = more ? tn : t;
-    fetch(tf, std::false_type{});
-    __syncthreads();  // every wavefront has consumed the hidden tile
+
+    // ---- (a) layer 1, accumulators start from b1.  [A: phase 1, B: phase 2]
+    __builtin_amdgcn_s_setprio(kMatrixPrio);
     {
-      // layer 2's epilogue with the output layer folded in
-      int lane_e = lane;
-      asm volatile("" : "+v"(lane_e));
-      const int ge = lane_e >> 5;
-      const float *lb2 = ldsBias + nct * 32;
-      float part[NBT];
+      int lane_1 = lane;
+      asm volatile("" : "+v"(lane_1));
+      bias_acc<CTH, NBT>(acc, ldsBias, ct0, lane_1);
+      if (NKB1 > 0) {
+        mma_range_static<true, CTH, NBT, PD, (NKB1 > 0 ? NKB1 : PD)>(acc, ring, ldsXB, a.xpitch, W1, nct, 0, W2, nct,
+                                                                    kb_own, ct0, 0, lane_1);
+      } else {
+        mma_layer<true, CTH, NBT, PD>(acc, ring, ldsXB, a.xpitch, nkb1, W1, nct, ct0, 0, lane_1);
+        prime<CTH, PD>(ring, W2 + (size_t)kb_own * nct * 64, NKBH, nct, ct0, lane_1);
+      }
+    }
+    __builtin_amdgcn_s_setprio(0);
+    __syncthreads();
+
+    // ---- (b) epilogue 1 -> own hidden half; first chunk of the next rows.
+    //      [A: phase 2, B: phase 3: every wavefront is done with the input tile]
+    fetch(tf, std::false_type{});  // chunk 0 of the next tile
+    if (!grpB) {
+      if (t != t_first) {
+        // the previous tile's values: group B delivered its partial sums in phase 1
+        int tid_y = threadIdx.x;
+        asm volatile("" : "+v"(tid_y));
+        if (tid_y < VBM) {
+          float y = b3_prev;
 #pragma unroll
-      for (int q = 0; q < NBT; ++q) part[q] = 0.0f;
-#pragma unroll
-      for (int c = 0; c < CTH; ++c) {
-        if (c == CTH - 1) {
-          // pin the first half's arithmetic above the loads (it has no side effect of its own and would
-          // otherwise be sunk below them, keeping all accumulators alive)
-#pragma unroll
-          for (int q = 0; q < NBT; ++q) asm volatile("" : "+v"(part[q]));
-          fetch(tf, std::true_type{});
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int f0 = (ct0 + c) * 32 + 8 * j + 4 * ge;
-          const f32x4 bv = *reinterpret_cast<const f32x4 *>(lb2 + f0);
-          const u32x2 wv = *reinterpret_cast<const u32x2 *>(ldsW3 + f0);  // four bf16 weights
-          const uint32_t wlo = wv[0], whi = wv[1];  // (scalars first: a bit cast straight from a vector element reads element 0)
-          const bf16x2 w01 = __builtin_bit_cast(bf16x2, wlo), w23 = __builtin_bit_cast(bf16x2, whi);
-#pragma unroll
-          for (int q = 0; q < NBT; ++q) {
-            float h[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              h[i] = tanh_from_scaled(fmaf(acc[c][q][4 * j + i], kTwoLog2e, bv[i] * kTwoLog2e));
-            // activations rounded to bf16 as the hidden tile would hold them; products summed in fp32
-            const bf16x2 h01 = {(__bf16)h[0], (__bf16)h[1]}, h23 = {(__bf16)h[2], (__bf16)h[3]};
-            part[q] = __builtin_amdgcn_fdot2_f32_bf16(h01, w01, part[q], false);
-            part[q] = __builtin_amdgcn_fdot2_f32_bf16(h23, w23, part[q], false);
-          }
+          for (int p = 0; p < 2 * NW; ++p) y += ldsPart[p * VBM + tid_y];
+          __builtin_nontemporal_store(y, &a.Y[(t - gridDim.x) * VBM + tid_y]);
         }
       }
-#pragma unroll
-      for (int q = 0; q < NBT; ++q) ldsPart[(2 * w + ge) * VBM + q * 32 + (lane_e & 31)] = part[q];
+      // output weights of this tile's agent: last read (previous tile, group B) in phase 1, next in phase 5
+      if (agent != agent_w3) stage_w3(net_of(a.net, agent), tid, NT / 2);
     }
-    if (more) {
-      stash();
-      const int agent_n = (int)(((tn * VBM) % a.N) / a.envs_per_agent);
+    agent_w3 = agent;
+    {
+      int lane_2 = lane;
+      asm volatile("" : "+v"(lane_2));
+      // (column f of a row-major half sits at byte 2 (f - first feature of the half))
+      epilogue_hidden_biased<CTH, NBT>(acc, ldsOwn - (size_t)kb_own * 32, VHPITCH, ct0, 0, lane_2);
+    }
+    hold(std::false_type{});
+    __syncthreads();
+
+    // ---- (c) layer 2 over the own half, accumulators start from b2.  [A: phase 3, B: phase 4]
+    __builtin_amdgcn_s_setprio(kMatrixPrio);
+    {
+      int lane_3 = lane;
+      asm volatile("" : "+v"(lane_3));
+      bias_acc<CTH, NBT>(acc, ldsBias + nct * 32, ct0, lane_3);
+      mma_range_static<true, CTH, NBT, PD, NKBH>(acc, ring, ldsOwn, VHPITCH, W2, nct, kb_own, W2, nct, kb_other, ct0, 0,
+                                                 lane_3);
+    }
+    __syncthreads();
+
+    // ---- (d) layer 2 over the other half.  [A: phase 4; B: phase 5 -- the input region is free: B writes its
+    //      rows, both chunks].  No weight blocks of the next tile yet.
+    if (grpB) {
+      stash(std::false_type{});
+      stash(std::true_type{});
+    }
+    {
       int lane_4 = lane;
       asm volatile("" : "+v"(lane_4));
-      if (agent_n == agent) prime<CTH, PD>(ring, net.W[0], net.nkb[0], nct, ct0, lane_4);
+      mma_range_static<true, CTH, NBT, PD, NKBH, false>(acc, ring, ldsOther, VHPITCH, W2, nct, kb_other, W2, nct, 0, ct0,
+                                                        0, lane_4);
     }
-    __syncthreads();  // partial sums (and the next input tile) complete
+    __builtin_amdgcn_s_setprio(0);
+    __syncthreads();
+
+    // ---- (e) epilogue 2 + output dot.  [A: phase 5 -- writes its rows of the next input tile; B: phase 1 of the
+    //      next tile]
+    if (!grpB) {
+      stash(std::false_type{});
+      // hidden biases of the next tile's agent: last read in phase 4 (group B), next in phase 1
+      if (agent_n != agent_b) stage_biases(net_of(a.net, agent_n), tid, NT / 2);
+    }
+    agent_b = agent_n;
+    fetch(tile_for_e(t), std::true_type{});
+    epilogue_out_dot(acc);
+    hold(std::true_type{});
+    if (!grpB) stash(std::true_type{});
+    {
+      int lane_5 = lane;
+      asm volatile("" : "+v"(lane_5));
+      prime<CTH, PD>(ring, wptr(0, agent_n), nkb1, nct, ct0, lane_5);  // in flight across the barrier
+    }
+    b3_prev = a.net.b[2][(size_t)agent * a.net.b_stride[2]];
+    __syncthreads();
+  }
+  // drain: group A waits out group B's last step, then writes the last tile's values
+  if (!grpB) {
+    __syncthreads();
     int tid_y = threadIdx.x;
     asm volatile("" : "+v"(tid_y));
     if (tid_y < VBM) {
-      float y = b3;
+      // (the last tile this workgroup took)
+      const int64_t t_last = t_first + (ntiles - 1 - t_first) / gridDim.x * gridDim.x;
+      float y = b3_prev;
 #pragma unroll
       for (int p = 0; p < 2 * NW; ++p) y += ldsPart[p * VBM + tid_y];
-      __builtin_nontemporal_store(y, &a.Y[row0 + tid_y]);
+      __builtin_nontemporal_store(y, &a.Y[t_last * VBM + tid_y]);
     }
   }
 }
@@ -911,9 +1144,9 @@ static bool try_launch_tiles(hipStream_t st, const PackedNet &net, int64_t rows,
 }
 
 
-template <int NKB1, int NKB2, int SS>
+template <int NKB1, int SS>
 static hipError_t launch_value(hipStream_t st, const ValueArgs &a, unsigned blocks, size_t lds) {
-  constexpr auto kern = value_kernel<NKB1, NKB2, SS>;
+  constexpr auto kern = value_kernel<NKB1, SS>;
   const hipError_t e = allow_full_lds<kern>();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(512), lds, st, a);
@@ -926,9 +1159,9 @@ static hipError_t launch_value(hipStream_t st, const ValueArgs &a, unsigned bloc
 static bool try_launch_value(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx,
                              float *Y, int32_t N, int32_t envs_per_agent, hipError_t *err) {
   const int S = net.in_dim[0], Hd = net.out_dim[0];
-  if (!net.bf16 || net.out_dim[2] != 1 || Hd != 512 || net.out_dim[1] != 512 || ldx != S || S < 4) return false;
+  if (!net.bf16 || net.out_dim[2] != 1 || Hd != 2 * VHALF || net.out_dim[1] != Hd || ldx != S || S < 4) return false;
   if ((reinterpret_cast<uintptr_t>(X) & 3u) || N % VBM != 0 || envs_per_agent % VBM != 0) return false;
-  if (net.nkb[0] > VPRE_MAX || rows < (int64_t)VBM * 4 * compute_units()) return false;
+  if (net.nkb[0] > VPRE_MAX || net.nkb[0] < 4 || rows < (int64_t)VBM * 4 * compute_units()) return false;
   ValueArgs a;
   a.X = X;
   a.rows = rows;
@@ -940,14 +1173,23 @@ static bool try_launch_value(hipStream_t st, const PackedNet &net, int64_t rows,
   a.groups = net.nkb[0] * 4;
   a.g_magic = (uint32_t)((0x100000000ull + (uint64_t)a.groups - 1) / (uint64_t)a.groups);
   a.xpitch = tile::tile_pitch(net.nkb[0] * 16, 2);
-  a.hpitch = tile::tile_pitch(Hd, 2);
-  const size_t lds = (size_t)VBM * a.hpitch + (size_t)net.nct[0] * 32 * (4 + 4 + 2) + (size_t)16 * VBM * 4;
-  if (lds > 160 * 1024) return false;
+  // LDS: hidden half A | input tile or hidden half B | b1, b2 | output weights | partial sums
+  size_t off = (size_t)VBM * VHPITCH;
+  a.off_xb = (int32_t)off;
+  off += (size_t)VBM * (a.xpitch > VHPITCH ? a.xpitch : VHPITCH);
+  a.off_bias = (int32_t)off;
+  off += (size_t)2 * Hd * 4;
+  a.off_w3 = (int32_t)off;
+  off += (size_t)Hd * 2;
+  a.off_part = (int32_t)off;
+  off += (size_t)16 * VBM * 4;
+  const size_t lds = off;
+  if (lds > (size_t)kMaxLdsBytes) return false;
   const int64_t ntiles = rows / VBM;
   const unsigned blocks = (unsigned)(ntiles < compute_units() ? ntiles : compute_units());
   // the observation width of the named workloads gets compile-time index arithmetic and k loops
-  if (S == 301) *err = launch_value<19, 32, 301>(st, a, blocks, lds);
-  else *err = launch_value<0, 32, 0>(st, a, blocks, lds);
+  if (S == 301) *err = launch_value<19, 301>(st, a, blocks, lds);
+  else *err = launch_value<0, 0>(st, a, blocks, lds);
   return true;
 }
 

@@ -264,6 +264,49 @@ __device__ inline void mma_layer_static(f32x16 (&acc)[CT][NBT], u32x4 (&ring)[PD
   }
 }
 
+// NKB consecutive k-blocks of a layer, straight-line, for callers that walk a layer in pieces or chain layers
+// without a stall: LDS column block i of `ldsX` pairs with weight block kbw0 + i of W.  On entry ring slot s must
+// hold weight block kbw0 + s (s < PD).  Inside the range a consumed slot is refilled with the block PD ahead; the
+// last PD steps refill their slots with blocks kbn0 + (slot) of Wn (nctn feature tiles per k-block): the ring is
+// then primed, slot for slot, for a range that starts at block kbn0 of Wn.  NEXT = false: no refills in the last PD
+// steps (the ring's registers are free afterwards; the caller primes it again before the next range).
+template <bool BF16, int CT, int NBT, int PD, int NKB, bool NEXT = true>
+__device__ inline void mma_range_static(f32x16 (&acc)[CT][NBT], u32x4 (&ring)[PD][CT], const unsigned char *ldsX,
+                                        int pitch, const u32x4 *W, int nct, int kbw0, const u32x4 *Wn, int nctn,
+                                        int kbn0, int ct0, int bt0, int lane) {
+  using O = Op<BF16>;
+  static_assert(NKB >= PD, "a range must be at least as long as the ring");
+  const int brow = lane & 31, g = lane >> 5;
+  const unsigned char *xbase = ldsX + (size_t)(bt0 * 32 + brow) * pitch + 16 * g;
+  const u32x4 *wp[CT], *wn[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) {
+    wp[c] = W + ((size_t)kbw0 * nct + min(ct0 + c, nct - 1)) * 64 + lane;
+    wn[c] = Wn + ((size_t)kbn0 * nctn + min(ct0 + c, nctn - 1)) * 64 + lane;
+  }
+#pragma unroll
+  for (int i = 0; i < NKB; ++i) {
+    constexpr int dummy = 0;
+    (void)dummy;
+    const int s = i % PD;
+    u32x4 x[NBT];
+#pragma unroll
+    for (int t = 0; t < NBT; ++t) x[t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)t * 32 * pitch + i * 32);
+#pragma unroll
+    for (int c = 0; c < CT; ++c)
+#pragma unroll
+      for (int t = 0; t < NBT; ++t) O::mma(ring[s][c], x[t], acc[c][t]);
+    if (i + PD < NKB) {
+#pragma unroll
+      for (int c = 0; c < CT; ++c) ring[s][c] = wp[c][(size_t)(i + PD) * nct * 64];
+    } else if (NEXT) {
+#pragma unroll
+      for (int c = 0; c < CT; ++c) ring[s][c] = wn[c][(size_t)s * nctn * 64];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 template <int CT, int NBT>
 __device__ inline void zero_acc(f32x16 (&acc)[CT][NBT]) {
 #pragma unroll
@@ -272,6 +315,77 @@ __device__ inline void zero_acc(f32x16 (&acc)[CT][NBT]) {
     for (int t = 0; t < NBT; ++t)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[c][t][i] = 0.0f;
+}
+
+// acc = bias of the wavefront's features (every batch row alike): a layer started this way needs no bias add in
+// its epilogue.  bias: LDS, padded to whole feature tiles.
+template <int CT, int NBT>
+__device__ inline void bias_acc(f32x16 (&acc)[CT][NBT], const float *bias, int ct0, int lane) {
+  const int g = lane >> 5;
+#pragma unroll
+  for (int c = 0; c < CT; ++c)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias + (ct0 + c) * 32 + 8 * j + 4 * g);
+#pragma unroll
+      for (int t = 0; t < NBT; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[c][t][4 * j + i] = bv[i];
+    }
+}
+
+// acc <- tanh(acc), in place, one feature tile (all NBT batch tiles of it: 16 NBT values per lane) at a time and
+// one operation at a time over all of them: every instruction's operand was produced 16 NBT instructions earlier,
+// so a wavefront that has a SIMD's vector unit to itself never waits for a result.  (Written value by value, the
+// compiler keeps four chains in flight -- all the registers it has next to live accumulators -- and the
+// transcendental latencies are exposed.)  The barriers keep the scheduler from interleaving the stages again.
+template <int NBT>
+__device__ inline void tanh_in_place(f32x16 (&acc)[NBT]) {
+#pragma unroll
+  for (int t = 0; t < NBT; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[t][i] *= kTwoLog2e;
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int t = 0; t < NBT; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[t][i] = __builtin_amdgcn_exp2f(acc[t][i]);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int t = 0; t < NBT; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[t][i] += 1.0f;
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int t = 0; t < NBT; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[t][i] = __builtin_amdgcn_rcpf(acc[t][i]);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int t = 0; t < NBT; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[t][i] = fmaf(-2.0f, acc[t][i], 1.0f);
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// hidden = tanh(acc) -> LDS, for bf16 layers whose accumulators started from the bias (bias_acc).  Overwrites acc.
+template <int CT, int NBT>
+__device__ inline void epilogue_hidden_biased(f32x16 (&acc)[CT][NBT], unsigned char *ldsH, int hpitch, int ct0,
+                                              int bt0, int lane) {
+  using O = Op<true>;
+  const int brow = lane & 31, g = lane >> 5;
+#pragma unroll
+  for (int c = 0; c < CT; ++c) {
+    tanh_in_place<NBT>(acc[c]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int f0 = (ct0 + c) * 32 + 8 * j + 4 * g;
+#pragma unroll
+      for (int t = 0; t < NBT; ++t)
+        O::store4(ldsH + (size_t)((bt0 + t) * 32 + brow) * hpitch + f0 * O::ESZ, acc[c][t][4 * j], acc[c][t][4 * j + 1],
+                  acc[c][t][4 * j + 2], acc[c][t][4 * j + 3]);
+    }
+  }
 }
 
 // hidden = tanh(acc + bias) -> row-major [batch][feature] LDS tile in the operand type.

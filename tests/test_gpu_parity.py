@@ -82,11 +82,14 @@ def test_mlp_forward_matches_checker(name, rows, agents):
             parity.check_networks(w, d["actor"], d["critic"], X[sel], mu[sel], val[sel], agent=g)
 
 
-@pytest.mark.parametrize("name,agents", [("large", 1), ("large", 3), ("dow30", 1)])
-def test_value_head_over_many_tiles_matches_checker(name, agents):
+@pytest.mark.parametrize("name,agents,stocks", [("large", 1, 30), ("large", 3, 30), ("dow30", 1, 30), ("large", 2, 20),
+                                                ("large", 1, 33)])
+def test_value_head_over_many_tiles_matches_checker(name, agents, stocks):
     """A long critic buffer: many tiles per compute unit in one persistent launch (the 128-row value-head
-    kernel for the bf16 networks), a ragged tail behind it, and agents that change along the buffer."""
-    w = inputs.WORKLOADS[name].replace(n_envs=128 * agents, n_agents=agents, steps=2)
+    kernel for the bf16 networks), a ragged tail behind it, and agents that change along the buffer; also at
+    observation widths other than the named workloads' 301 (20 stocks: 201 columns, rows narrower than 64
+    16-byte groups; 33 stocks: 331 columns, too wide for that kernel)."""
+    w = inputs.WORKLOADS[name].replace(n_envs=128 * agents, n_agents=agents, steps=2, n_stocks=stocks)
     d, ro, _ = _make(w)
     rows = 128 * 4 * 256 + 128 * agents + 64 + 40
     g = torch.Generator(device=DEV)
