@@ -269,6 +269,51 @@ def calibrate():
     print(json.dumps({"calibration": res}))
 
 
+def stages_alone(torch, pr, inputs, w, d, ro, out, roll, obs2d, sched, dev):
+    """Each stage of the path launched on its own (untimed companions of the timed path; none is part of `value`):
+    the environment + sampling stage with caller-supplied means (rollout_step_forced: the rollout's own kernel
+    without the actor) and the actor on all T x N recorded observations in one launch (rollout_mlp_forward).  In
+    the persistent schedule both live in one kernel, so these launches are what separates the environment's share
+    of the HBM roofline from the actor's share of the matrix roofline."""
+    T, N, D, S = w.steps, w.n_envs, w.n_stocks, w.state_dim
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    res = {}
+    mf = "mfma_bf16" if w.mlp_dtype else "mfma_fp32"
+    # actor over the recorded buffer
+    mu = torch.empty((T * N, D), dtype=torch.float32, device=dev)
+    ro.mlp_forward(pr.PR_NET_ACTOR, obs2d[:T * N], mu)
+    e0.record()
+    for _ in range(2):
+        ro.mlp_forward(pr.PR_NET_ACTOR, obs2d[:T * N], mu)
+    e1.record()
+    torch.cuda.synchronize()
+    t_actor = e0.elapsed_time(e1) / 2
+    fl = inputs.mlp_flops_per_env_step(w, critic=False) * T * N
+    res["actor_alone"] = {"ms": t_actor, "TFLOPs": fl / t_actor / 1e9, "frac_mfma": fl / t_actor / 1e9 / PEAK[mf][0],
+                          "note": "rollout_mlp_forward(actor) on the T x N recorded observations, one launch"}
+    # environment + sampling stage, forced onto the recorded means
+    mu3 = mu.view(T, N, D)
+
+    def forced():
+        ro.reset()
+        ro.step_forced(T, mu3, d["noise"], roll)
+
+    forced()
+    e0.record()
+    for _ in range(2):
+        forced()
+    e1.record()
+    torch.cuda.synchronize()
+    t_env = e0.elapsed_time(e1) / 2
+    by = inputs.bytes_per_env_step(w) * T * N
+    res["env_alone"] = {"ms": t_env, "algorithmic_GBps": by / t_env / 1e6, "frac_hbm": by / t_env / 1e6 / PEAK["hbm"][0],
+                        "note": "rollout_step_forced over T steps (observation assembly, sampling, trades, reward, "
+                                "done / reset) with the means of the actor launch above, "
+                                + ("one persistent launch" if sched == pr.PR_SCHED_FUSED else "one launch per step")}
+    del mu
+    return res
+
+
 def main():
     if "--calibrate" in sys.argv[1:]:
         return calibrate()
@@ -343,6 +388,7 @@ def main():
         torch.mul(src, 1.0, out=dst)  # one vectorised elementwise kernel: reads and writes copy_calibration MiB
         torch.cuda.synchronize()
 
+    alone = {} if args.no_extras else stages_alone(torch, pr, inputs, w, d, ro, out, roll, obs2d, sched, dev)
     extras = {} if args.no_extras else side_measurements(torch, pr, inputs, w, d, out, roll, adv, ret, obs2d, val2d,
                                                          sched, dev)
     ms = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in events) / args.steps
@@ -381,6 +427,7 @@ def main():
                    "env_steps_per_step": env_steps},
         "roofline": dom,
         "stages": stages,
+        "stages_alone": alone,
         "extras": extras,
     }
     if not args.no_cpu_baseline:
