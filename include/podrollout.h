@@ -68,7 +68,10 @@ typedef struct pr_config {
   int32_t schedule;     /* PR_SCHED_STEPWISE: one actor launch and one env launch
                            per step; PR_SCHED_FUSED: one persistent launch that
                            keeps each env tile on one compute unit for all T
-                           steps.  Same results bit for bit. */
+                           steps (bf16 networks with 256 or 512 hidden units,
+                           fp32 networks with 256; D <= 32, D K <= 252 and a
+                           multiple of 4; else PR_EUNSUPPORTED at init).  Given the
+                           same policy means, the same results bit for bit. */
   float cash0;          /* initial capital (> 0) */
   float hmax;           /* largest trade per stock and step, in shares */
   float cost;           /* proportional transaction cost c, 0 <= c < 1 */

@@ -35,7 +35,8 @@ using namespace tile;
 
 constexpr int NW = 8;
 constexpr int NT = NW * 64;
-constexpr int E = BM;            // envs per workgroup
+// envs per workgroup: 64 (bf16 networks) or 32 (fp32 networks, whose 64-row tiles do not fit in LDS); a template
+// parameter E of the kernel
 constexpr int PAIRS_MAX = 4;     // (env, stock) pairs per lane: D <= 32
 constexpr int DMAX = 32;         // stock slots per env row in LDS; slots D..31 hold neutral values (k = 0, h = 0)
 constexpr int kDp = DMAX + 1;    // odd row pitch: the per-env serial walks of the ledger hit distinct banks
@@ -108,8 +109,10 @@ __device__ inline Row row_of(const EnvDims &d, int32_t tau, int32_t start, int32
   return r;
 }
 
-template <bool BF16, int CTH, int NKB1, int NKB2, bool ACTOR>
+template <bool BF16, int E, int CTH, int NKB1, int NKB2, bool ACTOR>
 __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
+  static_assert(E == 64 || E == 32, "one or two 32-row batch tiles");
+  constexpr int NBT = E / 32;
   using O = tile::Op<BF16>;
   extern __shared__ __align__(16) unsigned char lds[];
   const EnvDims &d = a.d;
@@ -150,12 +153,12 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     net = net_of(a.actor, (n0 % d.N) / a.envs_per_agent);
     stage_net<NT>(net, ldsBias, ldsW3, tid);
     // padded k columns of the input tile must read as zero
-    for (int i = tid; i < BM * a.L.xpitch / 4; i += NT) reinterpret_cast<uint32_t *>(ldsX)[i] = 0u;
+    for (int i = tid; i < E * a.L.xpitch / 4; i += NT) reinterpret_cast<uint32_t *>(ldsX)[i] = 0u;
   }
   __syncthreads();
 
   // ---- prologue: load the state, emit observation 0
-  if (wave == 0) {
+  if (wave == 0 && lane < E) {
     const int n = n0 + lane;
     cash = a.st.cash[n];
     tau = a.st.tau[n];
@@ -302,7 +305,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     emit_portfolio(a.obs, std::false_type{}, 0);
   }
   __syncthreads();
-  if (wave == 0) {
+  if (wave == 0 && lane < E) {
     // account value the first reward is measured against; cursor rows of step 0
     const int e = lane;
     double v = (double)cash;
@@ -323,7 +326,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     const size_t g0 = ((size_t)t * N + n0) * D;
 
     if (ACTOR) {
-      mlp_tile<BF16, NW, CTH, false, NKB1, NKB2, true, true, KS>(
+      mlp_tile<BF16, NW, CTH, false, NKB1, NKB2, true, true, KS, NBT>(
           net, ring, ldsX, a.L.xpitch, ldsH, a.L.hpitch, ldsBias, ldsW3, tid,
           [&]() {
             fetch_step_inputs(t);
@@ -400,7 +403,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       }
     __syncthreads();
 
-    if (wave == 0) {
+    if (wave == 0 && lane < E) {
       // ---- the ledger: one lane per env walks the cash chain in stock order
       // Each pass stages a chunk of the lane's row in registers first, so that the LDS reads of a chunk are
       // all in flight together and the dependent chain on `cash` runs on registers only.
@@ -483,7 +486,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       s_cash[e] = cash;
       s_done[e] = dn;
       s_row[e] = row_of(d, tau, start, n);  // cursor rows of step t + 1 (nobody reads the old ones any more)
-    } else if (wave == 1 && a.logp) {
+    } else if (wave == 1 && lane < E && a.logp) {
       // ---- log-probability of the sampled action: squared noise summed in stock order, one lane per env
       int e = lane;
       asm volatile("" : "+v"(e));
@@ -510,7 +513,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
 
   // ---- epilogue: state back to the workspace
   __syncthreads();
-  if (wave == 0) {
+  if (wave == 0 && lane < E) {
     const int n = n0 + lane;
     a.st.cash[n] = cash;
     a.st.tau[n] = tau;
@@ -528,37 +531,44 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
 // Kernel instance for a configuration: feature tiles per wavefront and, for the named shape, compile-time k-block
 // counts of layers 1 and 2 (0: read at run time).
 struct FusedShape {
-  int cth, nkb1, nkb2;
+  int envs, cth, nkb1, nkb2;  // envs per workgroup; feature tiles per wavefront; k-blocks of layers 1, 2 (0: run time)
 };
 
 FusedShape fused_shape(const pr_config &c) {
   const int S = 1 + 2 * c.n_stocks + c.n_stocks * c.n_ind;
+  const int KB = c.mlp_dtype == PR_MLP_BF16 ? 16 : 8;
   FusedShape f;
+  f.envs = c.mlp_dtype == PR_MLP_BF16 ? 64 : 32;
   f.cth = (c.hidden / 32) / NW;
   f.nkb1 = f.nkb2 = 0;
-  if (f.cth == 2 && (S + 15) / 16 == 19 && c.hidden / 16 == 32) f.nkb1 = 19, f.nkb2 = 32;
+  // the named shapes: 301 inputs with 512 hidden units in bf16 / 256 hidden units in fp32
+  if (KB == 16 && f.cth == 2 && (S + 15) / 16 == 19 && c.hidden / 16 == 32) f.nkb1 = 19, f.nkb2 = 32;
+  if (KB == 8 && f.cth == 1 && (S + 7) / 8 == 38 && c.hidden / 8 == 32) f.nkb1 = 38, f.nkb2 = 32;
   return f;
 }
 
-// The one carve-up of the kernel's LDS (bf16 operands).
+// The one carve-up of the kernel's LDS.
 FusedLayout fused_layout(const pr_config &c, bool with_actor) {
   const int D = c.n_stocks, S = 1 + 2 * D + D * c.n_ind, Hd = c.hidden;
-  constexpr int KB = 16, esz = 2;
+  const bool bf = c.mlp_dtype == PR_MLP_BF16;
+  const int KB = bf ? 16 : 8, esz = bf ? 2 : 4;
+  const FusedShape fs = fused_shape(c);
+  const int E = fs.envs;
   const int nkb1 = (S + KB - 1) / KB, nct = Hd / 32;
   FusedLayout L;
   L.xpitch = tile_pitch(nkb1 * KB, esz);
   L.hpitch = tile_pitch(Hd, esz);
   // the env scratch (slots 16 B, executed shares, valuation prices, squared noise) must fit in the hidden tile
   const size_t env_scratch = (size_t)7 * E * kDp * 4;
-  if ((size_t)BM * L.hpitch < env_scratch) L.hpitch = (int32_t)(((env_scratch + BM - 1) / BM + 15) / 16 * 16);
-  size_t off = (size_t)BM * L.hpitch;
+  if ((size_t)E * L.hpitch < env_scratch) L.hpitch = (int32_t)(((env_scratch + E - 1) / E + 15) / 16 * 16);
+  size_t off = (size_t)E * L.hpitch;
   L.off_x = (int32_t)off;
-  size_t xbytes = (size_t)BM * L.xpitch;
-  const size_t mu_bytes = with_actor ? (size_t)mu_planes(fused_shape(c).nkb2) * E * MUP * 4 : 0;
+  size_t xbytes = (size_t)E * L.xpitch;
+  const size_t mu_bytes = with_actor ? (size_t)mu_planes(fs.nkb2) * E * MUP * 4 : 0;
   if (xbytes < mu_bytes) xbytes = (mu_bytes + 15) / 16 * 16;
   off += xbytes;
   L.off_w3 = (int32_t)off;
-  if (with_actor) off += (size_t)(Hd / KB) * 1024;  // output layer: one feature tile, Hd / 16 k-blocks of 1 KiB
+  if (with_actor) off += (size_t)(Hd / KB) * 1024;  // output layer: one feature tile, Hd / KB k-blocks of 1 KiB
   L.off_bias = (int32_t)off;
   if (with_actor) off += (size_t)(2 * nct + 1) * 32 * 4;
   L.off_h = (int32_t)off;
@@ -579,23 +589,27 @@ constexpr size_t kLdsMax = kMaxLdsBytes;
 
 }  // namespace
 
-// Shapes the persistent kernel covers: bf16 networks whose whole input tile, hidden tile and output-layer
-// weights fit in LDS next to the env arrays; N a multiple of 64; D <= 32; D K <= 252 and a multiple of 4 (the
-// indicator rows are moved in 16-byte groups; the market tensors must be 16-byte aligned); one output feature tile.
+// Shapes the persistent kernel covers: networks whose whole input tile, hidden tile and output-layer weights fit
+// in LDS next to the env arrays -- bf16 with 256 or 512 hidden units on 64-env tiles, fp32 with 256 hidden units
+// on 32-env tiles; N (and the envs of an agent) a multiple of the tile; D <= 32; D K <= 252 and a multiple of 4
+// (the indicator rows are moved in 16-byte groups; the market tensors must be 16-byte aligned); one output
+// feature tile.
 bool fused_supported(const pr_config &c) {
   const int D = c.n_stocks, DK = c.n_stocks * c.n_ind, S = 1 + 2 * D + DK, Hd = c.hidden;
-  if (c.n_envs % 64 != 0 || D > 32 || DK > 252 || DK < 4 || DK % 4 != 0 || S < 4) return false;
-  if (c.mlp_dtype != PR_MLP_BF16) return false;
+  if (c.mlp_dtype != PR_MLP_BF16 && c.mlp_dtype != PR_MLP_F32) return false;
+  const int E = fused_shape(c).envs;
+  if (c.n_envs % E != 0 || D > 32 || DK > 252 || DK < 4 || DK % 4 != 0 || S < 4) return false;
   if (Hd % 32 != 0 || Hd < 256 || Hd > 512 || (Hd / 32) % NW != 0) return false;
-  if (c.n_agents > 1 && (c.n_envs / c.n_agents) % 64 != 0) return false;
+  if (c.mlp_dtype == PR_MLP_F32 && Hd != 256) return false;
+  if (c.n_agents > 1 && (c.n_envs / c.n_agents) % E != 0) return false;
   return fused_lds_bytes(c, true) <= kLdsMax;
 }
 
 size_t fused_lds_bytes(const pr_config &c, bool with_actor) { return (size_t)fused_layout(c, with_actor).total; }
 
-template <bool ACTOR, int CTH, int NKB1, int NKB2>
+template <bool BF16, int E, bool ACTOR, int CTH, int NKB1, int NKB2>
 static hipError_t launch_fused_inst(hipStream_t st, const FusedArgs &a, unsigned blocks, size_t lds) {
-  constexpr auto kern = rollout_fused_kernel<true, CTH, NKB1, NKB2, ACTOR>;
+  constexpr auto kern = rollout_fused_kernel<BF16, E, CTH, NKB1, NKB2, ACTOR>;
   const hipError_t e = allow_full_lds<kern>();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(NT), lds, st, a);
@@ -631,15 +645,22 @@ hipError_t launch_rollout_fused(hipStream_t st, const pr_config &c, const EnvDim
   if (reinterpret_cast<uintptr_t>(ind) & 15u) return hipErrorInvalidValue;  // 16-byte indicator loads
   const size_t lds = (size_t)a.L.total;
   if (lds > kLdsMax) return hipErrorInvalidValue;
-  const unsigned blocks = (unsigned)(d.N / E);
   const FusedShape fs = fused_shape(c);
-  if (with_actor && (actor.nkb[0] * 32 + 16 != a.L.xpitch || actor.nkb[1] * 32 + 16 > a.L.hpitch ||
-                     actor.nkb[2] != actor.nkb[1] || actor.nct[2] != 1))
+  const unsigned blocks = (unsigned)(d.N / fs.envs);
+  const int KB = actor.bf16 ? 16 : 8, esz = actor.bf16 ? 2 : 4;
+  if (with_actor && ((actor.bf16 != 0) != (c.mlp_dtype == PR_MLP_BF16) || tile_pitch(actor.nkb[0] * KB, esz) != a.L.xpitch ||
+                     tile_pitch(actor.nkb[1] * KB, esz) > a.L.hpitch || actor.nkb[2] != actor.nkb[1] || actor.nct[2] != 1))
     return hipErrorInvalidValue;  // the packed network is not the one the layout was made for
-  if (!with_actor) return launch_fused_inst<false, 1, 0, 0>(st, a, blocks, lds);
-  if (fs.cth == 2 && fs.nkb1 == 19 && fs.nkb2 == 32) return launch_fused_inst<true, 2, 19, 32>(st, a, blocks, lds);
-  if (fs.cth == 2) return launch_fused_inst<true, 2, 0, 0>(st, a, blocks, lds);
-  if (fs.cth == 1) return launch_fused_inst<true, 1, 0, 0>(st, a, blocks, lds);
+  if (c.mlp_dtype == PR_MLP_BF16) {
+    if (!with_actor) return launch_fused_inst<true, 64, false, 1, 0, 0>(st, a, blocks, lds);
+    if (fs.cth == 2 && fs.nkb1 == 19 && fs.nkb2 == 32) return launch_fused_inst<true, 64, true, 2, 19, 32>(st, a, blocks, lds);
+    if (fs.cth == 2) return launch_fused_inst<true, 64, true, 2, 0, 0>(st, a, blocks, lds);
+    if (fs.cth == 1) return launch_fused_inst<true, 64, true, 1, 0, 0>(st, a, blocks, lds);
+  } else {
+    if (!with_actor) return launch_fused_inst<false, 32, false, 1, 0, 0>(st, a, blocks, lds);
+    if (fs.cth == 1 && fs.nkb1 == 38 && fs.nkb2 == 32) return launch_fused_inst<false, 32, true, 1, 38, 32>(st, a, blocks, lds);
+    if (fs.cth == 1) return launch_fused_inst<false, 32, true, 1, 0, 0>(st, a, blocks, lds);
+  }
   return hipErrorInvalidValue;
 }
 

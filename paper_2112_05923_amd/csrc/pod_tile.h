@@ -530,8 +530,10 @@ constexpr int ring_depth(int cth) { return cth >= 8 ? 2 : 4; }
 // a functor instead; it is called by EVERY wavefront as layer1(acc, ring, active) (it may contain barriers), must
 // leave layer 1's sums of the active wavefronts in acc, and owns the ring while it runs.
 struct WholeTileLayer1 {};
+// NBT: 32-row batch tiles of the tile (2: the usual 64 rows; 1: a 32-row tile, for shapes whose 64-row tiles do not
+// fit in LDS).
 template <bool BF16, int NW, int CTH, bool WIDE_OUT, int NKB1, int NKB2, bool PRIMED, bool RAW_OUT, int KSPLIT = 1,
-          class Early, class Late, class Sink, class Layer1 = WholeTileLayer1>
+          int NBT = 2, class Early, class Late, class Sink, class Layer1 = WholeTileLayer1>
 __device__ inline void mlp_tile(const Net &net, u32x4 (&ring)[ring_depth(CTH)][CTH], const unsigned char *ldsX,
                                 int xpitch, unsigned char *ldsH, int hpitch, const float *ldsBias,
                                 const u32x4 *ldsW3, int tid, Early early, Late late, Sink sink,
@@ -543,39 +545,39 @@ __device__ inline void mlp_tile(const Net &net, u32x4 (&ring)[ring_depth(CTH)][C
   const bool act = ct0 < net.nct[0];
   const float *lb1 = ldsBias, *lb2 = ldsBias + net.nct[0] * 32, *lb3 = lb2 + net.nct[1] * 32;
   {
-    f32x16 acc[CTH][2];
-    zero_acc<CTH, 2>(acc);
+    f32x16 acc[CTH][NBT];
+    zero_acc<CTH, NBT>(acc);
     if constexpr (!std::is_same<Layer1, WholeTileLayer1>::value) {
       layer1(acc, ring, act);
       if (act) prime<CTH, PD>(ring, net.W[1], net.nkb[1], net.nct[1], ct0, lane);
     } else if (act) {
       if (!PRIMED) prime<CTH, PD>(ring, net.W[0], net.nkb[0], net.nct[0], ct0, lane);
       if (NKB1 > 0)
-        mma_layer_static<BF16, CTH, 2, PD, NKB1>(acc, ring, ldsX, xpitch, net.W[0], net.nct[0], ct0, 0, lane);
+        mma_layer_static<BF16, CTH, NBT, PD, NKB1>(acc, ring, ldsX, xpitch, net.W[0], net.nct[0], ct0, 0, lane);
       else
-        mma_layer<BF16, CTH, 2, PD>(acc, ring, ldsX, xpitch, net.nkb[0], net.W[0], net.nct[0], ct0, 0, lane);
+        mma_layer<BF16, CTH, NBT, PD>(acc, ring, ldsX, xpitch, net.nkb[0], net.W[0], net.nct[0], ct0, 0, lane);
       prime<CTH, PD>(ring, net.W[1], net.nkb[1], net.nct[1], ct0, lane);
     }
     early();
-    if (act) epilogue_hidden<BF16, CTH, 2>(acc, lb1, ldsH, hpitch, net.nct[0], ct0, 0, lane);
+    if (act) epilogue_hidden<BF16, CTH, NBT>(acc, lb1, ldsH, hpitch, net.nct[0], ct0, 0, lane);
     __syncthreads();
-    zero_acc<CTH, 2>(acc);
+    zero_acc<CTH, NBT>(acc);
     if (act) {
       if (NKB2 > 0)
-        mma_layer_static<BF16, CTH, 2, PD, NKB2>(acc, ring, ldsH, hpitch, net.W[1], net.nct[1], ct0, 0, lane);
+        mma_layer_static<BF16, CTH, NBT, PD, NKB2>(acc, ring, ldsH, hpitch, net.W[1], net.nct[1], ct0, 0, lane);
       else
-        mma_layer<BF16, CTH, 2, PD>(acc, ring, ldsH, hpitch, net.nkb[1], net.W[1], net.nct[1], ct0, 0, lane);
+        mma_layer<BF16, CTH, NBT, PD>(acc, ring, ldsH, hpitch, net.nkb[1], net.W[1], net.nct[1], ct0, 0, lane);
     }
     __syncthreads();  // every wavefront has consumed the layer-1 tile; it is overwritten in place
-    if (act) epilogue_hidden<BF16, CTH, 2>(acc, lb2, ldsH, hpitch, net.nct[1], ct0, 0, lane);
+    if (act) epilogue_hidden<BF16, CTH, NBT>(acc, lb2, ldsH, hpitch, net.nct[1], ct0, 0, lane);
     __syncthreads();
   }
-  // output layer: few features.  One feature tile: wavefronts 0 and 1 take one 32-row batch tile each while
+  // output layer: few features.  One feature tile: the first NBT wavefronts take one 32-row batch tile each while
   // the others run late().  More feature tiles: split them over the wavefronts like the hidden layers.
   if constexpr (!WIDE_OUT && KSPLIT > 1) {
     static_assert(KSPLIT == 1 || (RAW_OUT && NKB2 > 0 && NKB2 % (KSPLIT > 0 ? KSPLIT : 1) == 0), "k split of the output layer");
-    if (w < 2 * KSPLIT) {
-      const int bt = w & 1, part = w >> 1;
+    if (w < NBT * KSPLIT) {
+      const int bt = w % NBT, part = w / NBT;
       f32x16 acc[1][1];
       zero_acc<1, 1>(acc);
       mma_out_lds<BF16, NKB2 / KSPLIT>(acc[0][0], ldsW3, ldsH, hpitch, net.nkb[2], bt, lane, part * (NKB2 / KSPLIT));
@@ -584,7 +586,7 @@ __device__ inline void mlp_tile(const Net &net, u32x4 (&ring)[ring_depth(CTH)][C
     }
     late();
   } else if constexpr (!WIDE_OUT) {
-    if (w < 2) {
+    if (w < NBT) {
       f32x16 acc[1][1];
       zero_acc<1, 1>(acc);
       mma_out_lds<BF16, NKB2>(acc[0][0], ldsW3, ldsH, hpitch, net.nkb[2], w, lane);  // nkb[2] == nkb[1]
@@ -597,11 +599,11 @@ __device__ inline void mlp_tile(const Net &net, u32x4 (&ring)[ring_depth(CTH)][C
     const int co0 = w * CTO;
     if (co0 < net.nct[2]) {
       u32x4 r4[2][CTO];
-      f32x16 acc[CTO][2];
-      zero_acc<CTO, 2>(acc);
+      f32x16 acc[CTO][NBT];
+      zero_acc<CTO, NBT>(acc);
       prime<CTO, 2>(r4, net.W[2], net.nkb[2], net.nct[2], co0, lane);
-      mma_layer<BF16, CTO, 2, 2>(acc, r4, ldsH, hpitch, net.nkb[2], net.W[2], net.nct[2], co0, 0, lane);
-      epilogue_out<CTO, 2, RAW_OUT>(acc, lb3, net.out_dim, net.out_tanh, net.nct[2], co0, 0, lane, sink);
+      mma_layer<BF16, CTO, NBT, 2>(acc, r4, ldsH, hpitch, net.nkb[2], net.W[2], net.nct[2], co0, 0, lane);
+      epilogue_out<CTO, NBT, RAW_OUT>(acc, lb3, net.out_dim, net.out_tanh, net.nct[2], co0, 0, lane, sink);
     }
   }
 }

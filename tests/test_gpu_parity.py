@@ -387,11 +387,14 @@ def _run(w, H, T, schedule, n_market=None, forced_mu=None, calls=1):
     return d, ro, ocfg, outs, state
 
 
-@pytest.mark.parametrize("hidden,N,agents,H,n_market,D,K", [(512, 128, 1, 10, None, 30, 8), (256, 192, 1, 24, None, 30, 8),
-                                                             (512, 128, 2, 7, None, 30, 8), (512, 64, 1, 24, 1, 30, 8),
-                                                             (256, 128, 1, 9, None, 5, 4), (512, 64, 1, 24, None, 2, 2),
-                                                             (256, 64, 1, 24, None, 32, 1)])
-def test_fused_schedule_equals_stepwise_given_the_same_means(hidden, N, agents, H, n_market, D, K):
+@pytest.mark.parametrize("base,hidden,N,agents,H,n_market,D,K", [
+    ("large", 512, 128, 1, 10, None, 30, 8), ("large", 256, 192, 1, 24, None, 30, 8), ("large", 512, 128, 2, 7, None, 30, 8),
+    ("large", 512, 64, 1, 24, 1, 30, 8), ("large", 256, 128, 1, 9, None, 5, 4), ("large", 512, 64, 1, 24, None, 2, 2),
+    ("large", 256, 64, 1, 24, None, 32, 1),
+    # fp32 networks: 32-env tiles
+    ("dow30", 256, 96, 1, 10, None, 30, 8), ("dow30", 256, 128, 2, 7, None, 30, 8), ("dow30", 256, 32, 1, 24, 1, 30, 8),
+    ("dow30", 256, 160, 1, 9, None, 5, 4)])
+def test_fused_schedule_equals_stepwise_given_the_same_means(base, hidden, N, agents, H, n_market, D, K):
     """(Also at observation widths far below the 301 of the named workloads, where the policy-mean planes of the
     persistent kernel are larger than its input tile.)
     The persistent kernel feeds its actor the observation columns in another order than the per-step
@@ -399,7 +402,7 @@ def test_fused_schedule_equals_stepwise_given_the_same_means(hidden, N, agents, 
     of the means must agree bit for bit: the per-step schedule, forced onto the means the persistent kernel
     produced, has to reproduce its whole record and final state."""
     T = 24
-    w = inputs.WORKLOADS["large"].replace(n_envs=N, n_agents=agents, hidden=hidden, steps=T, n_stocks=D, n_ind=K)
+    w = inputs.WORKLOADS[base].replace(n_envs=N, n_agents=agents, hidden=hidden, steps=T, n_stocks=D, n_ind=K)
     _, ro_f, _, (b,), sb = _run(w, H, T, FUSED, n_market)
     mu_f = parity.to_np(b["mu"])
     _, ro_s, _, (a,), sa = _run(w, H, T, pr.PR_SCHED_STEPWISE, n_market, forced_mu=mu_f)
@@ -415,7 +418,7 @@ def test_fused_schedule_equals_stepwise_given_the_same_means(hidden, N, agents, 
     val_s = ro_s.mlp_forward(pr.PR_NET_CRITIC, b["obs"].reshape((T + 1) * N, S)).reshape(T + 1, N)
     torch.cuda.synchronize()
     err = (mu_s - b["mu"]).abs().amax(dim=-1) / mu_s.abs().amax(dim=-1).clamp_min(1e-30)
-    assert float(err.max()) <= parity.TOL_BF16
+    assert float(err.max()) <= (parity.TOL_BF16 if w.mlp_dtype else 2.0 * parity.TOL_NORM_F32)
     assert torch.equal(val_s, b["value"].reshape(T + 1, N))
 
 
@@ -471,6 +474,26 @@ def test_purchase_guard_fires_and_matches_checker(schedule):
     gst = ro.get_state()
     torch.cuda.synchronize()
     assert np.array_equal(parity.to_np(gst["cash"]), ost.cash) and float(gst["cash"].min()) >= 0.0
+
+
+def test_fused_fp32_forced_env_stage_and_stagewise_against_checker():
+    """fp32 networks run the persistent schedule on 32-env tiles: the environment stage against the checker with
+    resets inside the rollout, then a free-running rollout checked stage by stage."""
+    T, H = 48, 20
+    w = inputs.WORKLOADS["dow30"].replace(n_envs=96, steps=T, cash0=20000.0)
+    rng = np.random.default_rng(33)
+    mu = rng.uniform(-1, 1, (T, w.n_envs, w.n_stocks)).astype(np.float32)
+    d, ro, ocfg, (out,), st = _run(w, H, T, FUSED, forced_mu=mu)
+    chk, ost = parity.check_env_record(w, ocfg, _rec(out), d["price"], d["ind"], d["noise"], mu)
+    assert np.array_equal(parity.to_np(st["cash"]), ost.cash) and np.array_equal(parity.to_np(st["holdings"]), ost.h)
+    assert np.array_equal(parity.to_np(st["cursor"]), ost.tau) and np.array_equal(parity.to_np(st["ep_count"]), ost.ep_cnt)
+    w2 = inputs.WORKLOADS["dow30"].replace(n_envs=64, steps=T)
+    d, ro, ocfg, outs, st = _run(w2, 12, T, FUSED, calls=2)
+    ra, rb = _rec(outs[0]), _rec(outs[1])
+    rec = {k: np.concatenate([ra[k], rb[k]]) for k in ("act_raw", "reward", "done", "shares", "logp", "mu")}
+    rec["obs"] = np.concatenate([ra["obs"], rb["obs"][1:]])
+    rec["value"] = np.concatenate([ra["value"], rb["value"][1:]])
+    _stagewise(w2, d, ro, ocfg, T, rec)
 
 
 def test_fused_rollout_stagewise_against_checker_and_carry_across_calls():
@@ -553,7 +576,8 @@ def test_deterministic_evaluation_rollout_and_its_metrics():
 
 @pytest.mark.parametrize("name,schedule,n_sample", [("large", FUSED, 256), ("dow30", pr.PR_SCHED_STEPWISE, 64),
                                                      ("wide", pr.PR_SCHED_STEPWISE, 24),
-                                                     ("tournament", pr.PR_SCHED_STEPWISE, 96)])
+                                                     ("tournament", pr.PR_SCHED_STEPWISE, 96), ("dow30", FUSED, 64),
+                                                     ("tournament", FUSED, 96)])
 def test_full_size_workloads(name, schedule, n_sample):
     """Every named workload at its real size through rollout_step_T (with values) and compute_gae -- `large` in
     the configuration bench.py times (persistent rollout kernel, 128-row value kernel over the whole buffer) --
