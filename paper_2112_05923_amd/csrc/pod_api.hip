@@ -22,6 +22,7 @@ struct pr_handle {
   float *b_packed[2][3];
   float *mu_scratch;      // [N, D]
   int32_t *start;         // [N] episode start rows (zeros unless a replay table is set)
+  float *split;           // activations between the launches of the layer-per-launch actor (small batches), or null
   int32_t S;
 };
 
@@ -51,7 +52,7 @@ bool is_pow2_float(float x) {
 struct Layout {
   size_t w[2][3], b[2][3];
   size_t w1_fused;
-  size_t cash, tau, h, ep_ret, ep_sum, ep_sqsum, ep_cnt, mu, start;
+  size_t cash, tau, h, ep_ret, ep_sum, ep_sqsum, ep_cnt, mu, start, split;
   size_t total;
 };
 
@@ -110,6 +111,7 @@ Layout make_layout(const pr_config &c) {
   L.ep_cnt = take(N * 4);
   L.mu = take(N * D * 4);
   L.start = take(N * 4);
+  L.split = take((size_t)split_scratch_rows(c.n_envs, Hd) * Hd * 4 * 2);
   L.total = off;
   return L;
 }
@@ -132,6 +134,9 @@ void fill_net(PackedNet &pn, const pr_handle *h, int net) {
   }
   pn.bf16 = bf;
   pn.out_tanh = net == 0 ? 1 : 0;
+  pn.split_rows = split_scratch_rows(c.n_envs, Hd);
+  pn.split_h[0] = pn.split_rows ? h->split : nullptr;
+  pn.split_h[1] = pn.split_rows ? h->split + (size_t)pn.split_rows * Hd : nullptr;
 }
 
 bool weights_ok(const pr_weights *w) { return w && w->W1 && w->b1 && w->W2 && w->b2 && w->W3 && w->b3; }
@@ -224,6 +229,7 @@ int rollout_init(const pr_config *cfg, const pr_market *market, const pr_weights
   h->st.ep_cnt = reinterpret_cast<int32_t *>(ws + L.ep_cnt);
   h->mu_scratch = reinterpret_cast<float *>(ws + L.mu);
   h->start = reinterpret_cast<int32_t *>(ws + L.start);
+  h->split = reinterpret_cast<float *>(ws + L.split);
   h->st.start = h->start;
 
   EnvDims &d = h->dims;

@@ -122,7 +122,12 @@ struct PackedNet {
   int32_t nkb[3], nct[3];         // k-blocks and column tiles per layer
   int32_t bf16;                   // operand type
   int32_t out_tanh;               // tanh on the last layer
+  float *split_h[2];              // scratch for the layer-per-launch path: two [split_rows, hidden] fp32 buffers, or null
+  int64_t split_rows;
 };
+// Rows up to which the layer-per-launch path is worth its scratch (fewer 64-row tiles than half the compute units
+// of the largest part), 0 if never for this batch size.
+int64_t split_scratch_rows(int64_t n_envs, int hidden);
 
 size_t packed_weight_bytes(int in_dim, int out_dim, int bf16);
 int padded_out(int out_dim);

@@ -293,6 +293,63 @@ __global__ __launch_bounds__(kThreads) void mlp3_kernel(MlpArgs a) {
 }
 
 
+// ------------------------------------------------ one layer per launch, for few rows
+// A step of a small batch (a few thousand envs) has fewer 64-row tiles than the chip has compute units, and a
+// kernel that carries a row tile through all three layers leaves the rest idle.  Here a launch computes ONE
+// layer, tiled over rows x output features: workgroup (x, y) owns rows [32 x, 32 x + 32) and the four feature
+// tiles [4 y, 4 y + 4), one per wavefront, so rows / 32 x features / 128 workgroups run (512 for 2048 rows and
+// 1024 hidden units); the input rows are staged 16 k-blocks at a time, because with so little arithmetic per
+// workgroup the time goes to the memory round trips, one per staged chunk.  Activations travel between the launches as fp32 rows in global memory (they stay in L2)
+// and are rounded to the operand type when they are staged, exactly where the whole-network kernels round them.
+constexpr int kSplitPD = 16;  // k-blocks per staged chunk of the layer-per-launch kernel
+struct LayerArgs {
+  const float *X;      // [rows, ldx]
+  int64_t ldx, rows;
+  int64_t row_offset;  // index of X's first row in the caller's buffer (selects the agent)
+  float *Y;            // [rows, ldy]
+  int64_t ldy;
+  const void *W;       // packed weights of the layer, agent-major
+  const float *b;      // padded biases, agent-major
+  int64_t w_stride;    // bytes between agents
+  int32_t b_stride;    // floats between agents
+  int32_t in_dim, out_dim, nkb, nct;
+  int32_t act;         // 0: linear, 1: tanh of a hidden layer, 2: tanh of an output layer (full accuracy)
+  int32_t N, envs_per_agent;
+  int32_t xpitch;
+};
+
+template <bool BF16, int RT, int PD>
+__global__ __launch_bounds__(kThreads) void dense_layer_kernel(LayerArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  constexpr int BM = 32 * RT;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int64_t row0 = (int64_t)blockIdx.x * BM;
+  const int nrows = (int)min((int64_t)BM, a.rows - row0);
+  const int agent = (int)(((row0 + a.row_offset) % a.N) / a.envs_per_agent);
+  const u32x4 *Wp = reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(a.W) + (size_t)agent * a.w_stride);
+  const float *bias = a.b + (size_t)agent * a.b_stride;
+  const int ct0 = blockIdx.y * kWaves + w;
+  const bool active = ct0 < a.nct;
+  f32x16 acc[RT][1];
+  zero_acc<RT, 1>(acc);
+  layer_from_global<BF16, RT, 1, PD>(acc, lds, a.xpitch, a.X, a.ldx, row0, nrows, a.in_dim, a.nkb, Wp, ct0, a.nct, active,
+                                     tid);
+  if (!active) return;
+  const int g = lane >> 5, col = ct0 * 32 + (lane & 31);
+  const float bv = bias[col];
+#pragma unroll
+  for (int r = 0; r < RT; ++r)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int row = r * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+      const float z = acc[r][0][i] + bv;
+      float y = z;
+      if (a.act == 1) y = BF16 ? tile::tanh_from_scaled(z * tile::kTwoLog2e) : tanh_accurate(z);
+      if (a.act == 2) y = tanh_accurate(z);
+      if (row < nrows && col < a.out_dim) a.Y[(row0 + row) * a.ldy + col] = y;
+    }
+}
+
 // ------------------------------------------------ persistent whole-tile kernel
 // Used when the rows of X are dense (ldx == S) and a whole 64 x S tile fits in
 // LDS next to the hidden tile.  Each workgroup walks tiles blockIdx.x,
@@ -1031,6 +1088,10 @@ bool pick_shape(int Hd, int O, int bf16, Shape *s) {
 
 }  // namespace
 
+int64_t split_scratch_rows(int64_t n_envs, int hidden) {
+  return (hidden >= 128 && n_envs >= 64 && (n_envs + 63) / 64 * 2 <= 256) ? n_envs : 0;
+}
+
 bool mlp_supported(int S, int Hd, int O, int bf16) {
   Shape s;
   return S >= 1 && pick_shape(Hd, O, bf16, &s);
@@ -1233,8 +1294,53 @@ static bool try_launch_wide(hipStream_t st, const PackedNet &net, int64_t rows, 
   return true;
 }
 
+// Few rows: one launch per layer (see dense_layer_kernel).  Needs the scratch of the packed network (two fp32
+// activation buffers of split_rows x hidden).
+static bool try_launch_split(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx, float *Y,
+                             int32_t N, int32_t envs_per_agent, hipError_t *err) {
+  const int Hd = net.out_dim[0];
+  if (!net.split_h[0] || !net.split_h[1] || rows > net.split_rows || rows < 64 || Hd < 128) return false;
+  if ((rows + 63) / 64 * 2 > compute_units()) return false;  // enough tiles for the whole-network kernels
+  if (envs_per_agent < N && envs_per_agent % 32 != 0) return false;  // a row tile never spans two agents
+  const int64_t tiles = (rows + 31) / 32;
+  const int esz = net.bf16 ? 2 : 4, KB = kblock(net.bf16);
+  const float *in = X;
+  int64_t ld_in = ldx;
+  for (int l = 0; l < 3; ++l) {
+    LayerArgs a;
+    a.X = in, a.ldx = ld_in, a.rows = rows, a.row_offset = 0;
+    a.Y = l == 2 ? Y : net.split_h[l];
+    a.ldy = l == 2 ? net.out_dim[2] : Hd;
+    a.W = net.W[l], a.b = net.b[l], a.w_stride = net.w_stride[l], a.b_stride = net.b_stride[l];
+    a.in_dim = net.in_dim[l], a.out_dim = net.out_dim[l], a.nkb = net.nkb[l], a.nct = net.nct[l];
+    a.act = l < 2 ? 1 : (net.out_tanh ? 2 : 0);
+    a.N = N, a.envs_per_agent = envs_per_agent;
+    a.xpitch = kSplitPD * KB * esz + 16;
+    const size_t lds = 2 * (size_t)32 * a.xpitch;
+    const dim3 grid((unsigned)tiles, (unsigned)((net.nct[l] + kWaves - 1) / kWaves));
+    if (net.bf16) {
+      *err = allow_full_lds<dense_layer_kernel<true, 1, kSplitPD>>();
+      if (*err != hipSuccess) return true;
+      hipLaunchKernelGGL((dense_layer_kernel<true, 1, kSplitPD>), grid, dim3(kThreads), lds, st, a);
+    } else {
+      *err = allow_full_lds<dense_layer_kernel<false, 1, kSplitPD>>();
+      if (*err != hipSuccess) return true;
+      hipLaunchKernelGGL((dense_layer_kernel<false, 1, kSplitPD>), grid, dim3(kThreads), lds, st, a);
+    }
+    *err = hipGetLastError();
+    if (*err != hipSuccess) return true;
+    in = net.split_h[l < 2 ? l : 0];
+    ld_in = Hd;
+  }
+  return true;
+}
+
 hipError_t launch_mlp(hipStream_t st, const PackedNet &net, int64_t rows, const float *X, int64_t ldx, float *Y,
                       int32_t N, int32_t envs_per_agent) {
+  {
+    hipError_t terr = hipSuccess;
+    if (try_launch_split(st, net, rows, X, ldx, Y, N, envs_per_agent, &terr)) return terr;
+  }
   Shape s;
   if (!pick_shape(net.out_dim[0], net.out_dim[2], net.bf16, &s)) return hipErrorInvalidValue;
   constexpr int BM = 64;

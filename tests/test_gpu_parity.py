@@ -219,7 +219,7 @@ def _stagewise(w, d, ro, ocfg, T, rec, state0=None):
     rng = np.random.default_rng(99)
     for g in range(w.n_agents):
         envs = np.arange(g * per_agent, (g + 1) * per_agent)
-        envs = envs[rng.permutation(envs.size)[:8]]
+        envs = np.union1d(envs[rng.permutation(envs.size)[:7]], envs[-1:])   # (the last env: the ragged row tile)
         ts = rng.permutation(T)[:12]
         obs = rec["obs"][ts][:, envs].reshape(-1, S)
         mu = rec["mu"][ts][:, envs].reshape(-1, w.n_stocks)
@@ -230,10 +230,14 @@ def _stagewise(w, d, ro, ocfg, T, rec, state0=None):
     return chk, st
 
 
-@pytest.mark.parametrize("name,N,T,H", [("tiny", 16, 64, 64), ("tiny", 16, 64, 20), ("dow30", 192, 24, 24),
-                                        ("large", 128, 16, 16)])
-def test_rollout_stagewise(name, N, T, H):
-    w = inputs.WORKLOADS[name].replace(n_envs=N, steps=T)
+@pytest.mark.parametrize("name,N,T,H,agents", [("tiny", 16, 64, 64, 1), ("tiny", 16, 64, 20, 1),
+                                               ("dow30", 192, 24, 24, 1), ("large", 128, 16, 16, 1),
+                                               # batches between 64 and 8192 rows take the actor kernel that runs one
+                                               # layer per launch: a ragged last row tile, and one agent per 64 rows
+                                               ("dow30", 200, 12, 12, 1), ("large", 74, 8, 8, 1),
+                                               ("large", 192, 8, 8, 3), ("wide", 96, 4, 4, 1)])
+def test_rollout_stagewise(name, N, T, H, agents):
+    w = inputs.WORKLOADS[name].replace(n_envs=N, steps=T, n_agents=agents)
     d, ro, ocfg = _make(w, horizon=H)
     out = ro.alloc_buffers(T, value=True, logp=True, mu=True, shares=True)
     ro.step_T(T, torch.from_numpy(d["noise"]).to(DEV), out)
