@@ -37,11 +37,15 @@ constexpr int NW = 8;
 constexpr int NT = NW * 64;
 // envs per workgroup: 64 (bf16 networks) or 32 (fp32 networks, whose 64-row tiles do not fit in LDS); a template
 // parameter E of the kernel
-constexpr int PAIRS_MAX = 4;     // (env, stock) pairs per lane: D <= 32
 constexpr int DMAX = 32;         // stock slots per env row in LDS; slots D..31 hold neutral values (k = 0, h = 0)
 constexpr int kDp = DMAX + 1;    // odd row pitch: the per-env serial walks of the ledger hit distinct banks
-constexpr int IND_MAX = 9;       // 16-byte indicator groups per lane (lanes 64..511): D*K <= 252, D*K % 4 == 0
-constexpr int NT_IND = NT - 64;  // lanes that carry indicator values
+// Lane maps of the parallel env work (no index divisions anywhere in the step loop):
+//  * (env, stock) slots: a half-wavefront per env row, lane % 32 = stock slot; wavefront w owns envs
+//    [w E/8, (w + 1) E/8), two per pass, E/16 passes;
+//  * market rows (prices and indicators of the next observation): one env row per instruction, wavefronts 1..7
+//    take rows w - 1, w + 6, ...; lane l carries price l and the 16-byte indicator group l (D K <= 252, D K % 4 == 0).
+//    The ledger wavefront carries none: a load of its own in flight would sit in front of whatever its serial
+//    pass waits for next (a wavefront's memory operations complete in order).
 
 constexpr int MUP = 33;         // row pitch of a policy-mean plane (lanes of one store differ in the row: 32 would hit one bank)
 // Planes the output layer's k range is split into (one per group of wavefronts), by the compile-time k-block count
@@ -83,7 +87,6 @@ struct FusedArgs {
   float *logp;             // opt [T, N]
   float *mu_out;           // opt [T, N, D]
   int32_t *shares;         // opt [T, N, D]
-  uint32_t d_magic, g_magic;  // ceil(2^32 / D), ceil(2^32 / (D K / 4))
 };
 
 // Ledger input of one (env, stock) slot, written by the parallel lanes.
@@ -92,12 +95,6 @@ struct __attribute__((aligned(16))) Slot {
   float val;   // sale proceeds (k < 0) or unit cost of a purchase (k > 0)
   double rcp;  // 1 / unit cost in binary64 (k > 0), else 0
 };
-
-// idx / div for the small indices used here, with magic = ceil(2^32 / div) (div >= 2; the magic of 1 does not fit
-// in 32 bits, so that divisor is handled apart -- uniformly, div is a launch constant).
-__device__ inline int div_small(int idx, int div, uint32_t magic) {
-  return div == 1 ? idx : (int)__umulhi((unsigned)idx, magic);
-}
 
 __device__ inline Row row_of(const EnvDims &d, int32_t tau, int32_t start, int32_t n) {
   const int32_t m = d.M == 1 ? 0 : n;
@@ -114,6 +111,9 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   static_assert(E == 64 || E == 32, "one or two 32-row batch tiles");
   constexpr int NBT = E / 32;
   using O = tile::Op<BF16>;
+  // the named bf16 shape runs its actor as two wavefront groups half a layer out of step (see the step loop)
+  constexpr bool SPLIT = ACTOR && BF16 && E == 64 && CTH == 2 && NKB2 == 32 && NKB1 >= 8;
+  constexpr int PDR = SPLIT ? 8 : ring_depth(CTH);  // weight blocks in flight per feature tile
   extern __shared__ __align__(16) unsigned char lds[];
   const EnvDims &d = a.d;
   const int D = d.D, DK = D * d.K, S = d.S;
@@ -152,6 +152,22 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   if (ACTOR) {
     net = net_of(a.actor, (n0 % d.N) / a.envs_per_agent);
     stage_net<NT>(net, ldsBias, ldsW3, tid);
+    if constexpr (SPLIT) {
+      // Output-layer blocks in the k order of an accumulator half: the lane of half g takes, from the standard
+      // block's two lanes of its output feature, the four k of each that an accumulator lane of half g holds.
+      __syncthreads();
+      u32x4 v[NKB2 * 64 / NT];
+#pragma unroll
+      for (int j = 0; j < NKB2 * 64 / NT; ++j) {
+        const int idx = tid + NT * j, blk = idx >> 6, l = idx & 63, o = l & 31, g = l >> 5;
+        const uint32_t *lo = reinterpret_cast<const uint32_t *>(ldsW3 + blk * 64 + o);
+        const uint32_t *hi = reinterpret_cast<const uint32_t *>(ldsW3 + blk * 64 + 32 + o);
+        v[j] = u32x4{lo[2 * g], lo[2 * g + 1], hi[2 * g], hi[2 * g + 1]};
+      }
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < NKB2 * 64 / NT; ++j) ldsW3[tid + NT * j] = v[j];
+    }
     // padded k columns of the input tile must read as zero
     for (int i = tid; i < E * a.L.xpitch / 4; i += NT) reinterpret_cast<uint32_t *>(ldsX)[i] = 0u;
   }
@@ -187,42 +203,40 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     }
   __syncthreads();
 
+  constexpr int PAIRS = E / 16;                   // (env, stock) slots per lane
+  constexpr int MROWS = (E + NW - 2) / (NW - 1);  // market rows per wavefront 1..7
+  // (Each helper starts from an opaque copy of the thread index: what it derives from it is loop invariant, and
+  // the compiler would otherwise keep it in registers across the matrix-core code instead of recomputing a few
+  // integer operations.)
   // Writes the market part of an observation (prices, indicators at row_obs) to HBM row `obs_row` and into the
-  // LDS input tile, and refreshes the execution prices.  `pv_obs` / `ind_v`: values already in registers.
-  // (Each helper starts from an opaque copy of the thread index: the (env, column) decompositions and the
-  // addresses derived from them are loop invariant, and the compiler would otherwise keep a hundred of them
-  // in registers across the matrix-core code instead of recomputing a few integer operations.)
-  auto emit_market = [&](float *obs_row, const float (&p_obs)[PAIRS_MAX], const f32x4 (&ind_v)[IND_MAX]) {
-    int tid = threadIdx.x;
-    asm volatile("" : "+v"(tid));
+  // LDS input tile, and refreshes the execution prices.  `p_obs` / `ind_v`: values already in registers.
+  auto emit_market = [&](float *obs_row, const float (&p_obs)[MROWS], const f32x4 (&ind_v)[MROWS]) {
+    int l = threadIdx.x & 63;
+    asm volatile("" : "+v"(l));
+    if (wave >= 1) {
 #pragma unroll
-    for (int i = 0; i < PAIRS_MAX; ++i) {
-      const int idx = tid + NT * i;
-      if (idx < E * D) {
-        const int e = div_small(idx, D, a.d_magic), dd = idx - e * D;
-        const float v = p_obs[i];
-        s_p[e * Dp + dd] = v;
-        const float sv = v * d.s_price;
-        __builtin_nontemporal_store(sv, &obs_row[(size_t)(n0 + e) * S + 1 + dd]);
-        if (ACTOR) O::store1(ldsX + (size_t)e * a.L.xpitch + (DK + 1 + dd) * O::ESZ, sv);
-      }
-    }
-    if (tid >= 64) {
-      const int G = DK >> 2;
-#pragma unroll
-      for (int i = 0; i < IND_MAX; ++i) {
-        const int idx = (tid - 64) + NT_IND * i;
-        if (idx < E * G) {
-          const int e = div_small(idx, G, a.g_magic), j = 4 * (idx - e * G);
-          f32x4 sv = ind_v[i];
-          sv[0] *= d.s_ind;
-          sv[1] *= d.s_ind;
-          sv[2] *= d.s_ind;
-          sv[3] *= d.s_ind;
-          // observation rows are 4-byte aligned only; a 16-byte store needs no more than that
-          __builtin_nontemporal_store(sv, reinterpret_cast<f32x4 *>(obs_row + (size_t)(n0 + e) * S + 1 + 2 * D + j));
-          // (indicators lead the LDS tile, so a group of four is one aligned store)
-          if (ACTOR) O::store4(ldsX + (size_t)e * a.L.xpitch + j * O::ESZ, sv[0], sv[1], sv[2], sv[3]);
+      for (int i = 0; i < MROWS; ++i) {
+        const int e = (wave - 1) + (NW - 1) * i;
+        if (e < E) {
+          float *orow = obs_row + (size_t)(n0 + e) * S;
+          if (l < D) {
+            const float v = p_obs[i];
+            s_p[e * Dp + l] = v;
+            const float sv = v * d.s_price;
+            __builtin_nontemporal_store(sv, &orow[1 + l]);
+            if (ACTOR) O::store1(ldsX + (size_t)e * a.L.xpitch + (DK + 1 + l) * O::ESZ, sv);
+          }
+          if (4 * l < DK) {
+            f32x4 sv = ind_v[i];
+            sv[0] *= d.s_ind;
+            sv[1] *= d.s_ind;
+            sv[2] *= d.s_ind;
+            sv[3] *= d.s_ind;
+            // observation rows are 4-byte aligned only; a 16-byte store needs no more than that
+            __builtin_nontemporal_store(sv, reinterpret_cast<f32x4 *>(orow + 1 + 2 * D + 4 * l));
+            // (indicators lead the LDS tile, so a group of four is one aligned store)
+            if (ACTOR) O::store4(ldsX + (size_t)e * a.L.xpitch + 4 * l * O::ESZ, sv[0], sv[1], sv[2], sv[3]);
+          }
         }
       }
     }
@@ -244,16 +258,16 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         for (int c = S; c < kp; ++c) O::store1(ldsX + (size_t)tid * a.L.xpitch + c * O::ESZ, 0.0f);
       }
     }
+    const int dd = tid & 31, e0 = (tid >> 6) * (E / NW) + ((tid >> 5) & 1);
+    if (dd < D) {
 #pragma unroll
-    for (int i = 0; i < PAIRS_MAX; ++i) {
-      const int idx = tid + NT * i;
-      if (idx < E * D) {
-        const int e = div_small(idx, D, a.d_magic), dd = idx - e * D;
+      for (int i = 0; i < PAIRS; ++i) {
+        const int e = e0 + 2 * i;
         int32_t h = s_h[e * Dp + dd];
         if (AFTER_STEP) {
           // sales were booked when they were sized; purchases (q > 0) are booked here
           const int32_t q = s_q[e * Dp + dd];
-          if (a.shares) a.shares[g0 + idx] = q;
+          if (a.shares) a.shares[g0 + (size_t)e * D + dd] = q;
           h = s_done[e] ? 0 : h + max(q, 0);
           s_h[e * Dp + dd] = h;
         }
@@ -263,44 +277,50 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       }
     }
   };
-  // Loads of the market rows named in s_row, into registers (issued early, consumed after the actor).
-  float r_eps[PAIRS_MAX], r_mu[PAIRS_MAX], r_pv[PAIRS_MAX], r_po[PAIRS_MAX];
-  f32x4 r_ind[IND_MAX];
-  auto fetch_market = [&]() {
+  // Loads into registers: the step's noise and valuation prices are requested at the start of the step and
+  // consumed after the actor; the market row of the next observation is requested at the start of the ledger
+  // phase and written out at its end (it does not depend on the step's outcome, and this way its registers are
+  // not live while the matrix steps need them for weight blocks in flight).
+  float r_eps[PAIRS], r_mu[PAIRS], r_pv[PAIRS], r_po[MROWS];
+  f32x4 r_ind[MROWS];
+  // (s_row is double-buffered by the step's parity: the ledger lanes write the rows of step t + 1 while other
+  // wavefronts may still read those of step t)
+  auto fetch_valuation = [&](const Row *rows) {
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
+    const int dd = min(tid & 31, D - 1), e0 = (tid >> 6) * (E / NW) + ((tid >> 5) & 1);
 #pragma unroll
-    for (int i = 0; i < PAIRS_MAX; ++i) {
-      const int idx = min(tid + NT * i, E * D - 1);
-      const int e = div_small(idx, D, a.d_magic), dd = idx - e * D;
-      const Row r = s_row[e];
-      r_pv[i] = __builtin_nontemporal_load(&a.price[(size_t)r.row_val * D + dd]);
-      r_po[i] = __builtin_nontemporal_load(&a.price[(size_t)r.row_obs * D + dd]);
-    }
-    if (tid >= 64) {
-      const int G = DK >> 2;
+    for (int i = 0; i < PAIRS; ++i)
+      r_pv[i] = __builtin_nontemporal_load(&a.price[(size_t)rows[e0 + 2 * i].row_val * D + dd]);
+  };
+  auto fetch_market = [&](const Row *rows) {
+    int l = threadIdx.x & 63;
+    asm volatile("" : "+v"(l));
+    if (wave >= 1) {
+      const int lp = min(l, D - 1), li = min(l, (DK >> 2) - 1);
 #pragma unroll
-      for (int i = 0; i < IND_MAX; ++i) {
-        const int idx = min((tid - 64) + NT_IND * i, E * G - 1);
-        const int e = div_small(idx, G, a.g_magic), j = 4 * (idx - e * G);
-        r_ind[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.ind + (size_t)s_row[e].row_obs * DK + j));
+      for (int i = 0; i < MROWS; ++i) {
+        const int e = min((wave - 1) + (NW - 1) * i, E - 1);
+        const size_t ro = (size_t)__builtin_amdgcn_readfirstlane(rows[e].row_obs);
+        r_po[i] = __builtin_nontemporal_load(&a.price[ro * D + lp]);
+        r_ind[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.ind + ro * DK) + li);
       }
     }
   };
   auto fetch_step_inputs = [&](int t) {
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
+    const int dd = min(tid & 31, D - 1), e0 = (tid >> 6) * (E / NW) + ((tid >> 5) & 1);
     const size_t g0 = ((size_t)t * N + n0) * D;
 #pragma unroll
-    for (int i = 0; i < PAIRS_MAX; ++i) {
-      const int idx = min(tid + NT * i, E * D - 1);
-      r_eps[i] = __builtin_nontemporal_load(&a.noise[g0 + idx]);
-      if (!ACTOR) r_mu[i] = a.mu_forced[g0 + idx];
+    for (int i = 0; i < PAIRS; ++i) {
+      r_eps[i] = __builtin_nontemporal_load(&a.noise[g0 + (size_t)(e0 + 2 * i) * D + dd]);
+      if (!ACTOR) r_mu[i] = a.mu_forced[g0 + (size_t)(e0 + 2 * i) * D + dd];
     }
   };
 
   {
-    fetch_market();
+    fetch_market(s_row);
     emit_market(a.obs, r_po, r_ind);
     emit_portfolio(a.obs, std::false_type{}, 0);
   }
@@ -311,44 +331,131 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     double v = (double)cash;
     for (int dd = 0; dd < D; ++dd) v += (double)s_h[e * Dp + dd] * (double)s_p[e * Dp + dd];
     asset = v;
-    s_row[e] = row_of(d, tau, start, n0 + e);
+    s_row[e] = row_of(d, tau, start, n0 + e);  // (step 0 reads buffer 0 again: the barrier at the loop top orders it)
   }
 
   // Weight ring of the actor.  Layer 1's first blocks are requested a phase early (here, and after each step's
   // ledger) so that they are in flight while the observation is completed.
-  u32x4 ring[ring_depth(CTH)][CTH];
+  u32x4 ring[PDR][CTH];
   const float *lb3 = ldsBias + (ACTOR ? (a.actor.nct[0] + a.actor.nct[1]) * 32 : 0);
-  if (ACTOR) prime<CTH, ring_depth(CTH)>(ring, net.W[0], net.nkb[0], net.nct[0], wave * CTH, lane);
+  if (ACTOR) prime<CTH, PDR>(ring, net.W[0], net.nkb[0], net.nct[0], wave * CTH, lane);
 
   for (int t = 0; t < a.T; ++t) {
     __syncthreads();  // observation t complete in LDS; ledger rows of step t visible
     float *obs_next = a.obs + (size_t)(t + 1) * N * S;
     const size_t g0 = ((size_t)t * N + n0) * D;
+    const Row *rows_t = s_row + (t & 1) * E;
+    Row *rows_next = s_row + ((t + 1) & 1) * E;
 
-    if (ACTOR) {
-      mlp_tile<BF16, NW, CTH, false, NKB1, NKB2, true, true, KS, NBT>(
-          net, ring, ldsX, a.L.xpitch, ldsH, a.L.hpitch, ldsBias, ldsW3, tid,
-          [&]() {
-            fetch_step_inputs(t);
-            fetch_market();
-          },
-          [&]() {},
-          [&](int b, int f, float z, int part = 0) { s_mu[part * (E * MUP) + b * MUP + f] = z; });  // finished below
-    } else {
-      fetch_step_inputs(t);
-      fetch_market();
-    }
-    __syncthreads();  // means in LDS; the hidden tile is free for the env scratch
-
-    // ---- everything that does not depend on the running cash, all lanes
-    int tid_p = threadIdx.x;
-    asm volatile("" : "+v"(tid_p));
+    if constexpr (SPLIT) {
+      // ---- the actor, two wavefront groups half a layer out of step
+      // Group A (wavefronts 0-3) owns hidden features 0-255, group B (4-7) features 256-511.  Both run the same
+      // five steps with a barrier after each -- (a) layer 1, (b) its tanh -> own half of the hidden tile,
+      // (c) layer 2 over the own half, (d) layer 2 over the other group's half, (e) tanh of layer 2 and the output
+      // layer's partial sums over the own features -- but B runs them one barrier later than A, so the tanh steps
+      // of one group fall under matrix steps of the other on the same SIMDs.  The slot a group has no step in
+      // (B the first, A the last) is where its lanes request the step's market rows and noise.
+      // Step (e) feeds the output layer from registers: the eight values a lane holds of a feature tile's half
+      // are one k-block of the transposed product, in the k order the output weights were permuted to at set-up.
+      // The partial sums of a wavefront pair (w, w + 4) meet in plane w of the policy means.
+      constexpr int PDS = PDR, HALF = NKB2 / 2;
+      const bool grpB = wave >= NW / 2;
+      const int ct0 = wave * CTH;
+      const int own0 = grpB ? HALF : 0, oth0 = grpB ? 0 : HALF;
+      const float *lb1 = ldsBias, *lb2 = ldsBias + net.nct[0] * 32;
+      f32x16 acc[CTH][NBT];
+      int lane_s = lane;  // (opaque per step, or the addresses of all weight blocks are hoisted out of the step loop)
+      asm volatile("" : "+v"(lane_s));
+      if (grpB) {
+        fetch_step_inputs(t);
+        fetch_valuation(rows_t);
+        __syncthreads();
+      }
+      bias_acc<CTH, NBT>(acc, lb1, ct0, lane_s);
+      mma_range_static<true, CTH, NBT, PDS, NKB1, true, true>(acc, ring, ldsX, a.L.xpitch, net.W[0], net.nct[0], 0, net.W[1],
+                                                   net.nct[1], own0, ct0, 0, lane_s);
+      __syncthreads();
+      epilogue_hidden_biased<CTH, NBT>(acc, ldsH, a.L.hpitch, ct0, 0, lane_s);
+      __syncthreads();
+      bias_acc<CTH, NBT>(acc, lb2, ct0, lane_s);
+      mma_range_static<true, CTH, NBT, PDS, HALF, true, true>(acc, ring, ldsH + own0 * 32, a.L.hpitch, net.W[1], net.nct[1], own0,
+                                                   net.W[1], net.nct[1], oth0, ct0, 0, lane_s);
+      __syncthreads();
+      mma_range_static<true, CTH, NBT, PDS, HALF, false, true>(acc, ring, ldsH + oth0 * 32, a.L.hpitch, net.W[1], net.nct[1],
+                                                          oth0, net.W[1], net.nct[1], 0, ct0, 0, lane_s);
+      __syncthreads();
+      {
+        f32x16 o3[NBT];
 #pragma unroll
-    for (int i = 0; i < PAIRS_MAX; ++i) {
-      const int idx = tid_p + NT * i;
-      if (idx < E * D) {
-        const int e = div_small(idx, D, a.d_magic), dd = idx - e * D;
-        const int o = e * Dp + dd;
+        for (int b = 0; b < NBT; ++b)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o3[b][i] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < CTH; ++c) {
+          tanh_in_place<NBT>(acc[c]);
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk) {
+            const u32x4 wb = ldsW3[((ct0 + c) * 2 + kk) * 64 + lane_s];
+#pragma unroll
+            for (int b = 0; b < NBT; ++b) {
+              const bf16x8 v = {(__bf16)acc[c][b][8 * kk],     (__bf16)acc[c][b][8 * kk + 1], (__bf16)acc[c][b][8 * kk + 2],
+                                (__bf16)acc[c][b][8 * kk + 3], (__bf16)acc[c][b][8 * kk + 4], (__bf16)acc[c][b][8 * kk + 5],
+                                (__bf16)acc[c][b][8 * kk + 6], (__bf16)acc[c][b][8 * kk + 7]};
+              O::mma(wb, __builtin_bit_cast(u32x4, v), o3[b]);
+            }
+          }
+        }
+        float *plane = s_mu + (wave & 3) * (E * MUP) + (lane_s & 31) * MUP + 4 * (lane_s >> 5);
+        if (grpB) {
+          // (all reads in flight before the first sum: one LDS round trip, not one per value)
+          f32x16 old[NBT];
+#pragma unroll
+          for (int b = 0; b < NBT; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) old[b][i] = plane[b * 32 * MUP + 8 * (i >> 2) + (i & 3)];
+#pragma unroll
+          for (int b = 0; b < NBT; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o3[b][i] += old[b][i];
+        }
+#pragma unroll
+        for (int b = 0; b < NBT; ++b)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) plane[b * 32 * MUP + 8 * (i >> 2) + (i & 3)] = o3[b][i];
+      }
+      __syncthreads();
+      if (!grpB) {
+        fetch_step_inputs(t);
+        fetch_valuation(rows_t);
+        __syncthreads();
+      }
+      // (both groups have passed six barriers: the means are complete and the hidden tile is free)
+    } else {
+      if (ACTOR) {
+        mlp_tile<BF16, NW, CTH, false, NKB1, NKB2, true, true, KS, NBT>(
+            net, ring, ldsX, a.L.xpitch, ldsH, a.L.hpitch, ldsBias, ldsW3, tid,
+            [&]() {
+              fetch_step_inputs(t);
+              fetch_valuation(rows_t);
+            },
+            [&]() {},
+            [&](int b, int f, float z, int part = 0) { s_mu[part * (E * MUP) + b * MUP + f] = z; });  // finished below
+      } else {
+        fetch_step_inputs(t);
+        fetch_valuation(rows_t);
+      }
+      __syncthreads();  // means in LDS; the hidden tile is free for the env scratch
+    }
+
+    // ---- everything that does not depend on the running cash, all lanes (slots D..31 get neutral values)
+    {
+      int tid_p = threadIdx.x;
+      asm volatile("" : "+v"(tid_p));
+      const int dd = tid_p & 31, e0 = (tid_p >> 6) * (E / NW) + ((tid_p >> 5) & 1);
+      const bool live = dd < D;
+#pragma unroll
+      for (int i = 0; i < PAIRS; ++i) {
+        const int e = e0 + 2 * i, o = e * Dp + dd;
         float mu;
         if (ACTOR) {
           float z = s_mu[e * MUP + dd];
@@ -358,10 +465,12 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         } else {
           mu = r_mu[i];
         }
-        const float eps = r_eps[i];
-        const float a_raw = mu + d.sigma * eps;
-        __builtin_nontemporal_store(a_raw, &a.act_raw[g0 + idx]);
-        if (ACTOR && a.mu_out) a.mu_out[g0 + idx] = mu;
+        const float eps = live ? r_eps[i] : 0.0f;
+        const float a_raw = live ? mu + d.sigma * eps : 0.0f;
+        if (live) {
+          __builtin_nontemporal_store(a_raw, &a.act_raw[g0 + (size_t)e * D + dd]);
+          if (ACTOR && a.mu_out) a.mu_out[g0 + (size_t)e * D + dd] = mu;
+        }
         const float ac = fminf(1.0f, fmaxf(-1.0f, a_raw));
         const int32_t k = (int32_t)truncf(ac * d.hmax);
         const float p = s_p[o];
@@ -385,25 +494,14 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         sl.rcp = rcp;
         s_slot[o] = sl;
         s_q[o] = q;
-        s_pv[o] = r_pv[i];
+        s_pv[o] = live ? r_pv[i] : 0.0f;
         s_e2[o] = eps * eps;
       }
     }
-    if (tid_p < E)
-      for (int dd = D; dd < DMAX; ++dd) {
-        const int o = tid_p * Dp + dd;
-        Slot sl;
-        sl.k = 0;
-        sl.val = 0.0f;
-        sl.rcp = 0.0;
-        s_slot[o] = sl;
-        s_q[o] = 0;
-        s_pv[o] = 0.0f;
-        s_e2[o] = 0.0f;
-      }
     __syncthreads();
 
-    if (wave == 0 && lane < E) {
+    if (wave == 0) {
+     if (lane < E) {
       // ---- the ledger: one lane per env walks the cash chain in stock order
       // Each pass stages a chunk of the lane's row in registers first, so that the LDS reads of a chunk are
       // all in flight together and the dependent chain on `cash` runs on registers only.
@@ -468,7 +566,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       const double r = (asset1 - asset) * (double)d.rho;
       asset = asset1;
       ep_ret += r;
-      const int dn = s_row[e].done;
+      const int dn = rows_t[e].done;
       const size_t tn = (size_t)t * N + n;
       a.reward[tn] = (float)r;
       a.done[tn] = (uint8_t)dn;
@@ -485,8 +583,13 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       }
       s_cash[e] = cash;
       s_done[e] = dn;
-      s_row[e] = row_of(d, tau, start, n);  // cursor rows of step t + 1 (nobody reads the old ones any more)
-    } else if (wave == 1 && lane < E && a.logp) {
+      rows_next[e] = row_of(d, tau, start, n);  // cursor rows of step t + 1
+     }
+    } else {
+     // ---- meanwhile, the other wavefronts: market row of observation t + 1 (requested here, written out at the
+     // end of the phase), and on one of them the log-probabilities
+     fetch_market(rows_t);
+     if (wave == 1 && lane < E && a.logp) {
       // ---- log-probability of the sampled action: squared noise summed in stock order, one lane per env
       int e = lane;
       asm volatile("" : "+v"(e));
@@ -501,11 +604,15 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         for (int j = 0; j < 16; ++j) e2 += ee[j];  // empty slots add +0
       }
       a.logp[(size_t)t * N + n0 + e] = fmaf(-0.5f, e2, d.logp_const);
+     }
+     emit_market(obs_next, r_po, r_ind);
     }
-    // ---- meanwhile (and the ledger lanes afterwards): market part of observation t+1
-    emit_market(obs_next, r_po, r_ind);
     __syncthreads();
-    if (ACTOR && t + 1 < a.T) prime<CTH, ring_depth(CTH)>(ring, net.W[0], net.nkb[0], net.nct[0], wave * CTH, lane);
+    if (ACTOR && t + 1 < a.T) {
+      int lane_p = lane;  // (opaque per step: the block addresses are recomputed here, not kept across the step)
+      asm volatile("" : "+v"(lane_p));
+      prime<CTH, PDR>(ring, net.W[0], net.nkb[0], net.nct[0], wave * CTH, lane_p);
+    }
 
     // ---- executed trades out; episode ends clear the holdings; portfolio part of observation t+1
     emit_portfolio(obs_next, std::true_type{}, g0);
@@ -576,7 +683,7 @@ FusedLayout fused_layout(const pr_config &c, bool with_actor) {
   L.off_p = (int32_t)off;
   off += (size_t)E * kDp * 4;
   L.off_row = (int32_t)off;
-  off += (size_t)E * sizeof(Row);
+  off += (size_t)2 * E * sizeof(Row);  // two buffers, by the step's parity
   L.off_cash = (int32_t)off;
   off += (size_t)E * 4;
   L.off_done = (int32_t)off;
@@ -640,8 +747,6 @@ hipError_t launch_rollout_fused(hipStream_t st, const pr_config &c, const EnvDim
   const int DK = d.D * d.K;
   const bool with_actor = mu_forced == nullptr;
   a.L = fused_layout(c, with_actor);
-  a.d_magic = (uint32_t)((0x100000000ull + (uint64_t)d.D - 1) / (uint64_t)d.D);
-  a.g_magic = (uint32_t)((0x100000000ull + (uint64_t)(DK / 4) - 1) / (uint64_t)(DK / 4));
   if (reinterpret_cast<uintptr_t>(ind) & 15u) return hipErrorInvalidValue;  // 16-byte indicator loads
   const size_t lds = (size_t)a.L.total;
   if (lds > kLdsMax) return hipErrorInvalidValue;

@@ -270,7 +270,7 @@ __device__ inline void mma_layer_static(f32x16 (&acc)[CT][NBT], u32x4 (&ring)[PD
 // last PD steps refill their slots with blocks kbn0 + (slot) of Wn (nctn feature tiles per k-block): the ring is
 // then primed, slot for slot, for a range that starts at block kbn0 of Wn.  NEXT = false: no refills in the last PD
 // steps (the ring's registers are free afterwards; the caller primes it again before the next range).
-template <bool BF16, int CT, int NBT, int PD, int NKB, bool NEXT = true>
+template <bool BF16, int CT, int NBT, int PD, int NKB, bool NEXT = true, bool XAHEAD = false>
 __device__ inline void mma_range_static(f32x16 (&acc)[CT][NBT], u32x4 (&ring)[PD][CT], const unsigned char *ldsX,
                                         int pitch, const u32x4 *W, int nct, int kbw0, const u32x4 *Wn, int nctn,
                                         int kbn0, int ct0, int bt0, int lane) {
@@ -284,14 +284,31 @@ __device__ inline void mma_range_static(f32x16 (&acc)[CT][NBT], u32x4 (&ring)[PD
     wp[c] = W + ((size_t)kbw0 * nct + min(ct0 + c, nct - 1)) * 64 + lane;
     wn[c] = Wn + ((size_t)kbn0 * nctn + min(ct0 + c, nctn - 1)) * 64 + lane;
   }
+  // XAHEAD: the activation block of step i + 1 is requested before the matrix instructions of step i, for a
+  // wavefront that has its SIMD's matrix pipe to itself (nobody else's instructions cover the LDS round trip)
+  u32x4 xn[NBT];
+  if (XAHEAD) {
+#pragma unroll
+    for (int t = 0; t < NBT; ++t) xn[t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)t * 32 * pitch);
+  }
 #pragma unroll
   for (int i = 0; i < NKB; ++i) {
     constexpr int dummy = 0;
     (void)dummy;
     const int s = i % PD;
     u32x4 x[NBT];
+    if (XAHEAD) {
 #pragma unroll
-    for (int t = 0; t < NBT; ++t) x[t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)t * 32 * pitch + i * 32);
+      for (int t = 0; t < NBT; ++t) x[t] = xn[t];
+      if (i + 1 < NKB) {
+#pragma unroll
+        for (int t = 0; t < NBT; ++t)
+          xn[t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)t * 32 * pitch + (i + 1) * 32);
+      }
+    } else {
+#pragma unroll
+      for (int t = 0; t < NBT; ++t) x[t] = *reinterpret_cast<const u32x4 *>(xbase + (size_t)t * 32 * pitch + i * 32);
+    }
 #pragma unroll
     for (int c = 0; c < CT; ++c)
 #pragma unroll
