@@ -298,10 +298,11 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     asm volatile("" : "+v"(l));
     if (wave >= 1) {
       const int lp = min(l, D - 1), li = min(l, (DK >> 2) - 1);
+      const int row_of_lane = rows[min(l, E - 1)].row_obs;  // one LDS read; the rows are then picked lane by lane
 #pragma unroll
       for (int i = 0; i < MROWS; ++i) {
         const int e = min((wave - 1) + (NW - 1) * i, E - 1);
-        const size_t ro = (size_t)__builtin_amdgcn_readfirstlane(rows[e].row_obs);
+        const size_t ro = (size_t)__builtin_amdgcn_readlane(row_of_lane, e);
         r_po[i] = __builtin_nontemporal_load(&a.price[ro * D + lp]);
         r_ind[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.ind + ro * DK) + li);
       }
@@ -448,7 +449,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     }
 
     // ---- everything that does not depend on the running cash, all lanes (slots D..31 get neutral values)
-    {
+    auto size_orders = [&]() {
       int tid_p = threadIdx.x;
       asm volatile("" : "+v"(tid_p));
       const int dd = tid_p & 31, e0 = (tid_p >> 6) * (E / NW) + ((tid_p >> 5) & 1);
@@ -497,10 +498,14 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         s_pv[o] = live ? r_pv[i] : 0.0f;
         s_e2[o] = eps * eps;
       }
-    }
-    __syncthreads();
+    };
 
+    // The ledger wavefront and the others run separate code from here to the end of the ledger phase (with the
+    // same barrier between the two phases), so that the registers of the market row the others carry through
+    // the ledger phase are not live in the ledger's code.
     if (wave == 0) {
+     size_orders();
+     __syncthreads();
      if (lane < E) {
       // ---- the ledger: one lane per env walks the cash chain in stock order
       // Each pass stages a chunk of the lane's row in registers first, so that the LDS reads of a chunk are
@@ -586,8 +591,10 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       rows_next[e] = row_of(d, tau, start, n);  // cursor rows of step t + 1
      }
     } else {
-     // ---- meanwhile, the other wavefronts: market row of observation t + 1 (requested here, written out at the
-     // end of the phase), and on one of them the log-probabilities
+     size_orders();
+     __syncthreads();
+     // ---- meanwhile, the other wavefronts: the market row of observation t + 1 (requested here, written out
+     // at the end of the phase), and on one of them the log-probabilities
      fetch_market(rows_t);
      if (wave == 1 && lane < E && a.logp) {
       // ---- log-probability of the sampled action: squared noise summed in stock order, one lane per env
