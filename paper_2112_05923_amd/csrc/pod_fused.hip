@@ -112,8 +112,15 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   constexpr int NBT = E / 32;
   using O = tile::Op<BF16>;
   // the named bf16 shape runs its actor as two wavefront groups half a layer out of step (see the step loop)
-  constexpr bool SPLIT = ACTOR && BF16 && E == 64 && CTH == 2 && NKB2 == 32 && NKB1 >= 8;
+  constexpr bool SPLIT = ACTOR && BF16 && E == 64 && CTH == 2 && NKB2 == 32 && NKB1 >= 16;
   constexpr int PDR = SPLIT ? 8 : ring_depth(CTH);  // weight blocks in flight per feature tile
+  // Roles of the wavefronts outside the actor.  The ledger wavefront LW walks the cash chains; MW others carry
+  // the market rows of the next observation.  In the split schedule these are the four wavefronts of group A,
+  // which then also run the first NK1A k-blocks of the next step's layer 1 (indicator columns only, complete
+  // once the market rows are written) while the ledger -- a wavefront of group B -- is still walking.
+  constexpr int LW = SPLIT ? NW / 2 : 0;
+  constexpr int MW = SPLIT ? NW / 2 : NW - 1;
+  constexpr int NK1A = SPLIT ? NKB1 - 8 : 0;
   extern __shared__ __align__(16) unsigned char lds[];
   const EnvDims &d = a.d;
   const int D = d.D, DK = D * d.K, S = d.S;
@@ -123,6 +130,8 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n0 = blockIdx.x * E;
   const size_t N = (size_t)d.N;
+  const bool is_market = SPLIT ? wave < NW / 2 : wave != 0;
+  const int mw = SPLIT ? wave : wave - 1;  // index among the market wavefronts
 
   // ---- LDS carve-up (see FusedLayout)
   unsigned char *ldsH = lds;
@@ -134,6 +143,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   Row *s_row = reinterpret_cast<Row *>(lds + a.L.off_row);
   float *s_cash = reinterpret_cast<float *>(lds + a.L.off_cash);
   int32_t *s_done = reinterpret_cast<int32_t *>(lds + a.L.off_done);  // episode-end flags of the step just taken
+  int32_t *s_sync = s_done + E;  // arrivals of group A's wavefronts at their own meeting point, counted up all rollout
   // scratch in the hidden tile
   Slot *s_slot = reinterpret_cast<Slot *>(ldsH);            // what the ledger needs per (env, stock), one 16-byte read
   int32_t *s_q = reinterpret_cast<int32_t *>(s_slot + E * Dp);  // executed shares, signed
@@ -170,11 +180,12 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     }
     // padded k columns of the input tile must read as zero
     for (int i = tid; i < E * a.L.xpitch / 4; i += NT) reinterpret_cast<uint32_t *>(ldsX)[i] = 0u;
+    if (tid == 0) *s_sync = 0;
   }
   __syncthreads();
 
   // ---- prologue: load the state, emit observation 0
-  if (wave == 0 && lane < E) {
+  if (wave == LW && lane < E) {
     const int n = n0 + lane;
     cash = a.st.cash[n];
     tau = a.st.tau[n];
@@ -204,7 +215,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   __syncthreads();
 
   constexpr int PAIRS = E / 16;                   // (env, stock) slots per lane
-  constexpr int MROWS = (E + NW - 2) / (NW - 1);  // market rows per wavefront 1..7
+  constexpr int MROWS = (E + MW - 1) / MW;        // market rows per market wavefront
   // (Each helper starts from an opaque copy of the thread index: what it derives from it is loop invariant, and
   // the compiler would otherwise keep it in registers across the matrix-core code instead of recomputing a few
   // integer operations.)
@@ -213,10 +224,10 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   auto emit_market = [&](float *obs_row, const float (&p_obs)[MROWS], const f32x4 (&ind_v)[MROWS]) {
     int l = threadIdx.x & 63;
     asm volatile("" : "+v"(l));
-    if (wave >= 1) {
+    if (is_market) {
 #pragma unroll
       for (int i = 0; i < MROWS; ++i) {
-        const int e = (wave - 1) + (NW - 1) * i;
+        const int e = mw + MW * i;
         if (e < E) {
           float *orow = obs_row + (size_t)(n0 + e) * S;
           if (l < D) {
@@ -296,12 +307,12 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   auto fetch_market = [&](const Row *rows) {
     int l = threadIdx.x & 63;
     asm volatile("" : "+v"(l));
-    if (wave >= 1) {
+    if (is_market) {
       const int lp = min(l, D - 1), li = min(l, (DK >> 2) - 1);
       const int row_of_lane = rows[min(l, E - 1)].row_obs;  // one LDS read; the rows are then picked lane by lane
 #pragma unroll
       for (int i = 0; i < MROWS; ++i) {
-        const int e = min((wave - 1) + (NW - 1) * i, E - 1);
+        const int e = min(mw + MW * i, E - 1);
         const size_t ro = (size_t)__builtin_amdgcn_readlane(row_of_lane, e);
         r_po[i] = __builtin_nontemporal_load(&a.price[ro * D + lp]);
         r_ind[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.ind + ro * DK) + li);
@@ -326,7 +337,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     emit_portfolio(a.obs, std::false_type{}, 0);
   }
   __syncthreads();
-  if (wave == 0 && lane < E) {
+  if (wave == LW && lane < E) {
     // account value the first reward is measured against; cursor rows of step 0
     const int e = lane;
     double v = (double)cash;
@@ -340,6 +351,35 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   u32x4 ring[PDR][CTH];
   const float *lb3 = ldsBias + (ACTOR ? (a.actor.nct[0] + a.actor.nct[1]) * 32 : 0);
   if (ACTOR) prime<CTH, PDR>(ring, net.W[0], net.nkb[0], net.nct[0], wave * CTH, lane);
+  // split schedule: layer-1 accumulators of group A, carried from the ledger phase of one step into the next
+  f32x16 acc1[SPLIT ? CTH : 1][SPLIT ? NBT : 1];
+  auto layer1_head = [&]() {  // group A: bias and the first NK1A k-blocks; leaves the ring primed with the rest
+    if constexpr (SPLIT) {
+      int lane_h = lane;
+      asm volatile("" : "+v"(lane_h));
+      bias_acc<CTH, NBT>(acc1, ldsBias, wave * CTH, lane_h);
+      mma_range_static<true, CTH, NBT, PDR, NK1A, true, true>(acc1, ring, ldsX, a.L.xpitch, net.W[0], net.nct[0], 0,
+                                                             net.W[0], net.nct[0], NK1A, wave * CTH, 0, lane_h);
+    }
+  };
+  if constexpr (SPLIT) {
+    if (wave < NW / 2) layer1_head();  // (observation 0 is complete: the barrier above)
+  }
+  // Group B's wavefronts start every step by overwriting the layer-1 accumulators and the ring, but the compiler
+  // cannot tell that the ledger code only runs on a wavefront of group B and would keep both live (128
+  // registers) through it.  An empty statement that "produces" them ends their live range there at no cost.
+  auto forget_actor_registers = [&]() {
+    if constexpr (SPLIT) {
+#pragma unroll
+      for (int c = 0; c < CTH; ++c)
+#pragma unroll
+        for (int b = 0; b < NBT; ++b) asm volatile("" : "=v"(acc1[c][b]));
+#pragma unroll
+      for (int s = 0; s < PDR; ++s)
+#pragma unroll
+        for (int c = 0; c < CTH; ++c) asm volatile("" : "=v"(ring[s][c]));
+    }
+  };
 
   for (int t = 0; t < a.T; ++t) {
     __syncthreads();  // observation t complete in LDS; ledger rows of step t visible
@@ -364,17 +404,22 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       const int ct0 = wave * CTH;
       const int own0 = grpB ? HALF : 0, oth0 = grpB ? 0 : HALF;
       const float *lb1 = ldsBias, *lb2 = ldsBias + net.nct[0] * 32;
-      f32x16 acc[CTH][NBT];
+      f32x16 (&acc)[CTH][NBT] = acc1;
       int lane_s = lane;  // (opaque per step, or the addresses of all weight blocks are hoisted out of the step loop)
       asm volatile("" : "+v"(lane_s));
       if (grpB) {
         fetch_step_inputs(t);
         fetch_valuation(rows_t);
         __syncthreads();
+        bias_acc<CTH, NBT>(acc, lb1, ct0, lane_s);
+        mma_range_static<true, CTH, NBT, PDS, NKB1, true, true>(acc, ring, ldsX, a.L.xpitch, net.W[0], net.nct[0], 0,
+                                                                net.W[1], net.nct[1], own0, ct0, 0, lane_s);
+      } else {
+        // (the head of layer 1 ran during the previous step's ledger phase)
+        mma_range_static<true, CTH, NBT, PDS, NKB1 - NK1A, true, true>(acc, ring, ldsX + NK1A * 32, a.L.xpitch, net.W[0],
+                                                                       net.nct[0], NK1A, net.W[1], net.nct[1], own0, ct0,
+                                                                       0, lane_s);
       }
-      bias_acc<CTH, NBT>(acc, lb1, ct0, lane_s);
-      mma_range_static<true, CTH, NBT, PDS, NKB1, true, true>(acc, ring, ldsX, a.L.xpitch, net.W[0], net.nct[0], 0, net.W[1],
-                                                   net.nct[1], own0, ct0, 0, lane_s);
       __syncthreads();
       epilogue_hidden_biased<CTH, NBT>(acc, ldsH, a.L.hpitch, ct0, 0, lane_s);
       __syncthreads();
@@ -425,12 +470,8 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
           for (int i = 0; i < 16; ++i) plane[b * 32 * MUP + 8 * (i >> 2) + (i & 3)] = o3[b][i];
       }
       __syncthreads();
-      if (!grpB) {
-        fetch_step_inputs(t);
-        fetch_valuation(rows_t);
-        __syncthreads();
-      }
-      // (both groups have passed six barriers: the means are complete and the hidden tile is free)
+      // (group A has passed five barriers, group B six; A's sixth is in its branch below, behind the requests for
+      // its noise, valuation prices and market rows -- the slot in which B runs step (e))
     } else {
       if (ACTOR) {
         mlp_tile<BF16, NW, CTH, false, NKB1, NKB2, true, true, KS, NBT>(
@@ -500,13 +541,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       }
     };
 
-    // The ledger wavefront and the others run separate code from here to the end of the ledger phase (with the
-    // same barrier between the two phases), so that the registers of the market row the others carry through
-    // the ledger phase are not live in the ledger's code.
-    if (wave == 0) {
-     size_orders();
-     __syncthreads();
-     if (lane < E) {
+    auto run_ledger = [&]() {
       // ---- the ledger: one lane per env walks the cash chain in stock order
       // Each pass stages a chunk of the lane's row in registers first, so that the LDS reads of a chunk are
       // all in flight together and the dependent chain on `cash` runs on registers only.
@@ -589,14 +624,8 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
       s_cash[e] = cash;
       s_done[e] = dn;
       rows_next[e] = row_of(d, tau, start, n);  // cursor rows of step t + 1
-     }
-    } else {
-     size_orders();
-     __syncthreads();
-     // ---- meanwhile, the other wavefronts: the market row of observation t + 1 (requested here, written out
-     // at the end of the phase), and on one of them the log-probabilities
-     fetch_market(rows_t);
-     if (wave == 1 && lane < E && a.logp) {
+    };
+    auto run_logp = [&]() {
       // ---- log-probability of the sampled action: squared noise summed in stock order, one lane per env
       int e = lane;
       asm volatile("" : "+v"(e));
@@ -611,14 +640,78 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         for (int j = 0; j < 16; ++j) e2 += ee[j];  // empty slots add +0
       }
       a.logp[(size_t)t * N + n0 + e] = fmaf(-0.5f, e2, d.logp_const);
-     }
-     emit_market(obs_next, r_po, r_ind);
-    }
-    __syncthreads();
-    if (ACTOR && t + 1 < a.T) {
-      int lane_p = lane;  // (opaque per step: the block addresses are recomputed here, not kept across the step)
-      asm volatile("" : "+v"(lane_p));
-      prime<CTH, PDR>(ring, net.W[0], net.nkb[0], net.nct[0], wave * CTH, lane_p);
+     
+    };
+
+    // The ledger wavefront and the others run separate code from here to the end of the ledger phase (with the
+    // same barrier between the two phases), so that the registers of the market row the others carry through
+    // the ledger phase are not live in the ledger's code.
+    if constexpr (SPLIT) {
+      if (wave < NW / 2) {
+        // group A: market row of observation t + 1 (requested in its last actor slot), then -- once all four of
+        // its wavefronts have written their rows -- the head of the next step's layer 1
+        fetch_step_inputs(t);
+        fetch_valuation(rows_t);
+        fetch_market(rows_t);
+        __syncthreads();  // the means are complete and the hidden tile is free
+        size_orders();
+        __syncthreads();
+        {
+          // (also after the last step, like the head of layer 1 below: harmless, and the ring and the accumulators
+          // are then defined on every path through this branch -- nothing of the previous step stays live in it)
+          int lane_p = lane;  // (opaque per step: the block addresses are recomputed here, not kept across the step)
+          asm volatile("" : "+v"(lane_p));
+          prime<CTH, PDR>(ring, net.W[0], net.nkb[0], net.nct[0], wave * CTH, lane_p);
+        }
+        emit_market(obs_next, r_po, r_ind);
+        // meeting point of group A alone (the other wavefronts are busy and meet everybody at the barrier below):
+        // a counter in LDS that every wavefront of the group bumps once per step and then waits on, with a bound
+        // on the wait so that a mistake elsewhere shows as a wrong result, never as a hang
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        if (lane == 0) __hip_atomic_fetch_add(s_sync, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const int target = (NW / 2) * (t + 1);
+        for (int spin = 0; spin < (1 << 20); ++spin) {
+          if (__hip_atomic_load(s_sync, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) >= target) break;
+          __builtin_amdgcn_s_sleep(1);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        layer1_head();
+      } else {
+        size_orders();
+        __syncthreads();
+        if (wave == LW) {
+          if (lane < E) run_ledger();
+        } else if (wave == LW + 1) {
+          if (lane < E && a.logp) run_logp();
+        }
+        forget_actor_registers();
+      }
+      __syncthreads();
+      if (wave >= NW / 2) {  // (also after the last step: the loads are harmless, and the ring is defined on every path)
+        int lane_p = lane;
+        asm volatile("" : "+v"(lane_p));
+        prime<CTH, PDR>(ring, net.W[0], net.nkb[0], net.nct[0], wave * CTH, lane_p);
+      }
+    } else {
+      if (wave == 0) {
+        size_orders();
+        __syncthreads();
+        if (lane < E) run_ledger();
+      } else {
+        size_orders();
+        __syncthreads();
+        // ---- meanwhile, the other wavefronts: the market row of observation t + 1 (requested here, written out
+        // at the end of the phase), and on one of them the log-probabilities
+        fetch_market(rows_t);
+        if (wave == 1 && lane < E && a.logp) run_logp();
+        emit_market(obs_next, r_po, r_ind);
+      }
+      __syncthreads();
+      if (ACTOR && t + 1 < a.T) {
+        int lane_p = lane;  // (opaque per step: the block addresses are recomputed here, not kept across the step)
+        asm volatile("" : "+v"(lane_p));
+        prime<CTH, PDR>(ring, net.W[0], net.nkb[0], net.nct[0], wave * CTH, lane_p);
+      }
     }
 
     // ---- executed trades out; episode ends clear the holdings; portfolio part of observation t+1
@@ -627,7 +720,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
 
   // ---- epilogue: state back to the workspace
   __syncthreads();
-  if (wave == 0 && lane < E) {
+  if (wave == LW && lane < E) {
     const int n = n0 + lane;
     a.st.cash[n] = cash;
     a.st.tau[n] = tau;
@@ -656,7 +749,10 @@ FusedShape fused_shape(const pr_config &c) {
   f.cth = (c.hidden / 32) / NW;
   f.nkb1 = f.nkb2 = 0;
   // the named shapes: 301 inputs with 512 hidden units in bf16 / 256 hidden units in fp32
-  if (KB == 16 && f.cth == 2 && (S + 15) / 16 == 19 && c.hidden / 16 == 32) f.nkb1 = 19, f.nkb2 = 32;
+  // (the split schedule of this instance runs the first 11 k-blocks of layer 1 before the portfolio columns
+  // exist: they must all be indicator columns)
+  if (KB == 16 && f.cth == 2 && (S + 15) / 16 == 19 && c.hidden / 16 == 32 && c.n_stocks * c.n_ind >= 11 * 16)
+    f.nkb1 = 19, f.nkb2 = 32;
   if (KB == 8 && f.cth == 1 && (S + 7) / 8 == 38 && c.hidden / 8 == 32) f.nkb1 = 38, f.nkb2 = 32;
   return f;
 }
@@ -694,7 +790,7 @@ FusedLayout fused_layout(const pr_config &c, bool with_actor) {
   L.off_cash = (int32_t)off;
   off += (size_t)E * 4;
   L.off_done = (int32_t)off;
-  off += (size_t)E * 4;
+  off += (size_t)E * 4 + 16;  // episode-end flags, and the meeting counter of the split schedule behind them
   L.total = (int32_t)off;
   return L;
 }
