@@ -118,6 +118,8 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   // the market rows of the next observation.  In the split schedule these are the four wavefronts of group A,
   // which then also run the first NK1A k-blocks of the next step's layer 1 (indicator columns only, complete
   // once the market rows are written) while the ledger -- a wavefront of group B -- is still walking.
+  // (Measured alternatives that were no faster: the three idle wavefronts of group B sharing the market rows;
+  // a raised priority for the ledger wavefront.)
   constexpr int LW = SPLIT ? NW / 2 : 0;
   constexpr int MW = SPLIT ? NW / 2 : NW - 1;
   constexpr int NK1A = SPLIT ? NKB1 - 8 : 0;
@@ -225,30 +227,28 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
     int l = threadIdx.x & 63;
     asm volatile("" : "+v"(l));
     if (is_market) {
+      // Straight-line code without lane masks: lanes beyond the row's prices / indicator groups, and passes beyond
+      // the tile's last row, repeat the last valid item -- they loaded the same value and store it to the same
+      // place again.
+      const int lp = min(l, D - 1), li = min(l, (DK >> 2) - 1);
 #pragma unroll
       for (int i = 0; i < MROWS; ++i) {
-        const int e = mw + MW * i;
-        if (e < E) {
-          float *orow = obs_row + (size_t)(n0 + e) * S;
-          if (l < D) {
-            const float v = p_obs[i];
-            s_p[e * Dp + l] = v;
-            const float sv = v * d.s_price;
-            __builtin_nontemporal_store(sv, &orow[1 + l]);
-            if (ACTOR) O::store1(ldsX + (size_t)e * a.L.xpitch + (DK + 1 + l) * O::ESZ, sv);
-          }
-          if (4 * l < DK) {
-            f32x4 sv = ind_v[i];
-            sv[0] *= d.s_ind;
-            sv[1] *= d.s_ind;
-            sv[2] *= d.s_ind;
-            sv[3] *= d.s_ind;
-            // observation rows are 4-byte aligned only; a 16-byte store needs no more than that
-            __builtin_nontemporal_store(sv, reinterpret_cast<f32x4 *>(orow + 1 + 2 * D + 4 * l));
-            // (indicators lead the LDS tile, so a group of four is one aligned store)
-            if (ACTOR) O::store4(ldsX + (size_t)e * a.L.xpitch + 4 * l * O::ESZ, sv[0], sv[1], sv[2], sv[3]);
-          }
-        }
+        const int e = min(mw + MW * i, E - 1);
+        float *orow = obs_row + (size_t)(n0 + e) * S;
+        const float v = p_obs[i];
+        s_p[e * Dp + lp] = v;
+        const float pv = v * d.s_price;
+        __builtin_nontemporal_store(pv, &orow[1 + lp]);
+        if (ACTOR) O::store1(ldsX + (size_t)e * a.L.xpitch + (DK + 1 + lp) * O::ESZ, pv);
+        f32x4 sv = ind_v[i];
+        sv[0] *= d.s_ind;
+        sv[1] *= d.s_ind;
+        sv[2] *= d.s_ind;
+        sv[3] *= d.s_ind;
+        // observation rows are 4-byte aligned only; a 16-byte store needs no more than that
+        __builtin_nontemporal_store(sv, reinterpret_cast<f32x4 *>(orow + 1 + 2 * D) + li);
+        // (indicators lead the LDS tile, so a group of four is one aligned store)
+        if (ACTOR) O::store4(ldsX + (size_t)e * a.L.xpitch + 4 * li * O::ESZ, sv[0], sv[1], sv[2], sv[3]);
       }
     }
   };
@@ -316,6 +316,13 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         const size_t ro = (size_t)__builtin_amdgcn_readlane(row_of_lane, e);
         r_po[i] = __builtin_nontemporal_load(&a.price[ro * D + lp]);
         r_ind[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.ind + ro * DK) + li);
+      }
+    } else {
+      // (defined on every path: otherwise the values of the previous step count as live all around the loop)
+#pragma unroll
+      for (int i = 0; i < MROWS; ++i) {
+        r_po[i] = 0.0f;
+        r_ind[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
       }
     }
   };
@@ -580,16 +587,20 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         }
 #pragma unroll
         for (int j = 0; j < CH; ++j) {
-          const bool buy = sl[j].k > 0;
-          const int32_t k = max(sl[j].k, 0);  // sales and holds: k = 0 and reciprocal 0 give q = 0, outlay 0
+          // On the chain through `cash`: widen, multiply, narrow, truncate, min, multiply, subtract | compare,
+          // select -- eight operations.  Sales and holds have k = 0 and reciprocal 0: q = 0, outlay 0.  The
+          // quotient is never negative (cash is not), so truncation is the floor and needs no clamp at 0; the
+          // outlay of one share less, (q - 1) u rounded once, is the fused q u - u (the same real number, one
+          // rounding); both candidate balances are formed before the comparison is known.
+          const float kf = (float)max(sl[j].k, 0);
           const float u = sl[j].val;
           const float ratio = (float)((double)cash * sl[j].rcp);
-          const int32_t m = (int32_t)ratio;  // (toward zero: floor for ratio >= 0, and negatives end at 0 below)
-          int32_t q = min(k, max(m, 0));
-          const float out_q = (float)q * u, out_q1 = (float)(q - 1) * u;
-          const bool over = buy && out_q > cash;
-          q = over ? q - 1 : q;
-          cash = cash - (over ? out_q1 : out_q);
+          const float q0 = fminf(kf, truncf(ratio));
+          const float out_q = q0 * u, out_q1 = fmaf(q0, u, -u);
+          const float bal0 = cash - out_q, bal1 = cash - out_q1;
+          const bool over = out_q > cash;
+          cash = over ? bal1 : bal0;
+          const int32_t q = (int32_t)(over ? q0 - 1.0f : q0);
           hn[c0 + j] = hh[j] + q;
           s_q[o0 + c0 + j] = qq[j] + q;  // (a purchase slot held 0)
         }
@@ -669,21 +680,22 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         // on the wait so that a mistake elsewhere shows as a wrong result, never as a hang
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         if (lane == 0) __hip_atomic_fetch_add(s_sync, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        const int target = (NW / 2) * (t + 1);
+        const int target = MW * (t + 1);
         for (int spin = 0; spin < (1 << 20); ++spin) {
           if (__hip_atomic_load(s_sync, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) >= target) break;
           __builtin_amdgcn_s_sleep(1);
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         layer1_head();
+      } else if (wave == LW) {
+        size_orders();
+        __syncthreads();
+        if (lane < E) run_ledger();
+        forget_actor_registers();
       } else {
         size_orders();
         __syncthreads();
-        if (wave == LW) {
-          if (lane < E) run_ledger();
-        } else if (wave == LW + 1) {
-          if (lane < E && a.logp) run_logp();
-        }
+        if (wave == LW + 1 && lane < E && a.logp) run_logp();
         forget_actor_registers();
       }
       __syncthreads();
