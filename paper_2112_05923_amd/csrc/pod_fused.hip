@@ -47,6 +47,7 @@ constexpr int kDp = DMAX + 1;    // odd row pitch: the per-env serial walks of t
 //    The ledger wavefront carries none: a load of its own in flight would sit in front of whatever its serial
 //    pass waits for next (a wavefront's memory operations complete in order).
 
+constexpr int kLagPrio = 2;  // wavefront priority of the lagging group's matrix steps in the split schedule (1..3 measure alike)
 constexpr int MUP = 33;         // row pitch of a policy-mean plane (lanes of one store differ in the row: 32 would hit one bank)
 // Planes the output layer's k range is split into (one per group of wavefronts), by the compile-time k-block count
 // of the kernel instance.
@@ -419,6 +420,8 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         fetch_valuation(rows_t);
         __syncthreads();
         bias_acc<CTH, NBT>(acc, lb1, ct0, lane_s);
+        // (group B is the one the barriers wait for: its matrix steps go first on the SIMDs it shares with A)
+        __builtin_amdgcn_s_setprio(kLagPrio);
         mma_range_static<true, CTH, NBT, PDS, NKB1, true, true>(acc, ring, ldsX, a.L.xpitch, net.W[0], net.nct[0], 0,
                                                                 net.W[1], net.nct[1], own0, ct0, 0, lane_s);
       } else {
@@ -427,15 +430,18 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
                                                                        net.nct[0], NK1A, net.W[1], net.nct[1], own0, ct0,
                                                                        0, lane_s);
       }
+      __builtin_amdgcn_s_setprio(0);
       __syncthreads();
       epilogue_hidden_biased<CTH, NBT>(acc, ldsH, a.L.hpitch, ct0, 0, lane_s);
       __syncthreads();
       bias_acc<CTH, NBT>(acc, lb2, ct0, lane_s);
+      if (grpB) __builtin_amdgcn_s_setprio(kLagPrio);
       mma_range_static<true, CTH, NBT, PDS, HALF, true, true>(acc, ring, ldsH + own0 * 32, a.L.hpitch, net.W[1], net.nct[1], own0,
                                                    net.W[1], net.nct[1], oth0, ct0, 0, lane_s);
       __syncthreads();
       mma_range_static<true, CTH, NBT, PDS, HALF, false, true>(acc, ring, ldsH + oth0 * 32, a.L.hpitch, net.W[1], net.nct[1],
                                                           oth0, net.W[1], net.nct[1], 0, ct0, 0, lane_s);
+      __builtin_amdgcn_s_setprio(0);
       __syncthreads();
       {
         f32x16 o3[NBT];
