@@ -394,6 +394,8 @@ def _run(w, H, T, schedule, n_market=None, forced_mu=None, calls=1):
 @pytest.mark.parametrize("base,hidden,N,agents,H,n_market,D,K", [
     ("large", 512, 128, 1, 10, None, 30, 8), ("large", 256, 192, 1, 24, None, 30, 8), ("large", 512, 128, 2, 7, None, 30, 8),
     ("large", 512, 64, 1, 24, 1, 30, 8), ("large", 256, 128, 1, 9, None, 5, 4), ("large", 512, 64, 1, 24, None, 2, 2),
+    # other observations of 19 k-blocks on the split schedule: all 32 stock slots in use / fewer indicator groups
+    ("large", 512, 128, 1, 10, None, 32, 7), ("large", 512, 128, 2, 8, None, 24, 10),
     ("large", 256, 64, 1, 24, None, 32, 1),
     # fp32 networks: 32-env tiles
     ("dow30", 256, 96, 1, 10, None, 30, 8), ("dow30", 256, 128, 2, 7, None, 30, 8), ("dow30", 256, 32, 1, 24, 1, 30, 8),
