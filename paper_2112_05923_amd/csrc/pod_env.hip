@@ -85,7 +85,8 @@ __global__ __launch_bounds__(kEnvThreads) void env_step_kernel(EnvDims d, EnvSta
   const int D = d.D, Dp = D | 1;
   double *s_a0 = reinterpret_cast<double *>(lds_raw);  // [E] account value before the trades
   double *s_a1 = s_a0 + E;                             // [E] account value after them, at the valuation prices
-  int32_t *s_k = reinterpret_cast<int32_t *>(s_a1 + E);
+  double *s_rcp = s_a1 + E;                            // [E][Dp] 1 / unit cost of a purchase in binary64, else 0
+  int32_t *s_k = reinterpret_cast<int32_t *>(s_rcp + E * Dp);
   float *s_e2 = reinterpret_cast<float *>(s_k + E * Dp);
   float *s_val = s_e2 + E * Dp;
   int32_t *s_q = reinterpret_cast<int32_t *>(s_val + E * Dp);
@@ -202,7 +203,8 @@ __global__ __launch_bounds__(kEnvThreads) void env_step_kernel(EnvDims d, EnvSta
           const float p = pn[u];
           const int32_t h = s_h[o];
           int32_t q = 0;
-          float val = 1.0f;  // (holds: a harmless divisor)
+          float val = 0.0f;
+          double rcp = 0.0;
           if (k < 0) {
             q = min(-k, h);
             s_h[o] = h - q;
@@ -211,7 +213,9 @@ __global__ __launch_bounds__(kEnvThreads) void env_step_kernel(EnvDims d, EnvSta
             q = -q;
           } else if (k > 0) {
             val = p * d.one_plus_c;
+            rcp = 1.0 / (double)val;
           }
+          s_rcp[o] = rcp;
           s_k[o] = k;
           s_e2[o] = eps[u] * eps[u];
           s_val[o] = val;
@@ -248,35 +252,66 @@ __global__ __launch_bounds__(kEnvThreads) void env_step_kernel(EnvDims d, EnvSta
       const int o0 = e * Dp;
       float cash = cash_in;  // (e == lane: E <= 64)
       float e2 = 0.0f;
-      for (int dd = 0; dd < D; ++dd) {
-        e2 += s_e2[o0 + dd];
-        const int32_t k = s_k[o0 + dd];
-        const float v = s_val[o0 + dd];
+      // Each pass stages a chunk of the lane's row in registers first, so that the LDS reads of a chunk are all in
+      // flight together and the dependent chain on `cash` runs on registers only (slots beyond D read as holds).
+      // (whole chunks run without bounds checks; the last D % 8 slots one by one)
+      constexpr int CH = 8;
+      const int Dfull = D & ~(CH - 1);
+      auto sell = [&](int32_t k, float v, float sq) {
+        e2 += sq;
         cash = k < 0 ? cash + v : cash;  // all sales in stock order
+      };
+      for (int c0 = 0; c0 < Dfull; c0 += CH) {
+        int32_t kk[CH];
+        float vv[CH], ee[CH];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) kk[j] = s_k[o0 + c0 + j], vv[j] = s_val[o0 + c0 + j], ee[j] = s_e2[o0 + c0 + j];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) sell(kk[j], vv[j], ee[j]);
       }
+      for (int dd = Dfull; dd < D; ++dd) sell(s_k[o0 + dd], s_val[o0 + dd], s_e2[o0 + dd]);
       // all purchases in stock order, each limited by the cash left:
       //   m = floor(cash / u); q = min(k, max(m, 0)); if (q u > cash) q -= 1; cash -= q u        (binary32)
-      for (int dd = 0; dd < D; ++dd) {
-        const int32_t kk = s_k[o0 + dd];
-        const bool buy = kk > 0;
-        const int32_t k = max(kk, 0);
-        const float u = s_val[o0 + dd];  // unit cost of a purchase; anything non-zero otherwise (k = 0 gives q = 0)
-        const float ratio = cash / u;
-        int32_t m = (int32_t)floorf(ratio);
-        m = max(m, 0);
-        int32_t q = buy ? min(k, m) : 0;
-        const float out_q = (float)q * u, out_q1 = (float)(q - 1) * u;
-        const bool over = buy && out_q > cash;
-        q = over ? q - 1 : q;
-        const float outlay = over ? out_q1 : out_q;
-        cash = buy ? cash - outlay : cash;
-        // (a purchase slot held 0, any other slot is rewritten with what it held: wavefront 1 reads the sale
-        // slots meanwhile.)  s_h keeps the holdings after the sales; purchases are added on the way out.
-        s_q[o0 + dd] += q;
+      // The binary32 quotient comes from one binary64 product with the reciprocal of u prepared by the other lanes:
+      // the product is within 2^-52 of cash / u, and a quotient of two binary32 numbers is at least 2^-49 (relative)
+      // away from every binary32 rounding boundary it does not hit exactly, so the product rounded to binary32 is
+      // the correctly rounded cash / u.  The quotient is never negative (cash is not), so truncation is the floor
+      // and needs no clamp at 0; the outlay of one share less, (q - 1) u rounded once, is the fused q u - u (the
+      // same real number, one rounding); both candidate balances are formed before the comparison is known.
+      // Sales and holds have k = 0 and reciprocal 0: q = 0, outlay 0.
+      // (A purchase slot of s_q held 0, any other slot is rewritten with what it held: wavefront 1 reads the sale
+      // slots meanwhile.)  s_h keeps the holdings after the sales; purchases are added on the way out.
+      auto buy = [&](int32_t k, float u, double r, int32_t q_in, int o) {
+        const float kf = (float)max(k, 0);
+        const float ratio = (float)((double)cash * r);
+        const float q0 = fminf(kf, truncf(ratio));
+        const float out_q = q0 * u, out_q1 = fmaf(q0, u, -u);
+        const float bal0 = cash - out_q, bal1 = cash - out_q1;
+        const bool over = out_q > cash;
+        cash = over ? bal1 : bal0;
+        s_q[o] = q_in + (int32_t)(over ? q0 - 1.0f : q0);
+      };
+      for (int c0 = 0; c0 < Dfull; c0 += CH) {
+        int32_t kk[CH], qq[CH];
+        float uu[CH];
+        double rr[CH];
+#pragma unroll
+        for (int j = 0; j < CH; ++j)
+          kk[j] = s_k[o0 + c0 + j], uu[j] = s_val[o0 + c0 + j], rr[j] = s_rcp[o0 + c0 + j], qq[j] = s_q[o0 + c0 + j];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) buy(kk[j], uu[j], rr[j], qq[j], o0 + c0 + j);
       }
+      for (int dd = Dfull; dd < D; ++dd) buy(s_k[o0 + dd], s_val[o0 + dd], s_rcp[o0 + dd], s_q[o0 + dd], o0 + dd);
       double asset1 = (double)cash;
-      for (int dd = 0; dd < D; ++dd)
-        asset1 += (double)(s_h[o0 + dd] + max(s_q[o0 + dd], 0)) * (double)s_pv[o0 + dd];
+      for (int c0 = 0; c0 < Dfull; c0 += CH) {
+        int32_t hh[CH];
+        float pp[CH];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) hh[j] = s_h[o0 + c0 + j] + max(s_q[o0 + c0 + j], 0), pp[j] = s_pv[o0 + c0 + j];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) asset1 += (double)hh[j] * (double)pp[j];
+      }
+      for (int dd = Dfull; dd < D; ++dd) asset1 += (double)(s_h[o0 + dd] + max(s_q[o0 + dd], 0)) * (double)s_pv[o0 + dd];
       s_a1[e] = asset1;
       cash_in = cash;  // now: cash after the trades
       s_e2sum[e] = e2;
@@ -401,7 +436,7 @@ __global__ __launch_bounds__(kEnvThreads) void env_step_kernel(EnvDims d, EnvSta
 
 size_t env_lds(int E, int D) {
   const int Dp = D | 1;
-  return (size_t)7 * E * Dp * 4 + (size_t)E * (sizeof(RowInfo) + 2 * sizeof(float) + 2 * sizeof(double));
+  return (size_t)9 * E * Dp * 4 + (size_t)E * (sizeof(RowInfo) + 2 * sizeof(float) + 2 * sizeof(double));
 }
 
 // ------------------------------------------------------------ state plumbing
@@ -516,10 +551,13 @@ __global__ void leaderboard_rank_kernel(int32_t P, const double *__restrict__ me
 
 // ------------------------------------------------------------------ launchers
 
+// LDS per workgroup up to which a tile size is taken: two workgroups per compute unit still fit.
+constexpr size_t kEnvLdsBudget = 78 * 1024;
+
 size_t env_step_lds_bytes(const EnvDims &d, int *envs_per_block) {
   const int choices[4] = {32, 16, 4, 1};  // (32-env tiles: two workgroups per compute unit overlap their round trips; measured 3 % ahead of 64)
   for (int E : choices) {
-    if (env_lds(E, d.D) <= 64 * 1024 || E == 1) {
+    if (env_lds(E, d.D) <= kEnvLdsBudget || E == 1) {
       if (envs_per_block) *envs_per_block = E;
       return env_lds(E, d.D);
     }
@@ -540,11 +578,25 @@ hipError_t launch_env_step(hipStream_t st, const EnvDims &d, const EnvState &s, 
   int E = 0;
   const size_t lds = env_step_lds_bytes(d, &E);
   const dim3 grid((d.N + E - 1) / E), block(kEnvThreads);
+  if (lds > kMaxLdsBytes) return hipErrorInvalidValue;
+  hipError_t e = hipSuccess;
   switch (E) {
-    case 32: hipLaunchKernelGGL(env_step_kernel<32>, grid, block, lds, st, d, s, price, ind, io); break;
-    case 16: hipLaunchKernelGGL(env_step_kernel<16>, grid, block, lds, st, d, s, price, ind, io); break;
-    case 4: hipLaunchKernelGGL(env_step_kernel<4>, grid, block, lds, st, d, s, price, ind, io); break;
-    default: hipLaunchKernelGGL(env_step_kernel<1>, grid, block, lds, st, d, s, price, ind, io); break;
+    case 32:
+      if ((e = allow_full_lds<env_step_kernel<32>>()) != hipSuccess) return e;
+      hipLaunchKernelGGL(env_step_kernel<32>, grid, block, lds, st, d, s, price, ind, io);
+      break;
+    case 16:
+      if ((e = allow_full_lds<env_step_kernel<16>>()) != hipSuccess) return e;
+      hipLaunchKernelGGL(env_step_kernel<16>, grid, block, lds, st, d, s, price, ind, io);
+      break;
+    case 4:
+      if ((e = allow_full_lds<env_step_kernel<4>>()) != hipSuccess) return e;
+      hipLaunchKernelGGL(env_step_kernel<4>, grid, block, lds, st, d, s, price, ind, io);
+      break;
+    default:
+      if ((e = allow_full_lds<env_step_kernel<1>>()) != hipSuccess) return e;
+      hipLaunchKernelGGL(env_step_kernel<1>, grid, block, lds, st, d, s, price, ind, io);
+      break;
   }
   return hipGetLastError();
 }
