@@ -189,6 +189,37 @@ def side_measurements(torch, pr, inputs, w, d, out, roll, adv, ret, obs2d, val2d
     return extras
 
 
+def measured_peaks():
+    """Two short launches that say what this machine delivers where the roofline uses published figures: the matrix
+    pipe alone (bf16, two wavefronts per SIMD of independent matrix instructions) and a streaming read of 1 GiB."""
+    import torch
+    from paper_2112_05923_amd import podrollout as pr
+
+    dev = torch.device("cuda:0")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+    sink = torch.empty(64, dtype=torch.float32, device=dev)
+    pr.calibrate_stream(pr.PR_CAL_READ, src, sink)
+    torch.cuda.synchronize()
+    e0.record()
+    pr.calibrate_stream(pr.PR_CAL_READ, src, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    read_gbps = src.numel() * 4 / e0.elapsed_time(e1) / 1e6
+    del src
+    IM = 4096
+    ticks = torch.full((256, 8), -1, dtype=torch.int64, device=dev)
+    roles = [pr.ROLE_MATRIX] * 8
+    pr.calibrate_probe(roles, IM, 0, 0, False, 256, ticks)
+    pr.calibrate_probe(roles, IM, 0, 0, False, 256, ticks)
+    torch.cuda.synchronize()
+    t_us = float(ticks.cpu().numpy().astype("float64").mean() * 10.0 / 1e3)
+    mfma_tflops = IM * 8 * 2 * 32 * 32 * 16 * 8 * 256 / (t_us * 1e-6) / 1e12
+    return {"hbm_read_GBps": read_gbps, "mfma_bf16_TFLOPs": mfma_tflops,
+            "note": "this box, measured in this run: streaming read of 1 GiB; 8 wavefronts per compute unit of "
+                    "independent v_mfma_f32_32x32x16_bf16"}
+
+
 def calibrate():
     """Measured machine figures the roofline fractions can be read against: streaming copy and read bandwidth,
     the matrix pipe alone, and how matrix instructions share a SIMD with the vector / transcendental
@@ -416,6 +447,13 @@ def main():
                "peak": PEAK[mf][0], "unit": "TFLOP/s", "ms_per_launch": t_critic}
     dom["frac"] = dom["achieved"] / dom["peak"]
     dom["traffic"] = recorded_traffic("fused" if args.schedule == "fused" else "critic", w.name)
+    if not args.no_extras:
+        mp = measured_peaks()
+        dom["measured"] = mp
+        if w.mlp_dtype:
+            dom["frac_of_measured_mfma"] = dom["achieved"] / mp["mfma_bf16_TFLOPs"]
+            stages["critic"]["frac_of_measured_mfma"] = stages["critic"]["TFLOPs"] / mp["mfma_bf16_TFLOPs"]
+        stages["gae"]["frac_of_measured_read"] = stages["gae"]["GBps"] / mp["hbm_read_GBps"]
 
     res = {
         "metric": "env-steps/sec (transitions/s) on 1 MI355X; achieved HBM GB/s and MFMA %",

@@ -127,6 +127,14 @@ typedef struct pr_handle pr_handle;
  * weights, env state, per-step scratch).  out: host pointer. */
 int rollout_workspace_bytes(const pr_config *cfg, size_t *out);
 
+/* LDS bytes per workgroup the persistent rollout kernel (Sec. 4.2 worker, the
+ * PR_SCHED_FUSED schedule) is launched with for this config: with_actor != 0
+ * for rollout_step_T, 0 for rollout_step_forced.  The launch reads the same
+ * carve-up, so this IS the launch size; it never exceeds 160 KiB for a config
+ * the schedule accepts.  out: host pointer.  PR_EUNSUPPORTED when the schedule
+ * does not cover the shape (no device work either way). */
+int rollout_kernel_lds_bytes(const pr_config *cfg, int32_t with_actor, size_t *out);
+
 /* Create a rollout worker (Sec. 4.2).  Packs both networks into the layout the
  * matrix-core kernels read, puts every env at (cash0, no shares, cursor 0).
  * cfg, market, actor, critic: host structs holding device pointers.

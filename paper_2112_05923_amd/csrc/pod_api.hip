@@ -193,6 +193,17 @@ int rollout_workspace_bytes(const pr_config *cfg, size_t *out) {
   return PR_OK;
 }
 
+int rollout_kernel_lds_bytes(const pr_config *cfg, int32_t with_actor, size_t *out) {
+  if (!out || !cfg) return PR_EINVAL;
+  pr_config c = *cfg;
+  c.schedule = PR_SCHED_STEPWISE;  // (validate the shape itself; whether the persistent kernel covers it is asked below)
+  const int rc = validate_config(&c);
+  if (rc != PR_OK) return rc;
+  if (!fused_supported(*cfg)) return PR_EUNSUPPORTED;
+  *out = fused_lds_bytes(*cfg, with_actor != 0);
+  return PR_OK;
+}
+
 int rollout_init(const pr_config *cfg, const pr_market *market, const pr_weights *actor, const pr_weights *critic,
                  void *workspace, size_t workspace_bytes, void *hip_stream, pr_handle **out) {
   if (!out) return PR_EINVAL;

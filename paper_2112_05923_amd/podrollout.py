@@ -21,7 +21,7 @@ PR_MLP_F32, PR_MLP_BF16 = 0, 1
 PR_SCHED_STEPWISE, PR_SCHED_FUSED = 0, 1
 PR_NET_ACTOR, PR_NET_CRITIC = 0, 1
 
-EXPORTS = ["rollout_workspace_bytes", "rollout_init", "rollout_set_weights", "rollout_reset", "rollout_set_replay",
+EXPORTS = ["rollout_workspace_bytes", "rollout_kernel_lds_bytes", "rollout_init", "rollout_set_weights", "rollout_reset", "rollout_set_replay",
            "rollout_step_T",
            "rollout_step_forced", "rollout_mlp_forward", "rollout_get_state", "rollout_set_state", "compute_gae",
            "trading_metrics", "population_refill", "ppo_workspace_bytes",
@@ -87,6 +87,7 @@ def lib():
         l.rollout_strerror.restype = C.c_char_p
         l.rollout_strerror.argtypes = [C.c_int]
         l.rollout_workspace_bytes.argtypes = [C.POINTER(PrConfig), C.POINTER(C.c_size_t)]
+        l.rollout_kernel_lds_bytes.argtypes = [C.POINTER(PrConfig), C.c_int32, C.POINTER(C.c_size_t)]
         l.rollout_init.argtypes = [C.POINTER(PrConfig), C.POINTER(PrMarket), C.POINTER(PrWeights),
                                    C.POINTER(PrWeights), C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]
         l.rollout_set_weights.argtypes = [C.c_void_p, C.POINTER(PrWeights), C.POINTER(PrWeights)]
@@ -156,6 +157,13 @@ def make_config(w, horizon: Optional[int] = None, n_market: Optional[int] = None
 def workspace_bytes(cfg: PrConfig) -> int:
     n = C.c_size_t()
     _check(lib().rollout_workspace_bytes(C.byref(cfg), C.byref(n)), "rollout_workspace_bytes")
+    return n.value
+
+
+def kernel_lds_bytes(cfg: PrConfig, with_actor: bool = True) -> int:
+    """LDS bytes per workgroup of the persistent rollout kernel for this config (raises where it is not covered)."""
+    n = C.c_size_t()
+    _check(lib().rollout_kernel_lds_bytes(C.byref(cfg), int(with_actor), C.byref(n)), "rollout_kernel_lds_bytes")
     return n.value
 
 

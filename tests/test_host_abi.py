@@ -71,6 +71,34 @@ def test_workspace_query_and_config_validation():
     assert pr.lib().rollout_workspace_bytes(None, None) == pr.PR_EINVAL
 
 
+def test_persistent_kernel_lds_fits_the_compute_unit_for_every_shape_it_accepts():
+    """The launch of the persistent kernel takes its LDS size from the same carve-up this query reads; every
+    shape the schedule accepts must fit the 160 KiB of a compute unit, with and without the actor, and the
+    schedule must accept the named workloads it is documented for."""
+    limit = 160 * 1024
+    seen = 0
+    for dtype, hiddens in ((1, (256, 512)), (0, (256,))):
+        for hidden in hiddens:
+            for D in (1, 2, 5, 17, 24, 30, 32):
+                for K in (1, 2, 4, 7, 8, 10, 16):
+                    w = inputs.WORKLOADS["large"].replace(n_envs=128, n_stocks=D, n_ind=K, hidden=hidden, mlp_dtype=dtype)
+                    cfg = pr.make_config(w, horizon=8, schedule=pr.PR_SCHED_FUSED)
+                    try:
+                        a, b = pr.kernel_lds_bytes(cfg, True), pr.kernel_lds_bytes(cfg, False)
+                    except pr.PodError as e:
+                        assert e.code == pr.PR_EUNSUPPORTED
+                        continue
+                    seen += 1
+                    assert 0 < b <= a <= limit, (dtype, hidden, D, K, a, b)
+    assert seen >= 40
+    for name in ("large", "dow30", "tournament"):
+        cfg = pr.make_config(inputs.WORKLOADS[name], schedule=pr.PR_SCHED_FUSED)
+        assert pr.kernel_lds_bytes(cfg) <= limit
+    for name in ("wide",):   # 500 stocks: per-step schedule only
+        with pytest.raises(pr.PodError):
+            pr.kernel_lds_bytes(pr.make_config(inputs.WORKLOADS[name], schedule=pr.PR_SCHED_FUSED))
+
+
 def test_null_arguments_are_rejected_without_device_work():
     lib = pr.lib()
     cfg = pr.make_config(inputs.WORKLOADS["tiny"])
