@@ -1,16 +1,24 @@
-// Persistent rollout kernel: one workgroup keeps a tile of 64 envs on its
-// compute unit for all T steps of a rollout (the worker of Sec. 4.2: actor x
-// batched environment; stock-trading task of Table 1 / Sec. 5.3).
+// Persistent rollout kernel: one workgroup keeps a tile of envs (64 with bf16
+// networks, 32 with fp32 networks) on its compute unit for all T steps of a
+// rollout (the worker of Sec. 4.2: actor x batched environment; stock-trading
+// task of Table 1 / Sec. 5.3).
 //
 // Envs are independent, so no grid-wide synchronisation is needed: each
 // workgroup loops   obs_t (LDS) -> actor (matrix cores) -> sample -> trade ->
 // reward / done / reset -> obs_{t+1} (LDS + HBM)   on its own.  The env state
-// (cash, cursor, episode sums: registers of 64 "ledger" lanes; holdings and
-// current prices: LDS) never leaves the compute unit during the rollout, and
+// (cash, cursor, episode sums: registers of one "ledger" lane per env; holdings
+// and current prices: LDS) never leaves the compute unit during the rollout, and
 // the next observation is assembled directly in the LDS tile the actor reads
 // its input from.  Per env-step the kernel therefore moves only the bytes the
 // method itself needs: noise and the next market row in, observation, raw
 // action, reward / done / log-prob out.
+//
+// For the 301-512-512 bf16 shape the actor runs as two wavefront groups half a
+// layer out of step, so that the tanh epilogues of one group execute under the
+// matrix instructions of the other, and the first k-blocks of the next step's
+// layer 1 run while the ledger of this step is still walking ("split schedule",
+// described at the step loop); other shapes run the layers with all wavefronts
+// in step.
 //
 // Trade execution reproduces, operation for operation in binary32, the serial
 // rule "all sales in stock order, then all purchases in stock order, each
@@ -156,7 +164,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
   constexpr int KS = mu_planes(NKB2);
   float *s_mu = reinterpret_cast<float *>(ldsX);
 
-  // ---- ledger lanes (wavefront 0): per-env scalars in registers for the whole rollout
+  // ---- ledger lanes (wavefront LW, see below): per-env scalars in registers for the whole rollout
   float cash = 0.0f;
   int32_t tau = 0, start = 0, ep_cnt = 0;
   double asset = 0.0, ep_ret = 0.0, ep_sum = 0.0, ep_sqsum = 0.0;
@@ -657,7 +665,7 @@ __global__ __launch_bounds__(NT) void rollout_fused_kernel(FusedArgs a) {
         for (int j = 0; j < 16; ++j) e2 += ee[j];  // empty slots add +0
       }
       a.logp[(size_t)t * N + n0 + e] = fmaf(-0.5f, e2, d.logp_const);
-     
+
     };
 
     // The ledger wavefront and the others run separate code from here to the end of the ledger phase (with the

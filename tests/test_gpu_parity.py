@@ -514,6 +514,30 @@ def test_fused_rollout_stagewise_against_checker_and_carry_across_calls():
     _stagewise(w, d, ro, ocfg, T, rec)
 
 
+def test_fused_one_step_per_call_and_odd_lengths_on_the_split_schedule():
+    """Calls of a single step, and of an odd number of steps, on the persistent kernel's split schedule: the state a
+    call leaves (ledger registers, holdings, the head of the next step's layer 1 that is computed and dropped at
+    the end of a call) must carry into the next call exactly as within one call."""
+    w = inputs.WORKLOADS["large"].replace(n_envs=64, steps=3)
+    for T, calls, H in ((3, 3, 2), (15, 3, 7)):
+        w = w.replace(steps=T)
+        d, ro, ocfg, outs, st = _run(w, H, T, FUSED, calls=calls)
+        recs = [_rec(o) for o in outs]
+        rec = {k: np.concatenate([r[k] for r in recs]) for k in ("act_raw", "reward", "done", "shares", "logp", "mu")}
+        rec["obs"] = np.concatenate([recs[0]["obs"]] + [r["obs"][1:] for r in recs[1:]])
+        rec["value"] = np.concatenate([recs[0]["value"]] + [r["value"][1:] for r in recs[1:]])
+        for a_, b_ in zip(recs[:-1], recs[1:]):
+            assert np.array_equal(a_["obs"][-1], b_["obs"][0])
+        _stagewise(w, d, ro, ocfg, T, rec)
+        # and the same rollout in one call gives the same record bit for bit
+        _, _, _, (one,), st1 = _run(w, H, T, FUSED)
+        one = _rec(one)
+        for k in ("obs", "act_raw", "reward", "done", "shares", "mu"):
+            assert np.array_equal(one[k], rec[k]), k
+        for k in st:
+            assert torch.equal(st[k], st1[k]), k
+
+
 # ------------------------------------------------ trading metrics (evaluator)
 
 def _check_metrics(obs, done, D, scales, periods, rf):
